@@ -1,0 +1,231 @@
+/*
+ * strp.h -- C ABI of libstrp.so: the per-module ADMM subproblem of STRUPRUNE on one MI355X.
+ *
+ * One transformer module is resident at a time.  For an FFN module of decoder layer l, with T
+ * calibration tokens (all matrices row-major, tokens are the contiguous axis of every activation):
+ *     X     [d x T]  input of fc1  (a^pre_{l-1})        W1hat [f x d]  pre-trained fc1
+ *     Z, Z0 [f x T]  auxiliary / dense pre-activation    W2hat [d x f]  pre-trained fc2
+ *     A     [f x T]  auxiliary post-activation (the "p" variable of the problem statement)
+ *     Y     [d x T]  dense module output (z^pre_{l+1})
+ * A structured unit j is hidden neuron j (row j of W1 and column j of W2); for attention the unit
+ * is a head, i.e. `group` consecutive channels.
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its name ends in _host.  The caller owns all
+ *     buffers, including the workspace; the library never allocates or frees device memory.
+ *   - Calls enqueue work on the stream given to strp_create and return; argument errors are
+ *     reported synchronously (nothing is enqueued), numeric failures (non-positive Cholesky
+ *     pivot, non-finite input) are recorded in a device status word read by strp_poll and by
+ *     strp_admm_step when it fills its report.
+ *   - Leading dimensions are in elements; activation leading dimensions must be multiples of 8
+ *     and base pointers 16-byte aligned.  Padding columns (index >= T) are never read as data
+ *     and never written.
+ *   - Inputs may be bf16 or fp32; auxiliaries, Gram matrices and refitted weights are fp32;
+ *     reductions that feed scores, factors and solves run in fp64.
+ */
+#ifndef STRP_H
+#define STRP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  STRP_OK = 0,
+  STRP_EINVAL = 1,     /* bad argument (null pointer, k > n, n % group != 0, ld < T, misalignment) */
+  STRP_ENOMEM = 2,     /* workspace missing or too small                                        */
+  STRP_ENOTPD = 3,     /* Cholesky met a non-positive pivot                                      */
+  STRP_ENONFINITE = 4, /* NaN/Inf met in a reduction                                              */
+  STRP_EHIP = 5,       /* a HIP runtime call failed                                               */
+  STRP_ESTATE = 6      /* call sequence error (e.g. admm_step before module_init)                 */
+} strp_status;
+
+typedef enum { STRP_BF16 = 0, STRP_F32 = 1 } strp_dtype;
+typedef enum { STRP_SCORE_WANDA = 0, STRP_SCORE_LEMMA = 1, STRP_SCORE_GAIN = 2 } strp_score_mode;
+typedef enum { STRP_SIDE_FC1 = 0, STRP_SIDE_FC2 = 1 } strp_side;
+/* How fp32 operands enter the bf16 matrix cores: rounded once (FAST) or as a two-term
+ * bf16 split hi+lo with the three leading cross products (SPLIT, ~2^-16 relative). */
+typedef enum { STRP_PREC_FAST = 0, STRP_PREC_SPLIT = 1 } strp_precision;
+
+typedef struct strp_ctx strp_ctx;
+
+/* Context: host object holding the device id, the caller's stream and the workspace. */
+strp_status strp_create(strp_ctx** out, int device, void* hip_stream);
+strp_status strp_destroy(strp_ctx* ctx);
+const char* strp_last_error(const strp_ctx* ctx);
+strp_status strp_set_precision(strp_ctx* ctx, strp_precision prec);
+/* Caller-owned scratch used by every entry point below (256-byte aligned). */
+strp_status strp_set_workspace(strp_ctx* ctx, void* dev_ptr, size_t bytes);
+/* Synchronise the stream and return the device status word (STRP_OK, STRP_ENOTPD, ...). */
+strp_status strp_poll(strp_ctx* ctx);
+
+/* ---- module description shared by the stateful entry points ------------------------- */
+typedef struct {
+  int32_t d, f;        /* widths                                                            */
+  int64_t T;           /* calibration tokens                                                */
+  int64_t ldx;         /* leading dimension of X                                            */
+  int64_t lda;         /* leading dimension of Z, A, Z0, Y (fp32)                           */
+  int32_t x_dtype;     /* strp_dtype of X                                                   */
+  int32_t w_dtype;     /* strp_dtype of W1hat, W2hat                                        */
+  int32_t k_max;       /* largest number of kept units any call will use (0: f)            */
+} strp_module_desc;
+
+/* Bytes of workspace sufficient for every entry point on this module (pure function). */
+size_t strp_workspace_bytes(const strp_module_desc* desc);
+
+/*
+ * strp_gram -- calibration Gram matrix over the tokens (the X X^T / a a^T that W = z a^+ needs;
+ * Appendix A.1 "Reversely recovering the weight matrix", Alg. 4 first step).
+ *   G[i, j] (+)= sum_{t<T} A[r_i, t] * A[r_j, t],   r_i = idx ? idx[i] : i,   i, j < s.
+ * A: [C x ldA] of dtype dt (row-major).  idx: s ascending row indices (device) or NULL (s == C).
+ * G: [s x ldG] fp32, full symmetric matrix written.  diag (optional): [s] fp64 diagonal of G.
+ * accumulate != 0 adds to the existing G (token-chunk accumulation).
+ * Errors: STRP_EINVAL (null A/G, s <= 0, s > C, ldA < T, ldG < s, misaligned), STRP_ENOMEM.
+ */
+strp_status strp_gram(strp_ctx* ctx, const void* A, strp_dtype dt, int32_t C, int64_t T, int64_t ldA,
+                      const int32_t* idx, int32_t s, float* G, int32_t ldG, double* diag, int accumulate);
+
+/*
+ * strp_score_alloc -- structural unit scores of one module and (optionally) the softmax sparsity
+ * allocation over all modules (Lemma 1 and eq. (wanda) for the scores; Lemma 2 and Alg. 1
+ * steps 1-2 for the allocation).
+ *
+ * Part 1 (always): per channel j < n_channels the token sums
+ *     g = sum A^2, e = sum A*relu(Z0), u = sum Z0*Z, v = sum Z0^2   (e, u, v only for LEMMA/GAIN)
+ * and n2_j = sum_i What[i, j]^2 give P = u + n2*e, Q = v + n2*g and
+ *     WANDA: n2*g     LEMMA: sum_group P / sum_group Q     GAIN: sum_group (2P - Q)
+ * summed over `group` consecutive channels per unit.  unit_score[n_channels/group] (fp32) and
+ * energies[layer_idx] = mean unit score (fp64) are written.
+ *
+ * Part 2 (iff r_out != NULL): for each softmax group (group_id, or one group if NULL)
+ *     w = softmax(-(I/mean|I|)/temperature), r = rbar*L_g*w, clip [0, rmax], rescale by rbar/mean(r)
+ *     if nothing sits at rmax, clip again; prune counts by largest-remainder rounding of r*n_units
+ *     (total = round(sum r*n), each layer keeps >= 1 unit).
+ * r_out[L] fp64 = pruned fractions, nprune_out[L] int32.
+ */
+typedef struct {
+  const void* A;       /* [n_channels x ld] post-activation auxiliary (or head outputs)      */
+  int32_t a_dtype;     /* strp_dtype of A                                                    */
+  const float* Z;      /* [n_channels x ld] or NULL (WANDA)                                  */
+  const float* Z0;     /* [n_channels x ld] or NULL (WANDA)                                  */
+  int64_t ld;
+  int64_t T;
+  int32_t n_channels;
+  int32_t group;       /* channels per unit (1: neurons, d_head: heads)                      */
+  int32_t mode;        /* strp_score_mode                                                    */
+  const double* n2;    /* [n_channels] squared column norms of What, or NULL to compute them */
+  const void* What;    /* [w_rows x ldw] next linear layer (used iff n2 == NULL)             */
+  int32_t w_dtype;
+  int32_t w_rows;
+  int64_t ldw;
+} strp_score_in;
+
+strp_status strp_score_alloc(strp_ctx* ctx, const strp_score_in* in, float* unit_score, double* energies,
+                             int32_t layer_idx, int32_t L, const int32_t* n_units, const int32_t* group_id,
+                             double rbar, double temperature, double rmax, double* r_out,
+                             int32_t* nprune_out);
+
+/*
+ * strp_mask_topk -- structured mask by score threshold (rule below Lemma 1; Alg. 4 threshold step).
+ * Keeps exactly the k highest of the n unit scores; equal scores keep the lower index.
+ *   mask[n] uint8 in {0,1};  idx[k*group] int32 ascending kept CHANNEL indices (unit*group + c);
+ *   tau (optional) = lowest kept score.
+ * Errors: STRP_EINVAL (k < 0, k > n, n <= 0, group <= 0, null pointers).
+ */
+strp_status strp_mask_topk(strp_ctx* ctx, const float* score, int32_t n, int32_t k, int32_t group,
+                           uint8_t* mask, int32_t* idx, float* tau);
+
+/*
+ * strp_refit -- closed-form ridge least-squares recovery of the surviving weights
+ * (W = z a^+ restricted to the kept support; Appendix A.1, Alg. 3 prune+recover lines).
+ *   R = Lhs_rows * Rhs_rows^T over the T tokens,  Wsub = R (Gram + lambda I)^-1.
+ * side == STRP_SIDE_FC2:  Lhs [out x ld_lhs] (all rows), Rhs rows idx[0..s) of an [in x ld_rhs]
+ *   matrix, Gram [s x s] = their Gram;  W[:, idx] = Wsub, every other column of W zero.
+ * side == STRP_SIDE_FC1:  Lhs rows idx[0..s) of an [out x ld_lhs] matrix, Rhs [in x ld_rhs] (all
+ *   rows), Gram [in x in];  W[idx, :] = Wsub, every other row of W zero.
+ * Gram: fp32 symmetric, unregularised, leading dimension ldg.  W: [out x in] fp32, dense row-major.
+ * chol (optional, fp64 [n x n], n = order of Gram): if chol_valid != 0 it holds the lower
+ * Cholesky factor of Gram + lambda I from an earlier call and Gram is not read; otherwise the
+ * factor is computed and, if chol != NULL, stored there for reuse.
+ * Numeric failure (pivot <= 0) sets STRP_ENOTPD in the status word.
+ */
+strp_status strp_refit(strp_ctx* ctx, strp_side side, const float* Gram, int32_t ldg, double lambda,
+                       double* chol, int chol_valid, const void* Lhs, strp_dtype lhs_dtype, int64_t ld_lhs,
+                       const void* Rhs, strp_dtype rhs_dtype, int64_t ld_rhs, int64_t T, const int32_t* idx,
+                       int32_t s, float* W, int32_t out, int32_t in);
+
+/* ---- stateful per-module path ---------------------------------------------------------- */
+typedef struct {
+  const void* X;       /* [d x ldx]   x_dtype                                               */
+  const void* W1hat;   /* [f x d]     w_dtype                                               */
+  const void* W2hat;   /* [d x f]     w_dtype                                               */
+  float* Z;            /* [f x lda]   auxiliary pre-activation                              */
+  float* A;            /* [f x lda]   auxiliary post-activation                             */
+  float* Z0;           /* [f x lda]   dense pre-activation (fixed)                          */
+  float* Y;            /* [d x lda]   dense module output (fixed)                           */
+  float* W1;           /* [f x d]     refitted fc1 (rows of pruned units zero)              */
+  float* W2;           /* [d x f]     refitted fc2 (columns of pruned units zero)           */
+  float* H;            /* [d x d]     X X^T                                                 */
+  double* cholH;       /* [d x d]     lower Cholesky factor of H + lam1 I                   */
+  double* n2;          /* [f]         squared column norms of W2hat                         */
+  float* score;        /* [f]         unit scores of the last selection                     */
+  uint8_t* mask;       /* [f]         1 = kept                                              */
+  int32_t* idx;        /* [f]         kept indices ascending (first s valid)                */
+  double* scalars;     /* [32]        device scalars: lam1, lam2, objective sums, tau       */
+  int32_t s;           /* kept units of the current mask (host field, set by the library)   */
+  int32_t iter;        /* inner iterations done (host field)                                */
+} strp_module_state;
+
+typedef struct {
+  double alpha, beta;  /* weights of the objective                                          */
+  double delta;        /* ridge damping: lam = delta * mean(diag Gram), fixed at init        */
+  int32_t mode;        /* strp_score_mode used when selecting                               */
+  int32_t reselect;    /* 0: select only when no mask exists yet; 1: every iteration        */
+  int32_t k;           /* units to keep                                                     */
+  int32_t stages;      /* bit mask of STRP_STAGE_*; 0 means all                              */
+} strp_params;
+
+enum {
+  STRP_STAGE_SELECT = 1, /* scores + top-k                                                  */
+  STRP_STAGE_REFIT2 = 2, /* Gram of kept A rows, fc2 refit                                  */
+  STRP_STAGE_REFIT1 = 4, /* fc1 refit with the cached factor of H                           */
+  STRP_STAGE_AUPD = 8,   /* a-update                                                        */
+  STRP_STAGE_ZUPD = 16,  /* z-update                                                        */
+  STRP_STAGE_OBJ = 32    /* objective                                                       */
+};
+
+typedef struct {
+  double terms[5];     /* (1/T)[a|Y-W2A|^2, b|A-relu Z|^2, a|Z-W1X|^2, a lam2|W2|^2, a lam1|W1|^2] */
+  double J;            /* first three terms                                                 */
+  double J_ridge;      /* all five                                                          */
+  double lam1, lam2;
+  float tau;           /* lowest kept score of the last selection                           */
+  int32_t s;
+  int32_t status;      /* strp_status from the device status word                           */
+} strp_report;
+
+/*
+ * strp_module_init -- Alg. 3 initialisation: Z0 = W1hat X, Z = Z0, A = relu(Z0), Y = W2hat A,
+ * H = X X^T, lam1 = delta tr(H)/d, lam2 = delta |A|_F^2 / f, factor of H + lam1 I (the cached
+ * pseudo-inverse of the listing), n2 = column norms of W2hat, W1 = W2 = 0, no mask.
+ */
+strp_status strp_module_init(strp_ctx* ctx, const strp_module_desc* desc, strp_module_state* st,
+                             const strp_params* params);
+
+/*
+ * strp_admm_step -- one inner iteration of Alg. 3 (FFN function) / Alg. 4 step body on the resident
+ * module: score + top-k (if due), fc2 refit, fc1 refit, a-update
+ *     A = (alpha W2^T W2 + beta I)^-1 (alpha W2^T Y + beta relu(Z)),
+ * z-update (exact per-element minimiser of beta(a - relu z)^2 + alpha(z - W1 x)^2) and the
+ * objective.  report_host (optional) is filled after synchronising the stream.
+ */
+strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_module_state* st,
+                           const strp_params* params, strp_report* report_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STRP_H */

@@ -1,0 +1,714 @@
+// C ABI of libstrp.so: argument validation, workspace carving and the per-module ADMM drivers.
+#include <stdarg.h>
+
+#include <cmath>
+#include <new>
+
+#include "strp_internal.h"
+
+namespace strp {
+
+strp_status fail(strp_ctx* ctx, strp_status st, const char* fmt, ...) {
+  if (ctx) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+    va_end(ap);
+  }
+  return st;
+}
+
+static inline long long round_up(long long x, long long a) { return (x + a - 1) / a * a; }
+static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+static int kind_of(int dtype, int other_dtype, int prec) {
+  if (dtype == STRP_BF16) return other_dtype == STRP_BF16 ? OP_BF16 : OP_BF16_H;
+  return prec == STRP_PREC_SPLIT ? OP_F32_2 : OP_F32_1;
+}
+
+// number of K splits of a token-contraction product: enough blocks to fill the chip and fp32
+// accumulation chains of at most 8192 tokens (partials are then summed in fp64)
+static int plan_splits(int ntiles, long long K) {
+  long long s_chain = (K + 8191) / 8192;
+  long long s_fill = (1024 + ntiles - 1) / ntiles;
+  long long s = s_chain > s_fill ? s_chain : s_fill;
+  long long s_max = K / 256 > 1 ? K / 256 : 1;
+  if (s > s_max) s = s_max;
+  return (int)s;
+}
+
+static size_t nt_partial_elems(int M, int N, long long K, int triangle) {
+  GemmP p;
+  memset(&p, 0, sizeof(p));
+  p.M = M; p.N = N; p.K = K; p.triangle = triangle;
+  gemm_plan_tiles(p, false, 1);
+  gemm_plan_tiles(p, false, plan_splits(p.ntiles, K));
+  return (size_t)p.splits * (size_t)M * (size_t)N;
+}
+
+// C = P Q^T over K (both operands K-contiguous); partials in the arena, fp64 reduction.
+static strp_status nt_product(strp_ctx* ctx, Arena arena, const Operand& P, int kp, const Operand& Q, int kq, int M, int N,
+                              long long K, int triangle, float* outf, long long ldof, double* outd, long long ldod,
+                              double* diag, int accumulate) {
+  GemmP p;
+  memset(&p, 0, sizeof(p));
+  p.P = P; p.Q = Q; p.M = M; p.N = N; p.K = K; p.triangle = triangle;
+  p.epi = EPI_PARTIAL;
+  gemm_plan_tiles(p, false, 1);
+  gemm_plan_tiles(p, false, plan_splits(p.ntiles, K));
+  STRP_TAKE(ctx, arena, part, float, (size_t)p.splits * M * N);
+  p.out = part;
+  STRP_TRY(launch_gemm(ctx, p, kp, kq, false));
+  return launch_splitk_reduce(ctx, part, p.splits, M, N, triangle, outf, ldof, outd, ldod, diag, accumulate);
+}
+
+// ---- small kernels ------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void add_diag_kernel(double* A, long long ld, int n, double lam, const double* lam_dev) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) A[(long long)i * ld + i] += lam_dev ? *lam_dev : lam;
+}
+
+// out[0] = scale * sum(v[0..n)) (single block, fixed order)
+__global__ __launch_bounds__(256) void vec_sum_kernel(const double* v, int n, double scale, double* out, double* raw) {
+  __shared__ double s[256];
+  double a = 0.0;
+  for (int i = threadIdx.x; i < n; i += 256) a += v[i];
+  s[threadIdx.x] = a;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) s[threadIdx.x] += s[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    if (raw) *raw = s[0];
+    *out = s[0] * scale;
+  }
+}
+
+// dst[r][c] (fp32, ld ldd, zero padded) = W[r][idx[c]]  (kept columns of fc2)
+__global__ __launch_bounds__(256) void gather_cols_kernel(const float* W, int rows, int in, const int32_t* idx, int s, float* dst,
+                                                          long long ldd) {
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (long long)rows * ldd) return;
+  const int r = (int)(e / ldd), c = (int)(e % ldd);
+  dst[e] = c < s ? W[(long long)r * in + idx[c]] : 0.0f;
+}
+// dst[r][c] = W[idx[r]][c]  (kept rows of fc1)
+__global__ __launch_bounds__(256) void gather_rows_kernel(const float* W, int in, const int32_t* idx, int s, float* dst, long long ldd) {
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (long long)s * ldd) return;
+  const int r = (int)(e / ldd), c = (int)(e % ldd);
+  dst[e] = c < in ? W[(long long)idx[r] * in + c] : 0.0f;
+}
+// dst[c][r] (fp64, ld ldd) = src[r][c] (fp32, ld lds): r < rows, c < cols
+__global__ __launch_bounds__(256) void transpose_f32_f64_kernel(const float* src, long long lds, int rows, int cols, double* dst,
+                                                                long long ldd) {
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (long long)rows * cols) return;
+  const int c = (int)(e / rows), r = (int)(e % rows);
+  dst[(long long)c * ldd + r] = (double)src[(long long)r * lds + c];
+}
+
+// Rows of pruned units (mask == 0): W2[:, j] = 0 and W1[j, :] = 0 decouple them.
+//   phase 0 (a-update): A_j = relu(Z_j)
+//   phase 1 (z-update): exact z rule with z1 = 0; accumulates (A - relu Z)^2 and (Z - 0)^2
+__global__ __launch_bounds__(256) void pruned_rows_kernel(const uint8_t* mask, float* Z, float* A, long long lda, long long T, int phase,
+                                                          float alpha, float beta, int write, double* red) {
+  const int j = blockIdx.x;
+  double r0 = 0.0, r1 = 0.0;
+  if (!mask[j]) {
+    float* z = Z + (long long)j * lda;
+    float* a = A + (long long)j * lda;
+    for (long long t = threadIdx.x; t < T; t += 256) {
+      if (phase == 0) {
+        a[t] = __builtin_fmaxf(z[t], 0.0f);
+      } else {
+        const float av = a[t];
+        float zv;
+        if (write) {
+          const float z2 = beta * av / (alpha + beta);
+          const float costm = beta * av * av;
+          const float cp = __builtin_fmaxf(z2, 0.0f);
+          const float costp = beta * (av - cp) * (av - cp) + alpha * cp * cp;
+          zv = costm < costp ? 0.0f : cp;
+          z[t] = zv;
+        } else {
+          zv = z[t];
+        }
+        const float ra = av - __builtin_fmaxf(zv, 0.0f);
+        r0 += (double)ra * (double)ra;
+        r1 += (double)zv * (double)zv;
+      }
+    }
+  }
+  if (red) {
+    __shared__ double sh[4][2];
+    for (int o = 32; o > 0; o >>= 1) {
+      r0 += __shfl_down(r0, o, 64);
+      r1 += __shfl_down(r1, o, 64);
+    }
+    if ((threadIdx.x & 63) == 0) {
+      sh[threadIdx.x >> 6][0] = r0;
+      sh[threadIdx.x >> 6][1] = r1;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      red[2 * (long long)j] = sh[0][0] + sh[1][0] + sh[2][0] + sh[3][0];
+      red[2 * (long long)j + 1] = sh[0][1] + sh[1][1] + sh[2][1] + sh[3][1];
+    }
+  }
+}
+
+// per-block sum of squares of an fp32 array -> red[block][0] (red[block][1] = 0)
+__global__ __launch_bounds__(256) void sumsq_kernel(const float* x, long long n, double* red) {
+  double a = 0.0;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) a += (double)x[i] * (double)x[i];
+  __shared__ double sh[4];
+  for (int o = 32; o > 0; o >>= 1) a += __shfl_down(a, o, 64);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = a;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    red[2 * (long long)blockIdx.x] = sh[0] + sh[1] + sh[2] + sh[3];
+    red[2 * (long long)blockIdx.x + 1] = 0.0;
+  }
+}
+
+// scalars[dst] = a * scalars[s0] + b * scalars[s1]   (one thread; keeps the objective assembly on device)
+__global__ void axpby_scalar_kernel(double* sc, int dst, double a, int s0, double b, int s1) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) sc[dst] = a * sc[s0] + (s1 >= 0 ? b * sc[s1] : 0.0);
+}
+
+// inverse of each 64x64 diagonal block of a stored lower factor (for a cached factor)
+__global__ __launch_bounds__(64) void diag_inverse_kernel(const double* L, int n, long long ld, double* invd) {
+  __shared__ double S[NB][NB + 1];
+  __shared__ double V[NB][NB + 1];
+  const int j0 = blockIdx.x * NB;
+  const int jb = (n - j0 < NB) ? (n - j0) : NB;
+  const int c = threadIdx.x;
+  for (int i = 0; i < NB; ++i) {
+    S[i][c] = (i < jb && c <= i && c < jb) ? L[(long long)(j0 + i) * ld + j0 + c] : 0.0;
+    V[i][c] = 0.0;
+  }
+  __syncthreads();
+  if (c < jb) {
+    for (int i = c; i < jb; ++i) {
+      double acc = (i == c) ? 1.0 : 0.0;
+      for (int k = c; k < i; ++k) acc -= S[i][k] * V[k][c];
+      V[i][c] = acc / S[i][i];
+    }
+  }
+  __syncthreads();
+  double* out = invd + (long long)blockIdx.x * NB * NB;
+  for (int i = 0; i < NB; ++i) out[i * NB + c] = V[i][c];
+}
+
+static strp_status diag_inverses(strp_ctx* ctx, const double* L, int n, long long ld, double* invd) {
+  hipLaunchKernelGGL(diag_inverse_kernel, dim3((n + NB - 1) / NB), dim3(64), 0, ctx->stream, L, n, ld, invd);
+  STRP_HIP(ctx, hipGetLastError());
+  return STRP_OK;
+}
+
+static unsigned blocks_for(long long n) { return (unsigned)((n + 255) / 256); }
+
+// scalar slots of strp_module_state::scalars
+enum { SC_LAM1 = 0, SC_LAM2 = 1, SC_SUMA0 = 2, SC_TRH = 3, SC_T1 = 4, SC_T2 = 5, SC_T3 = 6, SC_T4 = 7, SC_T5 = 8,
+       SC_TAU = 9, SC_ENERGY = 10, SC_TMP0 = 11, SC_TMP1 = 12, SC_TMP2 = 13, SC_TMP3 = 14, SC_W2SQ = 15, SC_W1SQ = 16, SC_COUNT = 32 };
+
+static strp_status check_desc(strp_ctx* ctx, const strp_module_desc* d) {
+  if (!d) return fail(ctx, STRP_EINVAL, "null module descriptor");
+  if (d->d <= 0 || d->f <= 0 || d->T <= 0) return fail(ctx, STRP_EINVAL, "module: d, f, T must be positive");
+  if (d->ldx < d->T || d->lda < d->T) return fail(ctx, STRP_EINVAL, "module: leading dimension below T");
+  if (d->ldx % 8 || d->lda % 8 || d->d % 8 || d->f % 8) return fail(ctx, STRP_EINVAL, "module: d, f and leading dimensions must be multiples of 8");
+  if ((d->x_dtype != STRP_BF16 && d->x_dtype != STRP_F32) || (d->w_dtype != STRP_BF16 && d->w_dtype != STRP_F32))
+    return fail(ctx, STRP_EINVAL, "module: unknown dtype");
+  if (d->k_max < 0 || d->k_max > d->f) return fail(ctx, STRP_EINVAL, "module: k_max outside [0, f]");
+  return STRP_OK;
+}
+
+}  // namespace strp
+
+using namespace strp;
+
+extern "C" {
+
+strp_status strp_create(strp_ctx** out, int device, void* hip_stream) {
+  if (!out) return STRP_EINVAL;
+  *out = nullptr;
+  int count = 0;
+  if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return STRP_EHIP;
+  if (hipSetDevice(device) != hipSuccess) return STRP_EHIP;
+  strp_ctx* c = new (std::nothrow) strp_ctx();
+  if (!c) return STRP_ENOMEM;
+  memset(c, 0, sizeof(*c));
+  c->device = device;
+  c->stream = (hipStream_t)hip_stream;
+  c->precision = STRP_PREC_SPLIT;
+  if (hipHostMalloc(&c->pinned, 4096, hipHostMallocDefault) != hipSuccess) {
+    delete c;
+    return STRP_EHIP;
+  }
+  *out = c;
+  return STRP_OK;
+}
+
+strp_status strp_destroy(strp_ctx* ctx) {
+  if (!ctx) return STRP_EINVAL;
+  if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+  delete ctx;
+  return STRP_OK;
+}
+
+const char* strp_last_error(const strp_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+
+strp_status strp_set_precision(strp_ctx* ctx, strp_precision prec) {
+  if (!ctx) return STRP_EINVAL;
+  if (prec != STRP_PREC_FAST && prec != STRP_PREC_SPLIT) return fail(ctx, STRP_EINVAL, "unknown precision %d", (int)prec);
+  ctx->precision = prec;
+  return STRP_OK;
+}
+
+strp_status strp_set_workspace(strp_ctx* ctx, void* dev_ptr, size_t bytes) {
+  if (!ctx) return STRP_EINVAL;
+  if (!dev_ptr || bytes < 4096) return fail(ctx, STRP_EINVAL, "workspace: null or smaller than 4096 bytes");
+  if ((uintptr_t)dev_ptr & 255u) return fail(ctx, STRP_EINVAL, "workspace: pointer not 256-byte aligned");
+  ctx->ws = (char*)dev_ptr;
+  ctx->ws_bytes = bytes;
+  ctx->status_dev = (int32_t*)dev_ptr;
+  return fill_zero(ctx, dev_ptr, 256);
+}
+
+strp_status strp_poll(strp_ctx* ctx) {
+  if (!ctx) return STRP_EINVAL;
+  if (!ctx->ws) return fail(ctx, STRP_ENOMEM, "no workspace set");
+  STRP_HIP(ctx, hipMemcpyAsync(ctx->pinned, ctx->status_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+  STRP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  const int32_t st = *(int32_t*)ctx->pinned;
+  if (st != 0) {
+    fail(ctx, (strp_status)st, "device status word = %d", st);
+    STRP_TRY(fill_zero(ctx, ctx->status_dev, 256));
+  }
+  return (strp_status)st;
+}
+
+size_t strp_workspace_bytes(const strp_module_desc* desc) {
+  if (!desc || desc->d <= 0 || desc->f <= 0 || desc->T <= 0) return 0;
+  const size_t d = desc->d, f = desc->f;
+  const size_t km = desc->k_max > 0 ? (size_t)desc->k_max : f;
+  const size_t kp = (size_t)round_up((long long)km, 8);
+  const long long T = desc->T;
+  size_t part = 0;
+  auto upd = [&](size_t e) { if (e > part) part = e; };
+  upd(nt_partial_elems((int)km, (int)km, T, 1));
+  upd(nt_partial_elems((int)d, (int)km, T, 0));
+  upd(nt_partial_elems((int)km, (int)d, T, 0));
+  upd(nt_partial_elems((int)d, (int)d, T, 1));
+  upd(nt_partial_elems((int)d, (int)d, (long long)kp, 1));
+  const size_t nmax = km > d ? km : d;
+  size_t tot = 256;
+  auto add = [&](size_t bytes) { tot += (bytes + 255) & ~size_t(255); };
+  add(part * 4);                                   // split-K partials
+  add(nmax * nmax * 8);                            // fp64 system matrix / factor
+  add(((nmax + NB - 1) / NB) * NB * NB * 8);       // diagonal block inverses
+  add(((d + NB - 1) / NB) * NB * NB * 8);          // same for the cached factor of H
+  add(d * km * 8);                                 // fp64 right-hand side / solution
+  add(d * d * 8);                                  // fp64 M = (beta/alpha) I + W W^T
+  add(d * kp * 4);                                 // compact fc2  [d x kp]
+  add(km * d * 4);                                 // compact fc1  [k x d]
+  add(km * d * 4);                                 // B = W^T M^-1 [k x d]
+  add(d * (size_t)desc->lda * 4);                  // E = Y - W2 relu(Z_S)
+  add(4 * f * 8);                                  // token sums
+  size_t tilesT = (size_t)((T + 127) / 128);
+  size_t nn_blocks = ((f + 127) / 128) * tilesT;
+  add((nn_blocks > f ? nn_blocks : f) * 16 + 4096); // per-block partial sums
+  return tot + 4096;
+}
+
+strp_status strp_gram(strp_ctx* ctx, const void* A, strp_dtype dt, int32_t C, int64_t T, int64_t ldA, const int32_t* idx,
+                      int32_t s, float* G, int32_t ldG, double* diag, int accumulate) {
+  if (!ctx) return STRP_EINVAL;
+  if (!A || !G) return fail(ctx, STRP_EINVAL, "gram: null A or G");
+  if (dt != STRP_BF16 && dt != STRP_F32) return fail(ctx, STRP_EINVAL, "gram: unknown dtype");
+  if (C <= 0 || s <= 0 || s > C || T <= 0) return fail(ctx, STRP_EINVAL, "gram: need 0 < s <= C and T > 0");
+  if (!idx && s != C) return fail(ctx, STRP_EINVAL, "gram: idx == NULL requires s == C");
+  if (ldA < T || ldA % 8 || ldG < s) return fail(ctx, STRP_EINVAL, "gram: bad leading dimension");
+  if (!aligned16(A)) return fail(ctx, STRP_EINVAL, "gram: A not 16-byte aligned");
+  if (!ctx->ws) return fail(ctx, STRP_ENOMEM, "gram: no workspace set");
+  Arena arena(ctx);
+  Operand op = {A, (long long)ldA, idx, s, 0};
+  const int kind = kind_of(dt, dt, ctx->precision);
+  return nt_product(ctx, arena, op, kind, op, kind, s, s, T, 1, G, ldG, nullptr, 0, diag, accumulate);
+}
+
+strp_status strp_score_alloc(strp_ctx* ctx, const strp_score_in* in, float* unit_score, double* energies, int32_t layer_idx,
+                             int32_t L, const int32_t* n_units, const int32_t* group_id, double rbar, double temperature,
+                             double rmax, double* r_out, int32_t* nprune_out) {
+  if (!ctx) return STRP_EINVAL;
+  if (!in || !unit_score || !energies) return fail(ctx, STRP_EINVAL, "score_alloc: null argument");
+  if (!in->A || in->n_channels <= 0 || in->group <= 0 || in->T <= 0) return fail(ctx, STRP_EINVAL, "score_alloc: bad input block");
+  if (in->n_channels % in->group) return fail(ctx, STRP_EINVAL, "score_alloc: n_channels %% group != 0");
+  if (in->ld < in->T || in->ld % 8 || !aligned16(in->A)) return fail(ctx, STRP_EINVAL, "score_alloc: bad leading dimension or alignment");
+  if (in->mode < STRP_SCORE_WANDA || in->mode > STRP_SCORE_GAIN) return fail(ctx, STRP_EINVAL, "score_alloc: unknown mode");
+  if (in->mode != STRP_SCORE_WANDA && (!in->Z || !in->Z0)) return fail(ctx, STRP_EINVAL, "score_alloc: LEMMA/GAIN need Z and Z0");
+  if (!in->n2 && !in->What) return fail(ctx, STRP_EINVAL, "score_alloc: need n2 or What");
+  if (L <= 0 || layer_idx < 0 || layer_idx >= L) return fail(ctx, STRP_EINVAL, "score_alloc: layer_idx outside [0, L)");
+  if (r_out && (!nprune_out || !n_units)) return fail(ctx, STRP_EINVAL, "score_alloc: allocation needs n_units and nprune_out");
+  if (r_out && (!(temperature > 0.0) || !(rbar >= 0.0) || !(rmax > 0.0))) return fail(ctx, STRP_EINVAL, "score_alloc: bad rbar/temperature/rmax");
+  if (!ctx->ws) return fail(ctx, STRP_ENOMEM, "score_alloc: no workspace set");
+  Arena arena(ctx);
+  STRP_TAKE(ctx, arena, sums, double, 4 * (size_t)in->n_channels);
+  const double* n2 = in->n2;
+  if (!n2) {
+    STRP_TAKE(ctx, arena, n2buf, double, (size_t)in->n_channels);
+    STRP_TRY(launch_colnorm2(ctx, in->What, in->w_dtype, in->w_rows, in->n_channels, in->ldw, n2buf));
+    n2 = n2buf;
+  }
+  STRP_TRY(launch_row_sums(ctx, in->A, in->a_dtype, in->Z, in->Z0, in->ld, in->T, in->n_channels, in->mode, sums));
+  STRP_TRY(launch_unit_scores(ctx, sums, n2, in->n_channels, in->group, in->mode, unit_score, energies + layer_idx));
+  if (r_out) STRP_TRY(launch_alloc(ctx, energies, L, n_units, group_id, rbar, temperature, rmax, r_out, nprune_out));
+  return STRP_OK;
+}
+
+strp_status strp_mask_topk(strp_ctx* ctx, const float* score, int32_t n, int32_t k, int32_t group, uint8_t* mask, int32_t* idx,
+                           float* tau) {
+  if (!ctx) return STRP_EINVAL;
+  if (!score || !mask || !idx) return fail(ctx, STRP_EINVAL, "mask_topk: null argument");
+  if (n <= 0 || k < 0 || k > n || group <= 0) return fail(ctx, STRP_EINVAL, "mask_topk: need n > 0, 0 <= k <= n, group > 0");
+  return launch_topk(ctx, score, n, k, group, mask, idx, tau, nullptr, 0);
+}
+
+}  // extern "C"
+
+namespace strp {
+
+// Solve Wsub (Gram + lam I) = R with R = Lhs Rhs^T over the tokens.  Returns the fp64 solution
+// [m x n] (leading dimension n) in *sol_out; it lives in the arena passed by reference.
+struct RefitIn {
+  int side;
+  const float* Gram; long long ldg;       // fp32 Gram (used when Ld_ready == 0 and Gd == nullptr)
+  double* Ld; int Ld_ready;               // [n x n] fp64: holds Gram + lam I (Ld_ready == 1), the factor (2), or scratch (0)
+  double lam; const double* lam_dev;
+  Operand Lhs; int lhs_kind; Operand Rhs; int rhs_kind;
+  int m, n; long long T;
+};
+
+static strp_status ridge_solve(strp_ctx* ctx, Arena& arena, const RefitIn& in, double** sol_out) {
+  const int n = in.n, m = in.m;
+  const int nblk = (n + NB - 1) / NB;
+  STRP_TAKE(ctx, arena, invd, double, (size_t)nblk * NB * NB);
+  if (in.Ld_ready == 2) {
+    STRP_TRY(diag_inverses(ctx, in.Ld, n, n, invd));
+  } else {
+    if (in.Ld_ready == 0) STRP_TRY(f32_to_f64_ridge(ctx, in.Gram, in.ldg, in.Ld, n, n, in.lam, in.lam_dev));
+    STRP_TRY(chol_factor(ctx, in.Ld, n, n, invd, ctx->status_dev));
+  }
+  STRP_TAKE(ctx, arena, R, double, (size_t)m * n);
+  STRP_TRY(nt_product(ctx, arena, in.Lhs, in.lhs_kind, in.Rhs, in.rhs_kind, m, n, in.T, 0, nullptr, 0, R, n, nullptr, 0));
+  STRP_TRY(chol_solve_right(ctx, in.Ld, n, n, invd, R, m, n));
+  *sol_out = R;
+  return STRP_OK;
+}
+
+static int nn_kind(int dtype, int other, int prec) { return kind_of(dtype, other, prec); }
+
+}  // namespace strp
+
+extern "C" {
+
+strp_status strp_refit(strp_ctx* ctx, strp_side side, const float* Gram, int32_t ldg, double lambda, double* chol, int chol_valid,
+                       const void* Lhs, strp_dtype lhs_dtype, int64_t ld_lhs, const void* Rhs, strp_dtype rhs_dtype,
+                       int64_t ld_rhs, int64_t T, const int32_t* idx, int32_t s, float* W, int32_t out, int32_t in) {
+  if (!ctx) return STRP_EINVAL;
+  if (side != STRP_SIDE_FC1 && side != STRP_SIDE_FC2) return fail(ctx, STRP_EINVAL, "refit: unknown side");
+  if (!Lhs || !Rhs || !W || !idx) return fail(ctx, STRP_EINVAL, "refit: null argument");
+  if (out <= 0 || in <= 0 || T <= 0 || s <= 0) return fail(ctx, STRP_EINVAL, "refit: non-positive size");
+  if (side == STRP_SIDE_FC2 && s > in) return fail(ctx, STRP_EINVAL, "refit: s > in");
+  if (side == STRP_SIDE_FC1 && s > out) return fail(ctx, STRP_EINVAL, "refit: s > out");
+  if (ld_lhs < T || ld_rhs < T || ld_lhs % 8 || ld_rhs % 8) return fail(ctx, STRP_EINVAL, "refit: bad leading dimension");
+  if (!aligned16(Lhs) || !aligned16(Rhs)) return fail(ctx, STRP_EINVAL, "refit: operands not 16-byte aligned");
+  if (chol_valid && !chol) return fail(ctx, STRP_EINVAL, "refit: chol_valid without chol");
+  if (!chol_valid && !Gram) return fail(ctx, STRP_EINVAL, "refit: need Gram or a valid factor");
+  const int n = side == STRP_SIDE_FC2 ? s : in;
+  const int m = side == STRP_SIDE_FC2 ? out : s;
+  if (!chol_valid && ldg < n) return fail(ctx, STRP_EINVAL, "refit: ldg below the order of Gram");
+  if (!(lambda >= 0.0)) return fail(ctx, STRP_EINVAL, "refit: negative lambda");
+  if (!ctx->ws) return fail(ctx, STRP_ENOMEM, "refit: no workspace set");
+  Arena arena(ctx);
+  RefitIn ri;
+  memset(&ri, 0, sizeof(ri));
+  ri.side = side; ri.Gram = Gram; ri.ldg = ldg; ri.lam = lambda; ri.lam_dev = nullptr;
+  if (chol) {
+    ri.Ld = chol;
+  } else {
+    STRP_TAKE(ctx, arena, Ld, double, (size_t)n * n);
+    ri.Ld = Ld;
+  }
+  ri.Ld_ready = chol_valid ? 2 : 0;
+  const int lk = kind_of(lhs_dtype, rhs_dtype, ctx->precision), rk = kind_of(rhs_dtype, lhs_dtype, ctx->precision);
+  if (side == STRP_SIDE_FC2) {
+    ri.Lhs = Operand{Lhs, (long long)ld_lhs, nullptr, out, 0};
+    ri.Rhs = Operand{Rhs, (long long)ld_rhs, idx, s, 0};
+  } else {
+    ri.Lhs = Operand{Lhs, (long long)ld_lhs, idx, s, 0};
+    ri.Rhs = Operand{Rhs, (long long)ld_rhs, nullptr, in, 0};
+  }
+  ri.lhs_kind = lk; ri.rhs_kind = rk; ri.m = m; ri.n = n; ri.T = T;
+  double* sol = nullptr;
+  STRP_TRY(ridge_solve(ctx, arena, ri, &sol));
+  return scatter_weights(ctx, sol, n, side, idx, s, W, out, in);
+}
+
+strp_status strp_module_init(strp_ctx* ctx, const strp_module_desc* desc, strp_module_state* st, const strp_params* params) {
+  if (!ctx) return STRP_EINVAL;
+  STRP_TRY(check_desc(ctx, desc));
+  if (!st || !params) return fail(ctx, STRP_EINVAL, "module_init: null state or params");
+  if (!st->X || !st->W1hat || !st->W2hat || !st->Z || !st->A || !st->Z0 || !st->Y || !st->W1 || !st->W2 || !st->H || !st->cholH ||
+      !st->n2 || !st->score || !st->mask || !st->idx || !st->scalars)
+    return fail(ctx, STRP_EINVAL, "module_init: null buffer in state");
+  if (!aligned16(st->X) || !aligned16(st->W1hat) || !aligned16(st->W2hat) || !aligned16(st->Z) || !aligned16(st->A) ||
+      !aligned16(st->Z0) || !aligned16(st->Y))
+    return fail(ctx, STRP_EINVAL, "module_init: buffers must be 16-byte aligned");
+  if (!(params->delta >= 0.0)) return fail(ctx, STRP_EINVAL, "module_init: negative delta");
+  if (!ctx->ws) return fail(ctx, STRP_ENOMEM, "module_init: no workspace set");
+  const int d = desc->d, f = desc->f;
+  const long long T = desc->T;
+  const int prec = ctx->precision;
+  Arena arena(ctx);
+  double* sc = st->scalars;
+  STRP_TRY(fill_zero(ctx, sc, SC_COUNT * sizeof(double)));
+  STRP_TRY(launch_colnorm2(ctx, st->W2hat, desc->w_dtype, d, f, f, st->n2));
+
+  // Z0 = W1hat X, Z = Z0, A = relu(Z0), sum A^2
+  {
+    GemmP p;
+    memset(&p, 0, sizeof(p));
+    p.P = Operand{st->W1hat, (long long)d, nullptr, f, 0};
+    p.Q = Operand{st->X, (long long)desc->ldx, nullptr, d, 0};
+    p.M = f; p.N = (int)T; p.K = d;
+    p.epi = EPI_INITZ; p.Zs = st->Z; p.As = st->A; p.Z0s = st->Z0; p.lda = desc->lda;
+    gemm_plan_tiles(p, true, 1);
+    Arena a2 = arena;
+    STRP_TAKE(ctx, a2, red, double, 2 * (size_t)gemm_grid_blocks(p));
+    p.red = red;
+    STRP_TRY(launch_gemm(ctx, p, nn_kind(desc->w_dtype, desc->x_dtype, prec), nn_kind(desc->x_dtype, desc->w_dtype, prec), true));
+    STRP_TRY(launch_block_sum(ctx, red, gemm_grid_blocks(p), sc + SC_SUMA0, nullptr, 1.0, 1.0));
+    hipLaunchKernelGGL(axpby_scalar_kernel, dim3(1), dim3(1), 0, ctx->stream, sc, (int)SC_LAM2, params->delta / (double)f, (int)SC_SUMA0, 0.0, -1);
+  }
+  // Y = W2hat A
+  {
+    GemmP p;
+    memset(&p, 0, sizeof(p));
+    p.P = Operand{st->W2hat, (long long)f, nullptr, d, 0};
+    p.Q = Operand{st->A, (long long)desc->lda, nullptr, f, 0};
+    p.M = d; p.N = (int)T; p.K = f;
+    p.epi = EPI_STORE; p.out = st->Y; p.ldo = desc->lda;
+    gemm_plan_tiles(p, true, 1);
+    STRP_TRY(launch_gemm(ctx, p, nn_kind(desc->w_dtype, STRP_F32, prec), nn_kind(STRP_F32, desc->w_dtype, prec), true));
+  }
+  // H = X X^T (fp32 copy and fp64 system), lam1 = delta tr(H)/d, factor of H + lam1 I
+  {
+    Arena a2 = arena;
+    STRP_TAKE(ctx, a2, diag, double, (size_t)d);
+    Operand xo = {st->X, (long long)desc->ldx, nullptr, d, 0};
+    const int kx = kind_of(desc->x_dtype, desc->x_dtype, prec);
+    STRP_TRY(nt_product(ctx, a2, xo, kx, xo, kx, d, d, T, 1, st->H, d, st->cholH, d, diag, 0));
+    hipLaunchKernelGGL(vec_sum_kernel, dim3(1), dim3(256), 0, ctx->stream, diag, d, params->delta / (double)d, sc + SC_LAM1, sc + SC_TRH);
+    hipLaunchKernelGGL(add_diag_kernel, dim3(blocks_for(d)), dim3(256), 0, ctx->stream, st->cholH, (long long)d, d, 0.0, sc + SC_LAM1);
+    STRP_TAKE(ctx, a2, invd, double, (size_t)((d + NB - 1) / NB) * NB * NB);
+    STRP_TRY(chol_factor(ctx, st->cholH, d, d, invd, ctx->status_dev));
+  }
+  STRP_TRY(fill_zero(ctx, st->W1, sizeof(float) * (size_t)f * d));
+  STRP_TRY(fill_zero(ctx, st->W2, sizeof(float) * (size_t)f * d));
+  STRP_TRY(fill_zero(ctx, st->mask, (size_t)f));
+  STRP_HIP(ctx, hipGetLastError());
+  st->s = 0;
+  st->iter = 0;
+  return STRP_OK;
+}
+
+strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_module_state* st, const strp_params* params,
+                           strp_report* report_host) {
+  if (!ctx) return STRP_EINVAL;
+  STRP_TRY(check_desc(ctx, desc));
+  if (!st || !params) return fail(ctx, STRP_EINVAL, "admm_step: null state or params");
+  if (!st->X || !st->W2hat || !st->Z || !st->A || !st->Z0 || !st->Y || !st->W1 || !st->W2 || !st->cholH || !st->n2 || !st->score ||
+      !st->mask || !st->idx || !st->scalars)
+    return fail(ctx, STRP_EINVAL, "admm_step: null buffer in state");
+  const int d = desc->d, f = desc->f;
+  const long long T = desc->T, lda = desc->lda;
+  const int stages = params->stages ? params->stages : 63;
+  const bool do_select = (stages & STRP_STAGE_SELECT) && (params->reselect || st->s == 0);
+  if (do_select && (params->k <= 0 || params->k > f)) return fail(ctx, STRP_EINVAL, "admm_step: k outside [1, f]");
+  if (desc->k_max > 0 && do_select && params->k > desc->k_max) return fail(ctx, STRP_EINVAL, "admm_step: k above desc.k_max");
+  if (!do_select && st->s <= 0) return fail(ctx, STRP_ESTATE, "admm_step: no mask selected yet");
+  if (!(params->alpha > 0.0) || !(params->beta > 0.0)) return fail(ctx, STRP_EINVAL, "admm_step: alpha, beta must be positive");
+  if (params->mode < STRP_SCORE_WANDA || params->mode > STRP_SCORE_GAIN) return fail(ctx, STRP_EINVAL, "admm_step: unknown score mode");
+  if (!ctx->ws) return fail(ctx, STRP_ENOMEM, "admm_step: no workspace set");
+  const int prec = ctx->precision;
+  const int kf32 = prec == STRP_PREC_SPLIT ? OP_F32_2 : OP_F32_1;
+  const int kx_h = kind_of(desc->x_dtype, STRP_F32, prec);  // X next to an fp32 operand
+  double* sc = st->scalars;
+  const float alpha = (float)params->alpha, beta = (float)params->beta;
+  Arena arena(ctx);
+
+  // ---- S2/S4: scores and top-k ---------------------------------------------------------
+  if (do_select) {
+    Arena a2 = arena;
+    STRP_TAKE(ctx, a2, sums, double, 4 * (size_t)f);
+    STRP_TRY(launch_row_sums(ctx, st->A, STRP_F32, st->Z, st->Z0, lda, T, f, params->mode, sums));
+    STRP_TRY(launch_unit_scores(ctx, sums, st->n2, f, 1, params->mode, st->score, sc + SC_ENERGY));
+    STRP_TRY(launch_topk(ctx, st->score, f, params->k, 1, st->mask, st->idx, (float*)(sc + SC_TAU), nullptr, 0));
+    st->s = params->k;
+  }
+  const int s = st->s;
+  const long long sp = round_up(s, 8);
+
+  // persistent (within this call) compact buffers
+  STRP_TAKE(ctx, arena, W2S, float, (size_t)d * sp);
+  STRP_TAKE(ctx, arena, W1S, float, (size_t)s * d);
+
+  // ---- S1/S5: Gram of the kept A rows, fc2 refit -------------------------------------------
+  if (stages & STRP_STAGE_REFIT2) {
+    Arena a2 = arena;
+    STRP_TAKE(ctx, a2, Gd, double, (size_t)s * s);
+    Operand ao = {st->A, lda, st->idx, s, 0};
+    Operand yo = {st->Y, lda, nullptr, d, 0};
+    STRP_TRY(nt_product(ctx, a2, ao, kf32, ao, kf32, s, s, T, 1, nullptr, 0, Gd, s, nullptr, 0));
+    hipLaunchKernelGGL(add_diag_kernel, dim3(blocks_for(s)), dim3(256), 0, ctx->stream, Gd, (long long)s, s, 0.0, sc + SC_LAM2);
+    RefitIn ri;
+    memset(&ri, 0, sizeof(ri));
+    ri.side = STRP_SIDE_FC2; ri.Ld = Gd; ri.Ld_ready = 1;
+    ri.Lhs = yo; ri.lhs_kind = kf32; ri.Rhs = ao; ri.rhs_kind = kf32; ri.m = d; ri.n = s; ri.T = T;
+    double* sol = nullptr;
+    STRP_TRY(ridge_solve(ctx, a2, ri, &sol));
+    STRP_TRY(scatter_weights(ctx, sol, s, STRP_SIDE_FC2, st->idx, s, st->W2, d, f));
+  }
+  // ---- S6: fc1 refit with the cached factor of H + lam1 I ------------------------------------
+  if (stages & STRP_STAGE_REFIT1) {
+    Arena a2 = arena;
+    Operand zo = {st->Z, lda, st->idx, s, 0};
+    Operand xo = {st->X, (long long)desc->ldx, nullptr, d, 0};
+    RefitIn ri;
+    memset(&ri, 0, sizeof(ri));
+    ri.side = STRP_SIDE_FC1; ri.Ld = st->cholH; ri.Ld_ready = 2;
+    ri.Lhs = zo; ri.lhs_kind = kf32; ri.Rhs = xo; ri.rhs_kind = kx_h; ri.m = s; ri.n = d; ri.T = T;
+    if (desc->x_dtype == STRP_F32) ri.rhs_kind = kf32;
+    double* sol = nullptr;
+    STRP_TRY(ridge_solve(ctx, a2, ri, &sol));
+    STRP_TRY(scatter_weights(ctx, sol, d, STRP_SIDE_FC1, st->idx, s, st->W1, f, d));
+  }
+  if (stages & (STRP_STAGE_AUPD | STRP_STAGE_OBJ))
+    hipLaunchKernelGGL(gather_cols_kernel, dim3(blocks_for((long long)d * sp)), dim3(256), 0, ctx->stream, st->W2, d, f, st->idx, s, W2S, sp);
+  if (stages & (STRP_STAGE_ZUPD | STRP_STAGE_OBJ))
+    hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks_for((long long)s * d)), dim3(256), 0, ctx->stream, st->W1, d, st->idx, s, W1S, (long long)d);
+
+  // ---- S7: a-update in residual (Woodbury) form ------------------------------------------------
+  //   A_S = relu(Z_S) + W^T M^-1 (Y - W relu(Z_S)),  M = (beta/alpha) I + W W^T,  W = W2[:, S];  A_j = relu(Z_j) for pruned j
+  if (stages & STRP_STAGE_AUPD) {
+    Arena a2 = arena;
+    STRP_TAKE(ctx, a2, Md, double, (size_t)d * d);
+    STRP_TAKE(ctx, a2, invd, double, (size_t)((d + NB - 1) / NB) * NB * NB);
+    STRP_TAKE(ctx, a2, Bd, double, (size_t)s * d);
+    STRP_TAKE(ctx, a2, Bm, float, (size_t)s * d);
+    STRP_TAKE(ctx, a2, E, float, (size_t)d * lda);
+    Operand wo = {W2S, sp, nullptr, d, 0};
+    STRP_TRY(nt_product(ctx, a2, wo, kf32, wo, kf32, d, d, sp, 1, nullptr, 0, Md, d, nullptr, 0));
+    hipLaunchKernelGGL(add_diag_kernel, dim3(blocks_for(d)), dim3(256), 0, ctx->stream, Md, (long long)d, d, params->beta / params->alpha, (const double*)nullptr);
+    STRP_TRY(chol_factor(ctx, Md, d, d, invd, ctx->status_dev));
+    hipLaunchKernelGGL(transpose_f32_f64_kernel, dim3(blocks_for((long long)d * s)), dim3(256), 0, ctx->stream, W2S, sp, d, s, Bd, (long long)d);
+    STRP_TRY(chol_solve_right(ctx, Md, d, d, invd, Bd, s, d));
+    STRP_TRY(cast_f64_f32(ctx, Bd, d, Bm, d, s, d));
+    {  // E = Y - W relu(Z_S)
+      GemmP p;
+      memset(&p, 0, sizeof(p));
+      p.P = Operand{W2S, sp, nullptr, d, 0};
+      p.Q = Operand{st->Z, lda, st->idx, s, 1};
+      p.M = d; p.N = (int)T; p.K = s;
+      p.epi = EPI_RESID; p.Yin = st->Y; p.ldy = lda; p.out = E; p.ldo = lda; p.write_out = 1;
+      gemm_plan_tiles(p, true, 1);
+      STRP_TRY(launch_gemm(ctx, p, kf32, kf32, true));
+    }
+    {  // A_S = relu(Z_S) + B E
+      GemmP p;
+      memset(&p, 0, sizeof(p));
+      p.P = Operand{Bm, (long long)d, nullptr, s, 0};
+      p.Q = Operand{E, lda, nullptr, d, 0};
+      p.M = s; p.N = (int)T; p.K = d;
+      p.epi = EPI_AUPD; p.Zs = st->Z; p.As = st->A; p.lda = lda; p.oidx = st->idx;
+      gemm_plan_tiles(p, true, 1);
+      STRP_TRY(launch_gemm(ctx, p, kf32, kf32, true));
+    }
+    hipLaunchKernelGGL(pruned_rows_kernel, dim3(f), dim3(256), 0, ctx->stream, st->mask, st->Z, st->A, lda, T, 0, alpha, beta, 1, (double*)nullptr);
+  }
+  // ---- S8 (+ objective terms 2, 3): z-update fused on Z1 = W1 X --------------------------------
+  const bool zupd = (stages & STRP_STAGE_ZUPD) != 0;
+  if (zupd || (stages & STRP_STAGE_OBJ)) {
+    Arena a2 = arena;
+    GemmP p;
+    memset(&p, 0, sizeof(p));
+    p.P = Operand{W1S, (long long)d, nullptr, s, 0};
+    p.Q = Operand{st->X, (long long)desc->ldx, nullptr, d, 0};
+    p.M = s; p.N = (int)T; p.K = d;
+    p.epi = EPI_ZUPD; p.Zs = st->Z; p.As = st->A; p.lda = lda; p.oidx = st->idx; p.alpha = alpha; p.beta = beta;
+    p.write_out = zupd ? 1 : 0;
+    gemm_plan_tiles(p, true, 1);
+    const int nb = gemm_grid_blocks(p);
+    STRP_TAKE(ctx, a2, red, double, 2 * (size_t)(nb > f ? nb : f));
+    p.red = red;
+    const int kq = desc->x_dtype == STRP_F32 ? kf32 : kx_h;
+    STRP_TRY(launch_gemm(ctx, p, kf32, kq, true));
+    STRP_TRY(launch_block_sum(ctx, red, nb, sc + SC_TMP0, sc + SC_TMP1, 1.0, 1.0));
+    hipLaunchKernelGGL(pruned_rows_kernel, dim3(f), dim3(256), 0, ctx->stream, st->mask, st->Z, st->A, lda, T, 1, alpha, beta, zupd ? 1 : 0, red);
+    STRP_TRY(launch_block_sum(ctx, red, f, sc + SC_TMP2, sc + SC_TMP3, 1.0, 1.0));
+    hipLaunchKernelGGL(axpby_scalar_kernel, dim3(1), dim3(1), 0, ctx->stream, sc, (int)SC_T2, params->beta / (double)T, (int)SC_TMP0, params->beta / (double)T, (int)SC_TMP2);
+    hipLaunchKernelGGL(axpby_scalar_kernel, dim3(1), dim3(1), 0, ctx->stream, sc, (int)SC_T3, params->alpha / (double)T, (int)SC_TMP1, params->alpha / (double)T, (int)SC_TMP3);
+  }
+  // ---- S9: objective term 1 and ridge terms ------------------------------------------------------
+  if (stages & STRP_STAGE_OBJ) {
+    Arena a2 = arena;
+    GemmP p;
+    memset(&p, 0, sizeof(p));
+    p.P = Operand{W2S, sp, nullptr, d, 0};
+    p.Q = Operand{st->A, lda, st->idx, s, 0};
+    p.M = d; p.N = (int)T; p.K = s;
+    p.epi = EPI_RESID; p.Yin = st->Y; p.ldy = lda; p.write_out = 0;
+    gemm_plan_tiles(p, true, 1);
+    const int nb = gemm_grid_blocks(p);
+    STRP_TAKE(ctx, a2, red, double, 2 * (size_t)(nb > 1024 ? nb : 1024));
+    p.red = red;
+    STRP_TRY(launch_gemm(ctx, p, OP_F32_1, OP_F32_1, true));
+    STRP_TRY(launch_block_sum(ctx, red, nb, sc + SC_T1, nullptr, params->alpha / (double)T, 1.0));
+    hipLaunchKernelGGL(sumsq_kernel, dim3(1024), dim3(256), 0, ctx->stream, W2S, (long long)d * sp, red);
+    STRP_TRY(launch_block_sum(ctx, red, 1024, sc + SC_W2SQ, nullptr, 1.0, 1.0));
+    hipLaunchKernelGGL(sumsq_kernel, dim3(1024), dim3(256), 0, ctx->stream, W1S, (long long)s * d, red);
+    STRP_TRY(launch_block_sum(ctx, red, 1024, sc + SC_W1SQ, nullptr, 1.0, 1.0));
+  }
+  STRP_HIP(ctx, hipGetLastError());
+  st->iter += 1;
+
+  if (report_host) {
+    double* h = (double*)ctx->pinned;
+    STRP_HIP(ctx, hipMemcpyAsync(h, sc, SC_COUNT * sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
+    STRP_HIP(ctx, hipMemcpyAsync(h + SC_COUNT, ctx->status_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+    STRP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    memset(report_host, 0, sizeof(*report_host));
+    report_host->lam1 = h[SC_LAM1];
+    report_host->lam2 = h[SC_LAM2];
+    report_host->terms[0] = h[SC_T1];
+    report_host->terms[1] = h[SC_T2];
+    report_host->terms[2] = h[SC_T3];
+    report_host->terms[3] = params->alpha * h[SC_LAM2] * h[SC_W2SQ] / (double)T;
+    report_host->terms[4] = params->alpha * h[SC_LAM1] * h[SC_W1SQ] / (double)T;
+    report_host->J = report_host->terms[0] + report_host->terms[1] + report_host->terms[2];
+    report_host->J_ridge = report_host->J + report_host->terms[3] + report_host->terms[4];
+    report_host->tau = *(float*)(h + SC_TAU);
+    report_host->s = s;
+    report_host->status = *(int32_t*)(h + SC_COUNT);
+    if (report_host->status != 0) {
+      fail(ctx, (strp_status)report_host->status, "device status word = %d", report_host->status);
+      STRP_TRY(fill_zero(ctx, ctx->status_dev, 256));
+    }
+  }
+  return STRP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,152 @@
+// Internal declarations shared by the HIP translation units of libstrp.so (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "strp.h"
+
+struct strp_ctx {
+  int device;
+  hipStream_t stream;
+  char* ws;            // caller-owned device workspace
+  size_t ws_bytes;
+  int precision;       // strp_precision
+  int32_t* status_dev; // first word of the workspace
+  void* pinned;        // small pinned host buffer for report read-back
+  char err[512];
+};
+
+namespace strp {
+
+// ---- error helpers -------------------------------------------------------------------
+strp_status fail(strp_ctx* ctx, strp_status st, const char* fmt, ...);
+#define STRP_HIP(ctx, call)                                                              \
+  do {                                                                                   \
+    hipError_t e_ = (call);                                                              \
+    if (e_ != hipSuccess)                                                                \
+      return strp::fail((ctx), STRP_EHIP, "%s failed: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+#define STRP_TRY(expr)                  \
+  do {                                  \
+    strp_status s_ = (expr);            \
+    if (s_ != STRP_OK) return s_;       \
+  } while (0)
+
+// ---- workspace bump arena (256-byte granules); the first granule holds the status word --
+struct Arena {
+  char* base;
+  size_t off, cap;
+  Arena() : base(nullptr), off(0), cap(0) {}
+  explicit Arena(strp_ctx* ctx) : base(ctx->ws), off(256), cap(ctx->ws_bytes) {}
+  void* take(size_t bytes) {
+    size_t b = (bytes + 255) & ~size_t(255);
+    if (!base || off + b > cap) return nullptr;
+    void* p = base + off;
+    off += b;
+    return p;
+  }
+};
+#define STRP_TAKE(ctx, arena, var, type, count)                                                     \
+  type* var = (type*)(arena).take(sizeof(type) * (size_t)(count));                                  \
+  if (!var) return strp::fail((ctx), STRP_ENOMEM, "workspace too small for %s (%zu bytes more)",    \
+                              #var, sizeof(type) * (size_t)(count))
+
+// ---- MFMA GEMM family (gemm_mfma.hip) ---------------------------------------------------
+// Operand kinds: how an operand reaches the 16-bit matrix cores.
+enum { OP_BF16 = 0,     // bf16 in memory, used as is (both operands must be OP_BF16)
+       OP_F32_1 = 1,    // fp32 in memory, rounded once to fp16
+       OP_F32_2 = 2,    // fp32 in memory, split into fp16 hi + scaled fp16 lo
+       OP_BF16_H = 3 }; // bf16 in memory, converted (exactly, in range) to fp16
+
+struct Operand {
+  const void* ptr;
+  long long ld;     // elements
+  const int* idx;   // optional row gather (rows of the stored matrix), device
+  int rows;         // logical rows (P: M; Q: N for token-contraction, K for token-parallel form)
+  int relu;         // apply max(x, 0) on load (fp32 kinds only)
+};
+
+enum { EPI_PARTIAL = 0, EPI_STORE = 1, EPI_INITZ = 2, EPI_RESID = 3, EPI_AUPD = 4, EPI_ZUPD = 5 };
+
+struct GemmP {
+  Operand P, Q;
+  int M, N;
+  long long K;
+  int tilesM, tilesN, ntiles;
+  int triangle;        // P == Q, only tiles with tn <= tm are computed
+  int splits;
+  long long kchunk;    // K range per split (multiple of the K tile)
+  int epi;
+  float* out;          // PARTIAL: [splits][M][N]; STORE / RESID: [M x ldo]
+  long long ldo;
+  const float* Yin;    // RESID: Y
+  long long ldy;
+  float* Zs;           // INITZ / AUPD / ZUPD state pointers, leading dimension lda
+  float* As;
+  float* Z0s;
+  long long lda;
+  const int* oidx;     // AUPD / ZUPD: output row m is state row oidx[m]
+  float alpha, beta;
+  double* red;         // per-block partial sums [gridDim.x][2] (INITZ, RESID, ZUPD)
+  int write_out;       // RESID: store the residual
+};
+
+// Token-contraction form ("NT"): C[M x N] = sum_k P[m,k] Q[n,k]; writes split-K partials.
+// Token-parallel form ("NN"): C[M x N] = sum_k P[m,k] Q[k,n] with fused epilogue.
+strp_status launch_gemm(strp_ctx* ctx, GemmP& p, int kindP, int kindQ, bool nn);
+int gemm_grid_blocks(const GemmP& p);
+void gemm_plan_tiles(GemmP& p, bool nn, int want_blocks);
+
+// Sum split-K partials in fp64; optional symmetric completion from the computed lower tiles.
+// outf / outd (either may be null): [M x ldo]; accumulate adds to outf's previous content.
+strp_status launch_splitk_reduce(strp_ctx* ctx, const float* part, int splits, int M, int N, int triangle,
+                                 float* outf, long long ldof, double* outd, long long ldod, double* diag,
+                                 int accumulate);
+// Sum per-block fp64 partials red[nblocks][2] into dst[0], dst[1] (fixed order).
+strp_status launch_block_sum(strp_ctx* ctx, const double* red, int nblocks, double* dst0, double* dst1,
+                             double scale0, double scale1);
+
+// ---- fp64 dense kernels (dense_f64.hip) ---------------------------------------------------
+constexpr int NB = 64;  // block order of the factorisation
+// In-place lower Cholesky of the n x n fp64 matrix A (ld), A += 0 (caller adds the ridge).
+// invd: [ceil(n/NB)][NB*NB] inverses of the diagonal blocks of L.  status: device word.
+strp_status chol_factor(strp_ctx* ctx, double* A, int n, long long ld, double* invd, int32_t* status);
+// In place X <- X (L L^T)^-1 for X [m x n] (ldx), L lower factor with block inverses invd.
+strp_status chol_solve_right(strp_ctx* ctx, const double* L, int n, long long ldl, const double* invd,
+                             double* X, int m, long long ldx);
+// C[M x N] = alpha * A * B + beta * C with arbitrary element strides; lower != 0 skips tiles above
+// the diagonal.
+strp_status dgemm(strp_ctx* ctx, int M, int N, int K, double alpha, const double* A, long long rsa,
+                  long long csa, const double* B, long long rsb, long long csb, double beta, double* C,
+                  long long ldc, int lower);
+// Ad[i*ld+j] = (double)Af[i*ldf+j] + (i==j ? lam (or *lam_dev if non-null) : 0)
+strp_status f32_to_f64_ridge(strp_ctx* ctx, const float* Af, long long ldf, double* Ad, long long ld, int n,
+                             double lam, const double* lam_dev);
+
+// ---- reductions, scores, allocation, select (score_select.hip) ------------------------------
+strp_status launch_row_sums(strp_ctx* ctx, const void* A, int a_dtype, const float* Z, const float* Z0,
+                            long long ld, long long T, int rows, int mode, double* sums /*[4][rows]*/);
+strp_status launch_colnorm2(strp_ctx* ctx, const void* W, int w_dtype, int rows, int cols, long long ldw,
+                            double* n2);
+strp_status launch_unit_scores(strp_ctx* ctx, const double* sums, const double* n2, int n_channels, int group,
+                               int mode, float* score, double* energy_out);
+strp_status launch_alloc(strp_ctx* ctx, const double* energies, int L, const int32_t* n_units,
+                         const int32_t* group_id, double rbar, double temperature, double rmax, double* r_out,
+                         int32_t* nprune_out);
+strp_status launch_topk(strp_ctx* ctx, const float* score, int n, int k, int group, uint8_t* mask, int32_t* idx,
+                        float* tau, void* scratch, size_t scratch_bytes);
+size_t topk_scratch_bytes(int n);
+
+// ---- small elementwise helpers (dense_f64.hip) -----------------------------------------------
+// dst (fp32, [rows x ldd]) = src (fp64, [rows x lds]) cast; pad columns [cols, ldd) zero-filled.
+strp_status cast_f64_f32(strp_ctx* ctx, const double* src, long long lds, float* dst, long long ldd, int rows,
+                         int cols);
+// W[out x in] dense fp32: scatter compact solution rows/columns by idx, everything else zero.
+strp_status scatter_weights(strp_ctx* ctx, const double* sol, long long lds, int side, const int32_t* idx,
+                            int s, float* W, int out, int in);
+strp_status fill_zero(strp_ctx* ctx, void* ptr, size_t bytes);
+
+}  // namespace strp
