@@ -456,7 +456,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* part, i
   if (e >= (long long)M * N) return;
   const int m = (int)(e / N), n = (int)(e % N);
   long long src = e;
-  if (triangle && (n / BN) > (m / BM)) src = (long long)n * N + m;  // mirror of a computed lower tile
+  if (triangle && n > m) src = (long long)n * N + m;  // upper half mirrors the computed lower half (exact symmetry)
   double s = 0.0;
   for (int sp = 0; sp < splits; ++sp) s += (double)part[(long long)sp * M * N + src];
   if (outf) {
