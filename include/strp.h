@@ -62,6 +62,20 @@ strp_status strp_set_workspace(strp_ctx* ctx, void* dev_ptr, size_t bytes);
 /* Synchronise the stream and return the device status word (STRP_OK, STRP_ENOTPD, ...). */
 strp_status strp_poll(strp_ctx* ctx);
 
+/* Optional per-kernel timing (HIP events on the context's stream), for benchmarks and profiles.
+ * strp_profile_enable(ctx, on) clears the records and switches recording on or off;
+ * strp_profile_read synchronises the stream and returns one aggregated entry per kernel class:
+ * launches, total milliseconds, algorithmic flops and algorithmic bytes.  out_host is HOST memory. */
+typedef struct {
+  char name[48];
+  int32_t launches;
+  double ms;
+  double flops;
+  double bytes;
+} strp_profile_entry;
+strp_status strp_profile_enable(strp_ctx* ctx, int on);
+strp_status strp_profile_read(strp_ctx* ctx, strp_profile_entry* out_host, int32_t max_entries, int32_t* n_out);
+
 /* ---- module description shared by the stateful entry points ------------------------- */
 typedef struct {
   int32_t d, f;        /* widths                                                            */

@@ -186,6 +186,7 @@ static strp_status panel_mul(strp_ctx* ctx, double* X, long long ldx, int rows, 
 }
 
 strp_status chol_factor(strp_ctx* ctx, double* A, int n, long long ld, double* invd, int32_t* status) {
+  ProfScope ps(ctx, "chol_factor_f64", (double)n * n * n / 3.0, 8.0 * (double)n * n);
   for (int j0 = 0; j0 < n; j0 += NB) {
     const int jb = (n - j0 < NB) ? (n - j0) : NB;
     double* Ajj = A + (long long)j0 * ld + j0;
@@ -205,6 +206,7 @@ strp_status chol_factor(strp_ctx* ctx, double* A, int n, long long ld, double* i
 
 strp_status chol_solve_right(strp_ctx* ctx, const double* L, int n, long long ldl, const double* invd, double* X, int m,
                              long long ldx) {
+  ProfScope ps(ctx, "chol_solve_f64", 2.0 * (double)m * n * n, 8.0 * ((double)n * n * 0.5 + 2.0 * (double)m * n));
   // V L^T = X  (column blocks ascending), then  X L = V  (descending); both in place.
   for (int j0 = 0; j0 < n; j0 += NB) {
     const int jb = (n - j0 < NB) ? (n - j0) : NB;

@@ -426,6 +426,17 @@ strp_status launch_gemm(strp_ctx* ctx, GemmP& p, int kp, int kq, bool nn) {
   if (p.ntiles <= 0 || p.splits <= 0) return fail(ctx, STRP_EINVAL, "gemm: tiles not planned");
   if ((kp == OP_BF16) != (kq == OP_BF16)) return fail(ctx, STRP_EINVAL, "gemm: bf16 cores need both operands bf16");
   const int key = (nn ? 100 : 0) + kp * 10 + kq;
+  static const char* const epi_names[] = {"partial", "store", "initz", "resid", "aupd", "zupd"};
+  static char names[2][4][4][6][40];
+  char* name = names[nn ? 1 : 0][kp][kq][p.epi];
+  if (!name[0]) snprintf(name, 40, "gemm_%s_p%d_q%d_%s", nn ? "nn" : "nt", kp, kq, epi_names[p.epi]);
+  const double mn = p.triangle ? 0.5 * (double)p.M * ((double)p.M + 1.0) : (double)p.M * (double)p.N;
+  const double esp = (kp == OP_BF16 || kp == OP_BF16_H) ? 2.0 : 4.0, esq = (kq == OP_BF16 || kq == OP_BF16_H) ? 2.0 : 4.0;
+  static const double out_words[] = {1.0, 1.0, 3.0, 2.0, 2.0, 2.0};
+  double obytes = 4.0 * out_words[p.epi] * (double)p.M * (double)p.N * (p.epi == EPI_PARTIAL ? (double)p.splits : 1.0);
+  if (p.epi == EPI_RESID && !p.write_out) obytes *= 0.5;
+  const double ibytes = p.triangle ? esp * (double)p.M * (double)p.K : esp * (double)p.M * (double)p.K + esq * (double)p.N * (double)p.K;
+  ProfScope ps(ctx, name, 2.0 * mn * (double)p.K, ibytes + obytes);
   switch (key) {
     case 0: launch_one<OP_BF16, OP_BF16, false>(ctx, p); break;
     case 11: launch_one<OP_F32_1, OP_F32_1, false>(ctx, p); break;
@@ -471,6 +482,7 @@ strp_status launch_splitk_reduce(strp_ctx* ctx, const float* part, int splits, i
                                  float* outf, long long ldof, double* outd, long long ldod, double* diag,
                                  int accumulate) {
   const long long tot = (long long)M * N;
+  ProfScope ps(ctx, "splitk_reduce", 0.0, 4.0 * (double)tot * (double)splits + (outf ? 4.0 : 0.0) * tot + (outd ? 8.0 : 0.0) * tot);
   hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, ctx->stream, part,
                      splits, M, N, triangle, outf, ldof, outd, ldod, diag, accumulate);
   STRP_HIP(ctx, hipGetLastError());

@@ -121,6 +121,9 @@ strp_status launch_row_sums(strp_ctx* ctx, const void* A, int a_dtype, const flo
   const bool full = mode != STRP_SCORE_WANDA;
   if (full && a_dtype != STRP_F32) return fail(ctx, STRP_EINVAL, "score: LEMMA/GAIN need fp32 auxiliaries");
   dim3 grid(rows), block(256);
+  const double es = a_dtype == STRP_BF16 ? 2.0 : 4.0;
+  ProfScope ps(ctx, full ? "row_sums_full" : "row_sums_wanda", (full ? 8.0 : 2.0) * (double)rows * (double)T,
+               (full ? 12.0 : es) * (double)rows * (double)T);
   if (full)
     hipLaunchKernelGGL((row_sums_kernel<false, true>), grid, block, 0, ctx->stream, A, Z, Z0, ld, T, rows, sums, ctx->status_dev);
   else if (a_dtype == STRP_BF16)
@@ -438,6 +441,7 @@ strp_status launch_topk(strp_ctx* ctx, const float* score, int n, int k, int gro
                         void* scratch, size_t scratch_bytes) {
   (void)scratch;
   (void)scratch_bytes;
+  ProfScope ps(ctx, "topk", 0.0, 5.0 * (double)n + 4.0 * (double)k * group);
   hipLaunchKernelGGL(topk_kernel, dim3(1), dim3(1024), 0, ctx->stream, score, n, k, group, mask, idx, tau);
   STRP_HIP(ctx, hipGetLastError());
   return STRP_OK;

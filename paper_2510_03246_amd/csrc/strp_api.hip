@@ -3,10 +3,47 @@
 
 #include <cmath>
 #include <new>
+#include <string>
+#include <vector>
 
 #include "strp_internal.h"
 
+struct Profiler {
+  struct Rec { const char* name; double flops, bytes; hipEvent_t e0, e1; };
+  bool on = false;
+  std::vector<Rec> recs;
+  std::vector<hipEvent_t> pool;
+  hipEvent_t get() {
+    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+  void clear() {
+    for (auto& r : recs) { pool.push_back(r.e0); pool.push_back(r.e1); }
+    recs.clear();
+  }
+  ~Profiler() {
+    clear();
+    for (auto e : pool) if (e) (void)hipEventDestroy(e);
+  }
+};
+
 namespace strp {
+
+int prof_begin(strp_ctx* ctx, const char* name, double flops, double bytes) {
+  Profiler* pr = ctx->prof;
+  if (!pr || !pr->on) return -1;
+  Profiler::Rec r{name, flops, bytes, pr->get(), pr->get()};
+  if (!r.e0 || !r.e1) return -1;
+  (void)hipEventRecord(r.e0, ctx->stream);
+  pr->recs.push_back(r);
+  return (int)pr->recs.size() - 1;
+}
+void prof_end(strp_ctx* ctx, int rec) {
+  if (rec < 0) return;
+  (void)hipEventRecord(ctx->prof->recs[rec].e1, ctx->stream);
+}
 
 strp_status fail(strp_ctx* ctx, strp_status st, const char* fmt, ...) {
   if (ctx) {
@@ -254,6 +291,7 @@ strp_status strp_create(strp_ctx** out, int device, void* hip_stream) {
 strp_status strp_destroy(strp_ctx* ctx) {
   if (!ctx) return STRP_EINVAL;
   if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+  delete ctx->prof;
   delete ctx;
   return STRP_OK;
 }
@@ -264,6 +302,43 @@ strp_status strp_set_precision(strp_ctx* ctx, strp_precision prec) {
   if (!ctx) return STRP_EINVAL;
   if (prec != STRP_PREC_FAST && prec != STRP_PREC_SPLIT) return fail(ctx, STRP_EINVAL, "unknown precision %d", (int)prec);
   ctx->precision = prec;
+  return STRP_OK;
+}
+
+strp_status strp_profile_enable(strp_ctx* ctx, int on) {
+  if (!ctx) return STRP_EINVAL;
+  if (!ctx->prof) ctx->prof = new (std::nothrow) Profiler();
+  if (!ctx->prof) return fail(ctx, STRP_ENOMEM, "profile: host allocation failed");
+  STRP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  ctx->prof->clear();
+  ctx->prof->on = on != 0;
+  return STRP_OK;
+}
+
+strp_status strp_profile_read(strp_ctx* ctx, strp_profile_entry* out_host, int32_t max_entries, int32_t* n_out) {
+  if (!ctx || !out_host || !n_out || max_entries <= 0) return ctx ? fail(ctx, STRP_EINVAL, "profile_read: bad argument") : STRP_EINVAL;
+  *n_out = 0;
+  if (!ctx->prof) return STRP_OK;
+  STRP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  int n = 0;
+  for (auto& r : ctx->prof->recs) {
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, r.e0, r.e1) != hipSuccess) continue;
+    int j = 0;
+    for (; j < n; ++j)
+      if (strncmp(out_host[j].name, r.name, sizeof(out_host[j].name)) == 0) break;
+    if (j == n) {
+      if (n == max_entries) continue;
+      memset(&out_host[n], 0, sizeof(out_host[n]));
+      strncpy(out_host[n].name, r.name, sizeof(out_host[n].name) - 1);
+      ++n;
+    }
+    out_host[j].launches += 1;
+    out_host[j].ms += ms;
+    out_host[j].flops += r.flops;
+    out_host[j].bytes += r.bytes;
+  }
+  *n_out = n;
   return STRP_OK;
 }
 
@@ -637,7 +712,10 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
       gemm_plan_tiles(p, true, 1);
       STRP_TRY(launch_gemm(ctx, p, kf32, kf32, true));
     }
-    hipLaunchKernelGGL(pruned_rows_kernel, dim3(f), dim3(256), 0, ctx->stream, st->mask, st->Z, st->A, lda, T, 0, alpha, beta, 1, (double*)nullptr);
+    {
+      ProfScope ps(ctx, "pruned_rows_a", 0.0, 8.0 * (double)(f - s) * (double)T);
+      hipLaunchKernelGGL(pruned_rows_kernel, dim3(f), dim3(256), 0, ctx->stream, st->mask, st->Z, st->A, lda, T, 0, alpha, beta, 1, (double*)nullptr);
+    }
   }
   // ---- S8 (+ objective terms 2, 3): z-update fused on Z1 = W1 X --------------------------------
   const bool zupd = (stages & STRP_STAGE_ZUPD) != 0;
@@ -657,7 +735,10 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     const int kq = desc->x_dtype == STRP_F32 ? kf32 : kx_h;
     STRP_TRY(launch_gemm(ctx, p, kf32, kq, true));
     STRP_TRY(launch_block_sum(ctx, red, nb, sc + SC_TMP0, sc + SC_TMP1, 1.0, 1.0));
-    hipLaunchKernelGGL(pruned_rows_kernel, dim3(f), dim3(256), 0, ctx->stream, st->mask, st->Z, st->A, lda, T, 1, alpha, beta, zupd ? 1 : 0, red);
+    {
+      ProfScope ps(ctx, "pruned_rows_z", 0.0, 8.0 * (double)(f - s) * (double)T);
+      hipLaunchKernelGGL(pruned_rows_kernel, dim3(f), dim3(256), 0, ctx->stream, st->mask, st->Z, st->A, lda, T, 1, alpha, beta, zupd ? 1 : 0, red);
+    }
     STRP_TRY(launch_block_sum(ctx, red, f, sc + SC_TMP2, sc + SC_TMP3, 1.0, 1.0));
     hipLaunchKernelGGL(axpby_scalar_kernel, dim3(1), dim3(1), 0, ctx->stream, sc, (int)SC_T2, params->beta / (double)T, (int)SC_TMP0, params->beta / (double)T, (int)SC_TMP2);
     hipLaunchKernelGGL(axpby_scalar_kernel, dim3(1), dim3(1), 0, ctx->stream, sc, (int)SC_T3, params->alpha / (double)T, (int)SC_TMP1, params->alpha / (double)T, (int)SC_TMP3);

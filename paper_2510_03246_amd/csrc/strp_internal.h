@@ -17,9 +17,23 @@ struct strp_ctx {
   int32_t* status_dev; // first word of the workspace
   void* pinned;        // small pinned host buffer for report read-back
   char err[512];
+  struct Profiler* prof;  // optional per-kernel event timing (host object)
 };
 
+struct Profiler;
+
 namespace strp {
+
+// ---- optional per-kernel timing with HIP events on the context's stream -----------------------
+// prof_begin returns a record index (or -1 when profiling is off); prof_end closes it.
+int prof_begin(strp_ctx* ctx, const char* name, double flops, double bytes);
+void prof_end(strp_ctx* ctx, int rec);
+struct ProfScope {
+  strp_ctx* ctx;
+  int rec;
+  ProfScope(strp_ctx* c, const char* name, double flops, double bytes) : ctx(c), rec(prof_begin(c, name, flops, bytes)) {}
+  ~ProfScope() { prof_end(ctx, rec); }
+};
 
 // ---- error helpers -------------------------------------------------------------------
 strp_status fail(strp_ctx* ctx, strp_status st, const char* fmt, ...);

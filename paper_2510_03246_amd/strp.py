@@ -24,7 +24,7 @@ STAGE_ALL = 63
 
 EXPORTS = [
     "strp_create", "strp_destroy", "strp_last_error", "strp_set_precision", "strp_set_workspace",
-    "strp_poll", "strp_workspace_bytes", "strp_gram", "strp_score_alloc", "strp_mask_topk",
+    "strp_poll", "strp_workspace_bytes", "strp_profile_enable", "strp_profile_read", "strp_gram", "strp_score_alloc", "strp_mask_topk",
     "strp_refit", "strp_module_init", "strp_admm_step",
 ]
 
@@ -64,6 +64,11 @@ class Report(C.Structure):
                 ("lam2", C.c_double), ("tau", C.c_float), ("s", C.c_int32), ("status", C.c_int32)]
 
 
+class ProfileEntry(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("launches", C.c_int32), ("ms", C.c_double), ("flops", C.c_double),
+                ("bytes", C.c_double)]
+
+
 _lib = None
 
 
@@ -84,6 +89,8 @@ def load_library():
     lib.strp_set_precision.argtypes = [vp, C.c_int]
     lib.strp_set_workspace.argtypes = [vp, vp, C.c_size_t]
     lib.strp_poll.argtypes = [vp]
+    lib.strp_profile_enable.argtypes = [vp, C.c_int]
+    lib.strp_profile_read.argtypes = [vp, C.POINTER(ProfileEntry), i32, C.POINTER(i32)]
     lib.strp_workspace_bytes.argtypes = [C.POINTER(ModuleDesc)]
     lib.strp_workspace_bytes.restype = C.c_size_t
     lib.strp_gram.argtypes = [vp, vp, C.c_int, i32, i64, i64, vp, i32, vp, i32, vp, C.c_int]
@@ -159,6 +166,17 @@ class Context:
 
     def poll(self) -> int:
         return self.lib.strp_poll(self.h)
+
+    def profile_enable(self, on: bool):
+        self.check(self.lib.strp_profile_enable(self.h, int(on)))
+
+    def profile_read(self):
+        """Per-kernel-class totals since profile_enable: {name: dict(launches, ms, flops, bytes)}."""
+        buf = (ProfileEntry * 64)()
+        n = C.c_int32(0)
+        self.check(self.lib.strp_profile_read(self.h, buf, 64, C.byref(n)))
+        return {buf[i].name.decode(): dict(launches=buf[i].launches, ms=buf[i].ms, flops=buf[i].flops,
+                                           bytes=buf[i].bytes) for i in range(n.value)}
 
     def workspace_bytes(self, desc: ModuleDesc) -> int:
         return int(self.lib.strp_workspace_bytes(C.byref(desc)))
