@@ -89,6 +89,8 @@ typedef struct {
 
 /* Bytes of workspace sufficient for every entry point on this module (pure function). */
 size_t strp_workspace_bytes(const strp_module_desc* desc);
+/* Bytes of the per-module plane cache (strp_module_state::cache); pure function. */
+size_t strp_module_cache_bytes(const strp_module_desc* desc);
 
 /*
  * strp_gram -- calibration Gram matrix over the tokens (the X X^T / a a^T that W = z a^+ needs;
@@ -189,6 +191,8 @@ typedef struct {
   uint8_t* mask;       /* [f]         1 = kept                                              */
   int32_t* idx;        /* [f]         kept indices ascending (first s valid)                */
   double* scalars;     /* [32]        device scalars: lam1, lam2, objective sums, tau       */
+  void* cache;         /* strp_module_cache_bytes(desc) bytes, 256-byte aligned: fp16 operand planes of
+                          X and Y written by strp_module_init and read by every later step      */
   int32_t s;           /* kept units of the current mask (host field, set by the library)   */
   int32_t iter;        /* inner iterations done (host field)                                */
 } strp_module_state;

@@ -1,13 +1,17 @@
-// MFMA GEMM family for gfx950: 128x128 block tiles, four wavefronts of 64x64, 32x32x16 matrix-core
-// instructions, LDS-staged 16-bit operand tiles, fp32 accumulation.
+// MFMA GEMM family for gfx950 on 16-bit operand planes: 128x128 block tiles, four wavefronts of 64x64,
+// v_mfma_f32_32x32x16 matrix-core instructions, LDS-staged tiles, fp32 accumulation.
 //
-// fp32 operands (ADMM auxiliaries, refitted weights) are fed to the 16-bit matrix cores as a
-// two-term fp16 split x = hi + lo/2048 (hi = fp16(x), lo = fp16((x - hi) * 2048)).  The products
-// hi*hi go to one accumulator set, hi*lo + lo*hi to a second one that is folded in with weight
-// 1/2048 in the epilogue; the dropped lo*lo term is ~2^-22 relative.  bf16 inputs are exact in one
-// plane.  Two memory forms share the MFMA core:
-//   token-contraction ("NT"):  C[m,n] = sum_t P[m,t] Q[n,t]   (Gram matrices, refit right-hand sides)
-//   token-parallel   ("NN"):  C[m,t] = sum_k P[m,k] Q[k,t]   (forward products with fused ADMM updates)
+// fp32 quantities (ADMM auxiliaries, refitted weights, targets) are kept for the matrix cores as TWO
+// fp16 planes, x*scale = hi + lo with hi = fp16(x*scale), lo = fp16(x*scale - hi) (fp16 subnormals are
+// honoured by the f16 MFMA, so lo is exact to 2^-25 absolute).  A product of two split operands runs
+// the three leading passes hi*hi + hi*lo + lo*hi into ONE fp32 accumulator (the dropped lo*lo term is
+// ~2^-22 relative); a bf16 input is exact in a single fp16 plane.  The planes are written once by the
+// split kernels below (or by a producing epilogue) instead of being re-converted by every tile that
+// reads them.  Two memory forms share the MFMA core:
+//   token-contraction ("NT"):  C[m,n] = sum_t P[m,t] Q[n,t]   both operands ROW planes [row][t]
+//   token-parallel   ("NN"):  C[m,t] = sum_k P[m,k] Q[k,t]   Q is a K8 plane [(k/8)][t][8]: the eight
+//                              k-values a matrix-core lane needs are one 16-byte chunk, and consecutive
+//                              tokens are consecutive chunks (coalesced), so no transpose is needed.
 #include "strp_internal.h"
 
 namespace strp {
@@ -16,12 +20,9 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128, BN = 128, BK = 32;
-constexpr int LDK = BK + 8;  // LDS row pitch in 16-bit elements (80 bytes: conflict-free b128 reads)
-constexpr float LO_SCALE = 2048.0f;
-
-__host__ __device__ constexpr bool kind_is_f32(int k) { return k == OP_F32_1 || k == OP_F32_2; }
-__host__ __device__ constexpr int kind_planes(int k) { return k == OP_F32_2 ? 2 : 1; }
+constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int LDK = BK + 8;      // LDS row pitch in 16-bit elements (144 bytes: conflict-free b128 reads)
+constexpr int NCH = BM * (BK / 8) / 256;  // 16-byte chunks per thread per plane per K tile (= 4)
 
 __device__ __forceinline__ unsigned short half_bits(float x) {
   _Float16 h = (_Float16)x;
@@ -34,179 +35,88 @@ __device__ __forceinline__ void split_half(float x, unsigned short& hi, unsigned
   x = clamp_half_range(x);
   _Float16 h = (_Float16)x;
   hi = __builtin_bit_cast(unsigned short, h);
-  lo = half_bits((x - (float)h) * LO_SCALE);
-}
-__device__ __forceinline__ float bf16_bits_to_float(unsigned short b) {
-  return __builtin_bit_cast(float, (unsigned int)b << 16);
+  lo = half_bits(x - (float)h);
 }
 __device__ __forceinline__ unsigned int pack2(unsigned short a, unsigned short b) {
   return (unsigned int)a | ((unsigned int)b << 16);
 }
 
-// ---------------------------------------------------------------------------------------------
-// K-contiguous operand tile: [128 rows][BK] elements, each thread owns fixed rows and a fixed k chunk
-// ---------------------------------------------------------------------------------------------
-template <int KIND>
-struct KcTile {
-  static constexpr bool F32 = kind_is_f32(KIND);
-  static constexpr int EW = F32 ? 4 : 8;            // elements per 16-byte chunk
-  static constexpr int NCH = F32 ? 4 : 2;           // chunks per thread per tile
-  static constexpr int CPR = BK / EW;               // chunks per row
-  static constexpr int RSTEP = 256 / CPR;           // row stride between a thread's chunks
-  const char* rp[NCH];                              // row base pointers (bytes)
-  uint4 r[NCH];
-  int kc;                                           // element offset of this thread's chunk in the tile
-  int row0;
+// ROW plane tile: [128 rows][64 k]; thread owns rows (tid>>3) + 32 i and the 8-element chunk tid&7
+template <int NP>
+struct RowLoader {
+  const unsigned short* rp[NP][NCH];
+  uint4 r[NP][NCH];
+  int kc, row0;
 
-  __device__ __forceinline__ void init(const Operand& op, int tile_row0) {
-    const int tid = threadIdx.x;
-    kc = (tid % CPR) * EW;
-    row0 = tid / CPR;
-    const int es = F32 ? 4 : 2;
+  __device__ __forceinline__ void init(const PlaneOp& op, int tile_row0) {
+    kc = (threadIdx.x & 7) * 8;
+    row0 = threadIdx.x >> 3;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-      int row = tile_row0 + row0 + i * RSTEP;
+      int row = tile_row0 + row0 + 32 * i;
       row = row < op.rows ? row : op.rows - 1;
-      long long srow = op.idx ? (long long)op.idx[row] : (long long)row;
-      rp[i] = (const char*)op.ptr + srow * op.ld * es;
+      rp[0][i] = op.hi + (long long)row * op.ld;
+      if (NP == 2) rp[NP - 1][i] = op.lo + (long long)row * op.ld;
     }
   }
-
   __device__ __forceinline__ void load(long long k, long long k1) {
-    const int es = F32 ? 4 : 2;
     const long long kk = k + kc;
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      if (kk < k1) {
-        r[i] = *(const uint4*)(rp[i] + kk * es);
-      } else {
-        r[i] = make_uint4(0, 0, 0, 0);
-      }
-    }
-    if (kk < k1 && kk + EW > k1) {  // ragged end of the contraction: zero the elements past k1
+    for (int pl = 0; pl < NP; ++pl)
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) r[pl][i] = (kk < k1) ? *(const uint4*)(rp[pl][i] + kk) : make_uint4(0, 0, 0, 0);
+    if (kk < k1 && kk + 8 > k1) {  // ragged end of the contraction: zero the elements past k1
       const int valid = (int)(k1 - kk);
 #pragma unroll
-      for (int i = 0; i < NCH; ++i) {
-        unsigned int w[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
-        if (F32) {
+      for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (e >= valid) w[e] = 0u;
-        } else {
+        for (int i = 0; i < NCH; ++i) {
+          unsigned int w[4] = {r[pl][i].x, r[pl][i].y, r[pl][i].z, r[pl][i].w};
 #pragma unroll
           for (int e = 0; e < 8; ++e)
             if (e >= valid) w[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+          r[pl][i] = make_uint4(w[0], w[1], w[2], w[3]);
         }
-        r[i] = make_uint4(w[0], w[1], w[2], w[3]);
-      }
     }
   }
-
-  // s0: hi plane (or the only plane), s1: lo plane (OP_F32_2 only)
-  __device__ __forceinline__ void store(unsigned short* s0, unsigned short* s1, int relu) const {
+  __device__ __forceinline__ void store(unsigned short (*s)[BM * LDK]) const {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int row = row0 + i * RSTEP;
-      unsigned short* d0 = s0 + row * LDK + kc;
-      if (KIND == OP_BF16) {
-        *(uint4*)d0 = r[i];
-      } else if (KIND == OP_BF16_H) {
-        unsigned int w[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
-        unsigned int o[4];
+    for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float a = clamp_half_range(bf16_bits_to_float((unsigned short)(w[e] & 0xffffu)));
-          float b = clamp_half_range(bf16_bits_to_float((unsigned short)(w[e] >> 16)));
-          o[e] = pack2(half_bits(a), half_bits(b));
-        }
-        *(uint4*)d0 = make_uint4(o[0], o[1], o[2], o[3]);
-      } else {
-        float v[4] = {__builtin_bit_cast(float, r[i].x), __builtin_bit_cast(float, r[i].y),
-                      __builtin_bit_cast(float, r[i].z), __builtin_bit_cast(float, r[i].w)};
-        if (relu) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = __builtin_fmaxf(v[e], 0.0f);
-        }
-        if (KIND == OP_F32_1) {
-          unsigned short h[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) h[e] = half_bits(clamp_half_range(v[e]));
-          *(uint2*)d0 = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
-        } else {
-          unsigned short h[4], l[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) split_half(v[e], h[e], l[e]);
-          *(uint2*)d0 = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
-          *(uint2*)(s1 + row * LDK + kc) = make_uint2(pack2(l[0], l[1]), pack2(l[2], l[3]));
-        }
-      }
-    }
+      for (int i = 0; i < NCH; ++i) *(uint4*)(&s[pl][(row0 + 32 * i) * LDK + kc]) = r[pl][i];
   }
 };
 
-// ---------------------------------------------------------------------------------------------
-// Token-parallel Q tile: source is [K rows][N contiguous]; each thread loads an 8(k) x 2(n) patch and
-// writes it transposed, so the LDS image is the same [n][k] layout the token-contraction form uses.
-// ---------------------------------------------------------------------------------------------
-template <int KIND>
-struct NnTile {
-  static constexpr bool F32 = kind_is_f32(KIND);
-  uint2 r[8];
-  int ng, kg;
-  long long ncol;   // global column of this thread's first element
+// K8 plane tile: chunk (kg, n) of the tile is the 16 bytes at ((k/8 + kg) * ld + n0 + n) * 8 elements
+template <int NP>
+struct K8Loader {
+  uint4 r[NP][NCH];
+  int n, kg0;
+  long long ncol;
   bool nvalid;
 
-  __device__ __forceinline__ void init(const Operand& op, int n0, int N) {
-    ng = threadIdx.x & 63;
-    kg = threadIdx.x >> 6;
-    ncol = (long long)n0 + 2 * ng;
+  __device__ __forceinline__ void init(const PlaneOp& op, int n0, int N) {
+    n = threadIdx.x & 127;
+    kg0 = threadIdx.x >> 7;
+    ncol = (long long)n0 + n;
     nvalid = ncol < N;
   }
-
-  __device__ __forceinline__ void load(const Operand& op, long long k, long long k1) {
-    const int es = F32 ? 4 : 2;
+  __device__ __forceinline__ void load(const PlaneOp& op, long long k, long long k1) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const long long kk = k + kg * 8 + i;
-      if (kk < k1 && nvalid) {
-        long long srow = op.idx ? (long long)op.idx[kk] : kk;
-        const char* src = (const char*)op.ptr + (srow * op.ld + ncol) * es;
-        if (F32) {
-          r[i] = *(const uint2*)src;
-        } else {
-          r[i].x = *(const unsigned int*)src;
-          r[i].y = 0;
-        }
-      } else {
-        r[i] = make_uint2(0, 0);
+    for (int pl = 0; pl < NP; ++pl) {
+      const unsigned short* base = pl == 0 ? op.hi : op.lo;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const long long kk = k + (kg0 + 2 * i) * 8;
+        r[pl][i] = (kk < k1 && nvalid) ? *(const uint4*)(base + ((kk >> 3) * op.ld + ncol) * 8) : make_uint4(0, 0, 0, 0);
       }
     }
   }
-
-  __device__ __forceinline__ void store(unsigned short* s0, unsigned short* s1, int relu) const {
+  __device__ __forceinline__ void store(unsigned short (*s)[BN * LDK]) const {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      unsigned short h[8], l[8];
+    for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        if (F32) {
-          float v = __builtin_bit_cast(float, j == 0 ? r[i].x : r[i].y);
-          if (relu) v = __builtin_fmaxf(v, 0.0f);
-          if (KIND == OP_F32_2) {
-            split_half(v, h[i], l[i]);
-          } else {
-            h[i] = half_bits(clamp_half_range(v));
-          }
-        } else {
-          unsigned short b = (unsigned short)(j == 0 ? (r[i].x & 0xffffu) : (r[i].x >> 16));
-          h[i] = (KIND == OP_BF16) ? b : half_bits(clamp_half_range(bf16_bits_to_float(b)));
-        }
-      }
-      const int off = (2 * ng + j) * LDK + kg * 8;
-      *(uint4*)(s0 + off) = make_uint4(pack2(h[0], h[1]), pack2(h[2], h[3]), pack2(h[4], h[5]), pack2(h[6], h[7]));
-      if (KIND == OP_F32_2)
-        *(uint4*)(s1 + off) = make_uint4(pack2(l[0], l[1]), pack2(l[2], l[3]), pack2(l[4], l[5]), pack2(l[6], l[7]));
-    }
+      for (int i = 0; i < NCH; ++i) *(uint4*)(&s[pl][n * LDK + (kg0 + 2 * i) * 8]) = r[pl][i];
   }
 };
 
@@ -225,11 +135,8 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
-template <int KP, int KQ, bool NN>
+template <int NPP, int NPQ, bool NN, bool BF>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
-  constexpr int NPP = kind_planes(KP), NPQ = kind_planes(KQ);
-  constexpr bool BF = (KP == OP_BF16);
-  constexpr bool CROSS = (NPP == 2 || NPQ == 2);
   __shared__ __attribute__((aligned(16))) unsigned short sP[NPP][BM * LDK];
   __shared__ __attribute__((aligned(16))) unsigned short sQ[NPQ][BN * LDK];
   __shared__ double sred[4][2];
@@ -262,38 +169,31 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 
-  KcTile<KP> lp;
+  RowLoader<NPP> lp;
   lp.init(p.P, m0);
-  KcTile<KQ> lq_kc;
-  NnTile<KQ> lq_nn;
-  if (NN) {
-    lq_nn.init(p.Q, n0, p.N);
-  } else {
-    lq_kc.init(p.Q, n0);
-  }
+  RowLoader<NPQ> lq_row;
+  K8Loader<NPQ> lq_k8;
+  if (NN) lq_k8.init(p.Q, n0, p.N); else lq_row.init(p.Q, n0);
 
-  floatx16 acc[2][2], acx[2][2];
+  floatx16 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        acc[i][j][e] = 0.0f;
-        acx[i][j][e] = 0.0f;
-      }
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
   if (k0 < k1) {
     lp.load(k0, k1);
-    if (NN) lq_nn.load(p.Q, k0, k1); else lq_kc.load(k0, k1);
+    if (NN) lq_k8.load(p.Q, k0, k1); else lq_row.load(k0, k1);
   }
   for (long long k = k0; k < k1; k += BK) {
-    lp.store(sP[0], sP[NPP - 1], p.P.relu);
-    if (NN) lq_nn.store(sQ[0], sQ[NPQ - 1], p.Q.relu); else lq_kc.store(sQ[0], sQ[NPQ - 1], p.Q.relu);
+    lp.store(sP);
+    if (NN) lq_k8.store(sQ); else lq_row.store(sQ);
     __syncthreads();
     if (k + BK < k1) {  // next tile's global loads fly during the matrix work
       lp.load(k + BK, k1);
-      if (NN) lq_nn.load(p.Q, k + BK, k1); else lq_kc.load(k + BK, k1);
+      if (NN) lq_k8.load(p.Q, k + BK, k1); else lq_row.load(k + BK, k1);
     }
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
@@ -315,72 +215,98 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
+          if (NPQ == 2) acc[i][j] = mma<BF>(ph[i], ql[j], acc[i][j]);
+          if (NPP == 2) acc[i][j] = mma<BF>(pl[i], qh[j], acc[i][j]);
           acc[i][j] = mma<BF>(ph[i], qh[j], acc[i][j]);
-          if (NPQ == 2) acx[i][j] = mma<BF>(ph[i], ql[j], acx[i][j]);
-          if (NPP == 2) acx[i][j] = mma<BF>(pl[i], qh[j], acx[i][j]);
         }
     }
     __syncthreads();
   }
 
   // ---- epilogue -----------------------------------------------------------------------------
+  float unscale = 1.0f;
+  if (p.P.scale) unscale /= *p.P.scale;
+  if (p.Q.scale) unscale /= *p.Q.scale;
   double red0 = 0.0, red1 = 0.0;
   const float ab = p.alpha + p.beta;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 2; ++j) {
+      const int n = n0 + wn * 64 + j * 32 + (lane & 31);
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int m = m0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        const int n = n0 + wn * 64 + j * 32 + (lane & 31);
-        if (m >= p.M || n >= p.N) continue;
-        float v = acc[i][j][e];
-        if (CROSS) v += acx[i][j][e] * (1.0f / LO_SCALE);
-        switch (p.epi) {
-          case EPI_PARTIAL:
-            p.out[((long long)split * p.M + m) * p.N + n] = v;
-            break;
-          case EPI_STORE:
-            p.out[(long long)m * p.ldo + n] = v;
-            break;
-          case EPI_INITZ: {
-            const long long o = (long long)m * p.lda + n;
-            const float a = __builtin_fmaxf(v, 0.0f);
-            p.Z0s[o] = v;
-            p.Zs[o] = v;
-            p.As[o] = a;
-            red0 += (double)a * (double)a;
-          } break;
-          case EPI_RESID: {
-            const float r = p.Yin[(long long)m * p.ldy + n] - v;
-            if (p.write_out) p.out[(long long)m * p.ldo + n] = r;
-            red0 += (double)r * (double)r;
-          } break;
-          case EPI_AUPD: {
-            const long long o = (long long)p.oidx[m] * p.lda + n;
-            p.As[o] = __builtin_fmaxf(p.Zs[o], 0.0f) + v;
-          } break;
-          case EPI_ZUPD: {
-            const long long o = (long long)p.oidx[m] * p.lda + n;
-            const float a = p.As[o];
-            const float z1 = v;
-            const float z2 = (p.beta * a + p.alpha * z1) / ab;
-            const float cm = __builtin_fminf(z1, 0.0f);
-            const float costm = p.beta * a * a + p.alpha * (cm - z1) * (cm - z1);
-            const float cp = __builtin_fmaxf(z2, 0.0f);
-            const float costp = p.beta * (a - cp) * (a - cp) + p.alpha * (cp - z1) * (cp - z1);
-            const float z = costm < costp ? cm : cp;
-            p.Zs[o] = z;
-            const float ra = a - __builtin_fmaxf(z, 0.0f);
-            const float rz = z - z1;
-            red0 += (double)ra * (double)ra;
-            red1 += (double)rz * (double)rz;
-          } break;
-          default:
-            break;
+      for (int q = 0; q < 4; ++q) {
+        const int mq = m0 + wm * 64 + i * 32 + 8 * q + 4 * (lane >> 5);  // rows mq .. mq+3
+        float outv[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int m = mq + r;
+          float v = acc[i][j][4 * q + r] * unscale;
+          outv[r] = 0.0f;
+          if (m >= p.M || n >= p.N) continue;
+          switch (p.epi) {
+            case EPI_PARTIAL:
+              p.out[((long long)split * p.M + m) * p.N + n] = v;
+              break;
+            case EPI_STORE:
+              p.out[(long long)m * p.ldo + n] = v;
+              outv[r] = v;
+              break;
+            case EPI_INITZ: {
+              const long long o = (long long)m * p.lda + n;
+              const float a = __builtin_fmaxf(v, 0.0f);
+              p.Z0s[o] = v;
+              p.Zs[o] = v;
+              p.As[o] = a;
+              outv[r] = a;
+              red0 += (double)a * (double)a;
+            } break;
+            case EPI_RESID: {
+              const float rr = p.Yin[(long long)m * p.ldy + n] - v;
+              outv[r] = rr;
+              red0 += (double)rr * (double)rr;
+            } break;
+            case EPI_AUPD: {
+              const long long o = (long long)p.oidx[m] * p.lda + n;
+              p.As[o] = __builtin_fmaxf(p.Zs[o], 0.0f) + v;
+            } break;
+            case EPI_ZUPD: {
+              const long long o = (long long)p.oidx[m] * p.lda + n;
+              const float a = p.As[o];
+              const float z1 = v;
+              float z;
+              if (p.write_out) {
+                const float z2 = (p.beta * a + p.alpha * z1) / ab;
+                const float cm = __builtin_fminf(z1, 0.0f);
+                const float costm = p.beta * a * a + p.alpha * (cm - z1) * (cm - z1);
+                const float cp = __builtin_fmaxf(z2, 0.0f);
+                const float costp = p.beta * (a - cp) * (a - cp) + p.alpha * (cp - z1) * (cp - z1);
+                z = costm < costp ? cm : cp;
+                p.Zs[o] = z;
+              } else {
+                z = p.Zs[o];
+              }
+              const float ra = a - __builtin_fmaxf(z, 0.0f);
+              const float rz = z - z1;
+              red0 += (double)ra * (double)ra;
+              red1 += (double)rz * (double)rz;
+            } break;
+            default:
+              break;
+          }
+        }
+        // optional K8-plane copy of the produced tile (its rows are the k axis of the consumer):
+        // this lane's four rows are half of one 16-byte chunk; rows >= M inside a chunk are zeros
+        if (p.k8_hi && n < p.N && mq < p.M) {
+          unsigned short h[4], l[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) split_half(outv[r], h[r], l[r]);
+          const long long o = ((long long)(mq >> 3) * p.k8_ld + n) * 8 + (mq & 7);
+          *(uint2*)(p.k8_hi + o) = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
+          if (p.k8_lo) *(uint2*)(p.k8_lo + o) = make_uint2(pack2(l[0], l[1]), pack2(l[2], l[3]));
         }
       }
+    }
   if (p.red) {
     red0 = wave_sum(red0);
     red1 = wave_sum(red1);
@@ -416,44 +342,45 @@ void gemm_plan_tiles(GemmP& p, bool nn, int want_splits) {
 
 int gemm_grid_blocks(const GemmP& p) { return p.ntiles * p.splits; }
 
-template <int KP, int KQ, bool NN>
+template <int NPP, int NPQ, bool NN, bool BF>
 static void launch_one(strp_ctx* ctx, const GemmP& p) {
-  hipLaunchKernelGGL((gemm_kernel<KP, KQ, NN>), dim3(gemm_grid_blocks(p)), dim3(256), 0, ctx->stream, p);
+  hipLaunchKernelGGL((gemm_kernel<NPP, NPQ, NN, BF>), dim3(gemm_grid_blocks(p)), dim3(256), 0, ctx->stream, p);
 }
 
-strp_status launch_gemm(strp_ctx* ctx, GemmP& p, int kp, int kq, bool nn) {
+strp_status launch_gemm(strp_ctx* ctx, GemmP& p, bool nn, bool bf16) {
   if (p.M <= 0 || p.N <= 0 || p.K <= 0) return fail(ctx, STRP_EINVAL, "gemm: empty shape");
   if (p.ntiles <= 0 || p.splits <= 0) return fail(ctx, STRP_EINVAL, "gemm: tiles not planned");
-  if ((kp == OP_BF16) != (kq == OP_BF16)) return fail(ctx, STRP_EINVAL, "gemm: bf16 cores need both operands bf16");
-  const int key = (nn ? 100 : 0) + kp * 10 + kq;
+  if (!p.P.hi || !p.Q.hi) return fail(ctx, STRP_EINVAL, "gemm: null operand plane");
+  if ((p.M % 8) && p.k8_hi) return fail(ctx, STRP_EINVAL, "gemm: K8 output needs M %% 8 == 0");
+  const int npp = p.P.lo ? 2 : 1, npq = p.Q.lo ? 2 : 1;
+  if (bf16 && (npp != 1 || npq != 1 || nn)) return fail(ctx, STRP_EINVAL, "gemm: bf16 cores take single ROW planes only");
   static const char* const epi_names[] = {"partial", "store", "initz", "resid", "aupd", "zupd"};
-  static char names[2][4][4][6][40];
-  char* name = names[nn ? 1 : 0][kp][kq][p.epi];
-  if (!name[0]) snprintf(name, 40, "gemm_%s_p%d_q%d_%s", nn ? "nn" : "nt", kp, kq, epi_names[p.epi]);
+  static char names[2][2][3][3][6][40];
+  char* name = names[nn ? 1 : 0][bf16 ? 1 : 0][npp][npq][p.epi];
+  if (!name[0]) snprintf(name, 40, "gemm_%s_%s%dx%d_%s", nn ? "nn" : "nt", bf16 ? "bf" : "h", npp, npq, epi_names[p.epi]);
   const double mn = p.triangle ? 0.5 * (double)p.M * ((double)p.M + 1.0) : (double)p.M * (double)p.N;
-  const double esp = (kp == OP_BF16 || kp == OP_BF16_H) ? 2.0 : 4.0, esq = (kq == OP_BF16 || kq == OP_BF16_H) ? 2.0 : 4.0;
   static const double out_words[] = {1.0, 1.0, 3.0, 2.0, 2.0, 2.0};
   double obytes = 4.0 * out_words[p.epi] * (double)p.M * (double)p.N * (p.epi == EPI_PARTIAL ? (double)p.splits : 1.0);
-  if (p.epi == EPI_RESID && !p.write_out) obytes *= 0.5;
-  const double ibytes = p.triangle ? esp * (double)p.M * (double)p.K : esp * (double)p.M * (double)p.K + esq * (double)p.N * (double)p.K;
+  if (p.epi == EPI_RESID) obytes *= 0.5;
+  if (p.k8_hi) obytes += (p.k8_lo ? 4.0 : 2.0) * (double)p.M * (double)p.N;
+  const double ibytes = p.triangle ? 2.0 * npp * (double)p.M * (double)p.K
+                                   : 2.0 * npp * (double)p.M * (double)p.K + 2.0 * npq * (double)p.N * (double)p.K;
   ProfScope ps(ctx, name, 2.0 * mn * (double)p.K, ibytes + obytes);
-  switch (key) {
-    case 0: launch_one<OP_BF16, OP_BF16, false>(ctx, p); break;
-    case 11: launch_one<OP_F32_1, OP_F32_1, false>(ctx, p); break;
-    case 22: launch_one<OP_F32_2, OP_F32_2, false>(ctx, p); break;
-    case 13: launch_one<OP_F32_1, OP_BF16_H, false>(ctx, p); break;
-    case 23: launch_one<OP_F32_2, OP_BF16_H, false>(ctx, p); break;
-    case 31: launch_one<OP_BF16_H, OP_F32_1, false>(ctx, p); break;
-    case 32: launch_one<OP_BF16_H, OP_F32_2, false>(ctx, p); break;
-    case 100: launch_one<OP_BF16, OP_BF16, true>(ctx, p); break;
-    case 111: launch_one<OP_F32_1, OP_F32_1, true>(ctx, p); break;
-    case 122: launch_one<OP_F32_2, OP_F32_2, true>(ctx, p); break;
-    case 113: launch_one<OP_F32_1, OP_BF16_H, true>(ctx, p); break;
-    case 123: launch_one<OP_F32_2, OP_BF16_H, true>(ctx, p); break;
-    case 131: launch_one<OP_BF16_H, OP_F32_1, true>(ctx, p); break;
-    case 132: launch_one<OP_BF16_H, OP_F32_2, true>(ctx, p); break;
-    default:
-      return fail(ctx, STRP_EINVAL, "gemm: operand kind combination %d/%d not built", kp, kq);
+  const int key = (nn ? 100 : 0) + npp * 10 + npq;
+  if (bf16) {
+    launch_one<1, 1, false, true>(ctx, p);
+  } else {
+    switch (key) {
+      case 11: launch_one<1, 1, false, false>(ctx, p); break;
+      case 12: launch_one<1, 2, false, false>(ctx, p); break;
+      case 21: launch_one<2, 1, false, false>(ctx, p); break;
+      case 22: launch_one<2, 2, false, false>(ctx, p); break;
+      case 111: launch_one<1, 1, true, false>(ctx, p); break;
+      case 112: launch_one<1, 2, true, false>(ctx, p); break;
+      case 121: launch_one<2, 1, true, false>(ctx, p); break;
+      case 122: launch_one<2, 2, true, false>(ctx, p); break;
+      default: return fail(ctx, STRP_EINVAL, "gemm: plane combination %d not built", key);
+    }
   }
   STRP_HIP(ctx, hipGetLastError());
   return STRP_OK;
@@ -516,6 +443,172 @@ __global__ __launch_bounds__(256) void block_sum_kernel(const double* red, int n
 strp_status launch_block_sum(strp_ctx* ctx, const double* red, int nblocks, double* dst0, double* dst1,
                              double scale0, double scale1) {
   hipLaunchKernelGGL(block_sum_kernel, dim3(1), dim3(256), 0, ctx->stream, red, nblocks, dst0, dst1, scale0, scale1);
+  STRP_HIP(ctx, hipGetLastError());
+  return STRP_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// split kernels: fp32 / bf16 / fp64 sources -> fp16 planes
+// ---------------------------------------------------------------------------------------------
+// Activations: a block converts one group of 8 (gathered) rows x 1024 tokens; each thread 8 rows x 4 tokens.
+//   ROW planes  [rows8][ld_row]         (token-contiguous; padding columns zero up to ld_row)
+//   K8  planes  [(rows8/8)][T][8]       (relu applied when relu_k8 != 0)
+// Rows >= rows inside the last group are written as zeros.
+template <bool SRC_BF16>
+__global__ __launch_bounds__(256) void split_rows_kernel(const void* src, long long lds, const int* idx, int rows, long long T,
+                                                         int relu_row, int relu_k8, unsigned short* row_hi, unsigned short* row_lo,
+                                                         long long ld_row, unsigned short* k8_hi, unsigned short* k8_lo) {
+  const int g = blockIdx.y;
+  const long long t0 = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
+  const long long cols = row_hi ? ld_row : T;
+  if (t0 >= cols) return;
+  float v[8][4];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const int row = g * 8 + r;
+    v[r][0] = v[r][1] = v[r][2] = v[r][3] = 0.0f;
+    if (row < rows && t0 < T) {
+      const long long srow = idx ? (long long)idx[row] : (long long)row;
+      if (SRC_BF16) {
+        const uint2 w = *(const uint2*)((const unsigned short*)src + srow * lds + t0);
+        v[r][0] = __builtin_bit_cast(float, w.x << 16);
+        v[r][1] = __builtin_bit_cast(float, w.x & 0xffff0000u);
+        v[r][2] = __builtin_bit_cast(float, w.y << 16);
+        v[r][3] = __builtin_bit_cast(float, w.y & 0xffff0000u);
+      } else {
+        const float4 w = *(const float4*)((const float*)src + srow * lds + t0);
+        v[r][0] = w.x; v[r][1] = w.y; v[r][2] = w.z; v[r][3] = w.w;
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (t0 + c >= T) v[r][c] = 0.0f;
+    }
+  }
+  if (row_hi) {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      unsigned short h[4], l[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) split_half(relu_row ? __builtin_fmaxf(v[r][c], 0.0f) : v[r][c], h[c], l[c]);
+      const long long o = (long long)(g * 8 + r) * ld_row + t0;
+      *(uint2*)(row_hi + o) = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
+      if (row_lo) *(uint2*)(row_lo + o) = make_uint2(pack2(l[0], l[1]), pack2(l[2], l[3]));
+    }
+  }
+  if (k8_hi) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if (t0 + c >= T) continue;
+      unsigned short h[8], l[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) split_half(relu_k8 ? __builtin_fmaxf(v[r][c], 0.0f) : v[r][c], h[r], l[r]);
+      const long long o = ((long long)g * T + t0 + c) * 8;
+      *(uint4*)(k8_hi + o) = make_uint4(pack2(h[0], h[1]), pack2(h[2], h[3]), pack2(h[4], h[5]), pack2(h[6], h[7]));
+      if (k8_lo) *(uint4*)(k8_lo + o) = make_uint4(pack2(l[0], l[1]), pack2(l[2], l[3]), pack2(l[4], l[5]), pack2(l[6], l[7]));
+    }
+  }
+}
+
+strp_status split_rows(strp_ctx* ctx, const void* src, int src_dtype, long long lds, const int* idx, int rows, long long T,
+                       int relu_row, int relu_k8, unsigned short* row_hi, unsigned short* row_lo, long long ld_row,
+                       unsigned short* k8_hi, unsigned short* k8_lo) {
+  if (rows <= 0 || T <= 0) return fail(ctx, STRP_EINVAL, "split_rows: empty");
+  if (row_hi && (ld_row < T || ld_row % 8)) return fail(ctx, STRP_EINVAL, "split_rows: bad plane pitch");
+  const long long cols = row_hi ? ld_row : T;
+  dim3 grid((unsigned)((cols + 1023) / 1024), (unsigned)((rows + 7) / 8));
+  const double es = src_dtype == STRP_BF16 ? 2.0 : 4.0;
+  const double wb = (row_hi ? 2.0 : 0.0) + (row_lo ? 2.0 : 0.0) + (k8_hi ? 2.0 : 0.0) + (k8_lo ? 2.0 : 0.0);
+  ProfScope ps(ctx, "split_rows", 0.0, (es + wb) * (double)rows * (double)T);
+  if (src_dtype == STRP_BF16)
+    hipLaunchKernelGGL((split_rows_kernel<true>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_row, relu_k8,
+                       row_hi, row_lo, ld_row, k8_hi, k8_lo);
+  else
+    hipLaunchKernelGGL((split_rows_kernel<false>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_row, relu_k8,
+                       row_hi, row_lo, ld_row, k8_hi, k8_lo);
+  STRP_HIP(ctx, hipGetLastError());
+  return STRP_OK;
+}
+
+// Small matrices (weights): ROW planes [rows][ldp] of src * scale, zero padded to ldp.  transpose != 0 reads src[c][r].
+// scale_dev (device, may be null = 1) is a power of two chosen by weight_scale_kernel.
+__device__ __forceinline__ double small_src(const double* s, long long i) { return s[i]; }
+__device__ __forceinline__ double small_src(const float* s, long long i) { return (double)s[i]; }
+__device__ __forceinline__ double small_src(const unsigned short* s, long long i) {
+  return (double)__builtin_bit_cast(float, (unsigned int)s[i] << 16);
+}
+
+template <typename TS>
+__global__ __launch_bounds__(256) void split_small_kernel(const TS* src, long long lds, int rows, int cols, int transpose,
+                                                          const float* scale_dev, unsigned short* hi, unsigned short* lo, long long ldp) {
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (long long)rows * ldp) return;
+  const int r = (int)(e / ldp), c = (int)(e % ldp);
+  double x = 0.0;
+  if (c < cols) x = transpose ? small_src(src, (long long)c * lds + r) : small_src(src, (long long)r * lds + c);
+  x *= scale_dev ? (double)*scale_dev : 1.0;
+  x = fmin(fmax(x, -65504.0), 65504.0);
+  const _Float16 h = (_Float16)x;
+  hi[e] = __builtin_bit_cast(unsigned short, h);
+  if (lo) {
+    const _Float16 l = (_Float16)(x - (double)h);
+    lo[e] = __builtin_bit_cast(unsigned short, l);
+  }
+}
+
+strp_status split_small(strp_ctx* ctx, const void* src, int src_kind, long long lds, int rows, int cols, int transpose,
+                        const float* scale_dev, unsigned short* hi, unsigned short* lo, long long ldp) {
+  const long long tot = (long long)rows * ldp;
+  dim3 grid((unsigned)((tot + 255) / 256)), block(256);
+  if (src_kind == SRC_F64)
+    hipLaunchKernelGGL((split_small_kernel<double>), grid, block, 0, ctx->stream, (const double*)src, lds, rows, cols, transpose, scale_dev, hi, lo, ldp);
+  else if (src_kind == SRC_F32)
+    hipLaunchKernelGGL((split_small_kernel<float>), grid, block, 0, ctx->stream, (const float*)src, lds, rows, cols, transpose, scale_dev, hi, lo, ldp);
+  else
+    hipLaunchKernelGGL((split_small_kernel<unsigned short>), grid, block, 0, ctx->stream, (const unsigned short*)src, lds, rows, cols, transpose, scale_dev, hi, lo, ldp);
+  STRP_HIP(ctx, hipGetLastError());
+  return STRP_OK;
+}
+
+// scale = 2^e with max|x| * scale in [2^11, 2^12): keeps fp16 hi far from overflow and lo out of the subnormals.
+// Pass 1: grid-wide max of |x| through an integer atomic on the float bits (order-preserving for x >= 0).
+template <typename TS>
+__global__ __launch_bounds__(256) void absmax_kernel(const TS* src, long long lds, int rows, int cols, unsigned int* slot) {
+  float m = 0.0f;
+  const long long n = (long long)rows * cols;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+    const long long r = i / cols, c = i % cols;
+    m = __builtin_fmaxf(m, __builtin_fabsf((float)small_src(src, r * lds + c)));
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = __builtin_fmaxf(m, __shfl_down(m, o, 64));
+  if ((threadIdx.x & 63) == 0 && m > 0.0f) atomicMax(slot, __builtin_bit_cast(unsigned int, m));
+}
+// Pass 2: the slot (max bits) becomes the scale (float) in place.
+__global__ void scale_from_max_kernel(unsigned int* slot) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const float m = __builtin_bit_cast(float, *slot);
+  float s = 1.0f;
+  if (m > 0.0f && m < 3.0e38f) {
+    int e;
+    (void)frexpf(m, &e);        // m = q * 2^e, q in [0.5, 1)
+    s = ldexpf(1.0f, 12 - e);   // m * s in [2^11, 2^12)
+  }
+  *slot = __builtin_bit_cast(unsigned int, s);
+}
+
+strp_status weight_scale(strp_ctx* ctx, const void* src, int src_kind, long long lds, int rows, int cols, float* scale_out) {
+  STRP_TRY(fill_zero(ctx, scale_out, 4));
+  unsigned int* slot = (unsigned int*)scale_out;
+  long long blocks = ((long long)rows * cols + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  dim3 grid((unsigned)blocks), block(256);
+  if (src_kind == SRC_F64)
+    hipLaunchKernelGGL((absmax_kernel<double>), grid, block, 0, ctx->stream, (const double*)src, lds, rows, cols, slot);
+  else if (src_kind == SRC_F32)
+    hipLaunchKernelGGL((absmax_kernel<float>), grid, block, 0, ctx->stream, (const float*)src, lds, rows, cols, slot);
+  else
+    hipLaunchKernelGGL((absmax_kernel<unsigned short>), grid, block, 0, ctx->stream, (const unsigned short*)src, lds, rows, cols, slot);
+  hipLaunchKernelGGL(scale_from_max_kernel, dim3(1), dim3(1), 0, ctx->stream, slot);
   STRP_HIP(ctx, hipGetLastError());
   return STRP_OK;
 }

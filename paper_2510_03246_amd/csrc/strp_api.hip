@@ -58,47 +58,6 @@ strp_status fail(strp_ctx* ctx, strp_status st, const char* fmt, ...) {
 static inline long long round_up(long long x, long long a) { return (x + a - 1) / a * a; }
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
-static int kind_of(int dtype, int other_dtype, int prec) {
-  if (dtype == STRP_BF16) return other_dtype == STRP_BF16 ? OP_BF16 : OP_BF16_H;
-  return prec == STRP_PREC_SPLIT ? OP_F32_2 : OP_F32_1;
-}
-
-// number of K splits of a token-contraction product: enough blocks to fill the chip and fp32
-// accumulation chains of at most 8192 tokens (partials are then summed in fp64)
-static int plan_splits(int ntiles, long long K) {
-  long long s_chain = (K + 8191) / 8192;
-  long long s_fill = (1024 + ntiles - 1) / ntiles;
-  long long s = s_chain > s_fill ? s_chain : s_fill;
-  long long s_max = K / 256 > 1 ? K / 256 : 1;
-  if (s > s_max) s = s_max;
-  return (int)s;
-}
-
-static size_t nt_partial_elems(int M, int N, long long K, int triangle) {
-  GemmP p;
-  memset(&p, 0, sizeof(p));
-  p.M = M; p.N = N; p.K = K; p.triangle = triangle;
-  gemm_plan_tiles(p, false, 1);
-  gemm_plan_tiles(p, false, plan_splits(p.ntiles, K));
-  return (size_t)p.splits * (size_t)M * (size_t)N;
-}
-
-// C = P Q^T over K (both operands K-contiguous); partials in the arena, fp64 reduction.
-static strp_status nt_product(strp_ctx* ctx, Arena arena, const Operand& P, int kp, const Operand& Q, int kq, int M, int N,
-                              long long K, int triangle, float* outf, long long ldof, double* outd, long long ldod,
-                              double* diag, int accumulate) {
-  GemmP p;
-  memset(&p, 0, sizeof(p));
-  p.P = P; p.Q = Q; p.M = M; p.N = N; p.K = K; p.triangle = triangle;
-  p.epi = EPI_PARTIAL;
-  gemm_plan_tiles(p, false, 1);
-  gemm_plan_tiles(p, false, plan_splits(p.ntiles, K));
-  STRP_TAKE(ctx, arena, part, float, (size_t)p.splits * M * N);
-  p.out = part;
-  STRP_TRY(launch_gemm(ctx, p, kp, kq, false));
-  return launch_splitk_reduce(ctx, part, p.splits, M, N, triangle, outf, ldof, outd, ldod, diag, accumulate);
-}
-
 // ---- small kernels ------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void add_diag_kernel(double* A, long long ld, int n, double lam, const double* lam_dev) {
   const int i = blockIdx.x * 256 + threadIdx.x;
@@ -365,55 +324,6 @@ strp_status strp_poll(strp_ctx* ctx) {
   return (strp_status)st;
 }
 
-size_t strp_workspace_bytes(const strp_module_desc* desc) {
-  if (!desc || desc->d <= 0 || desc->f <= 0 || desc->T <= 0) return 0;
-  const size_t d = desc->d, f = desc->f;
-  const size_t km = desc->k_max > 0 ? (size_t)desc->k_max : f;
-  const size_t kp = (size_t)round_up((long long)km, 8);
-  const long long T = desc->T;
-  size_t part = 0;
-  auto upd = [&](size_t e) { if (e > part) part = e; };
-  upd(nt_partial_elems((int)km, (int)km, T, 1));
-  upd(nt_partial_elems((int)d, (int)km, T, 0));
-  upd(nt_partial_elems((int)km, (int)d, T, 0));
-  upd(nt_partial_elems((int)d, (int)d, T, 1));
-  upd(nt_partial_elems((int)d, (int)d, (long long)kp, 1));
-  const size_t nmax = km > d ? km : d;
-  size_t tot = 256;
-  auto add = [&](size_t bytes) { tot += (bytes + 255) & ~size_t(255); };
-  add(part * 4);                                   // split-K partials
-  add(nmax * nmax * 8);                            // fp64 system matrix / factor
-  add(((nmax + NB - 1) / NB) * NB * NB * 8);       // diagonal block inverses
-  add(((d + NB - 1) / NB) * NB * NB * 8);          // same for the cached factor of H
-  add(d * km * 8);                                 // fp64 right-hand side / solution
-  add(d * d * 8);                                  // fp64 M = (beta/alpha) I + W W^T
-  add(d * kp * 4);                                 // compact fc2  [d x kp]
-  add(km * d * 4);                                 // compact fc1  [k x d]
-  add(km * d * 4);                                 // B = W^T M^-1 [k x d]
-  add(d * (size_t)desc->lda * 4);                  // E = Y - W2 relu(Z_S)
-  add(4 * f * 8);                                  // token sums
-  size_t tilesT = (size_t)((T + 127) / 128);
-  size_t nn_blocks = ((f + 127) / 128) * tilesT;
-  add((nn_blocks > f ? nn_blocks : f) * 16 + 4096); // per-block partial sums
-  return tot + 4096;
-}
-
-strp_status strp_gram(strp_ctx* ctx, const void* A, strp_dtype dt, int32_t C, int64_t T, int64_t ldA, const int32_t* idx,
-                      int32_t s, float* G, int32_t ldG, double* diag, int accumulate) {
-  if (!ctx) return STRP_EINVAL;
-  if (!A || !G) return fail(ctx, STRP_EINVAL, "gram: null A or G");
-  if (dt != STRP_BF16 && dt != STRP_F32) return fail(ctx, STRP_EINVAL, "gram: unknown dtype");
-  if (C <= 0 || s <= 0 || s > C || T <= 0) return fail(ctx, STRP_EINVAL, "gram: need 0 < s <= C and T > 0");
-  if (!idx && s != C) return fail(ctx, STRP_EINVAL, "gram: idx == NULL requires s == C");
-  if (ldA < T || ldA % 8 || ldG < s) return fail(ctx, STRP_EINVAL, "gram: bad leading dimension");
-  if (!aligned16(A)) return fail(ctx, STRP_EINVAL, "gram: A not 16-byte aligned");
-  if (!ctx->ws) return fail(ctx, STRP_ENOMEM, "gram: no workspace set");
-  Arena arena(ctx);
-  Operand op = {A, (long long)ldA, idx, s, 0};
-  const int kind = kind_of(dt, dt, ctx->precision);
-  return nt_product(ctx, arena, op, kind, op, kind, s, s, T, 1, G, ldG, nullptr, 0, diag, accumulate);
-}
-
 strp_status strp_score_alloc(strp_ctx* ctx, const strp_score_in* in, float* unit_score, double* energies, int32_t layer_idx,
                              int32_t L, const int32_t* n_units, const int32_t* group_id, double rbar, double temperature,
                              double rmax, double* r_out, int32_t* nprune_out) {
@@ -455,14 +365,97 @@ strp_status strp_mask_topk(strp_ctx* ctx, const float* score, int32_t n, int32_t
 
 namespace strp {
 
+static inline int planes_for(int dtype, int prec) { return (dtype == STRP_F32 && prec == STRP_PREC_SPLIT) ? 2 : 1; }
+
+// ROW planes of `rows` (optionally gathered) activation rows, carved from the arena.
+static strp_status make_row_planes(strp_ctx* ctx, Arena& arena, const void* src, int dtype, long long lds, const int* idx, int rows,
+                                   long long T, int relu, int np, PlaneOp* out) {
+  const long long rows8 = round_up(rows, 8), ldp = round_up(T, 8);
+  STRP_TAKE(ctx, arena, hi, unsigned short, (size_t)rows8 * ldp);
+  unsigned short* lo = nullptr;
+  if (np == 2) {
+    STRP_TAKE(ctx, arena, lo2, unsigned short, (size_t)rows8 * ldp);
+    lo = lo2;
+  }
+  STRP_TRY(split_rows(ctx, src, dtype, lds, idx, rows, T, relu, 0, hi, lo, ldp, nullptr, nullptr));
+  *out = PlaneOp{hi, lo, ldp, (int)rows8, nullptr};
+  return STRP_OK;
+}
+
+// K8 planes of `rows` (optionally gathered) activation rows: the rows are the contraction axis of the consumer.
+static strp_status make_k8_planes(strp_ctx* ctx, Arena& arena, const void* src, int dtype, long long lds, const int* idx, int rows,
+                                  long long T, int relu, int np, PlaneOp* out) {
+  const long long rows8 = round_up(rows, 8);
+  STRP_TAKE(ctx, arena, hi, unsigned short, (size_t)rows8 * T);
+  unsigned short* lo = nullptr;
+  if (np == 2) {
+    STRP_TAKE(ctx, arena, lo2, unsigned short, (size_t)rows8 * T);
+    lo = lo2;
+  }
+  STRP_TRY(split_rows(ctx, src, dtype, lds, idx, rows, T, 0, relu, nullptr, nullptr, 0, hi, lo));
+  *out = PlaneOp{hi, lo, T, 0, nullptr};
+  return STRP_OK;
+}
+
+// ROW planes [rows][round_up(cols, 8)] of a small matrix (weights), scaled by a device-chosen power of two.
+static strp_status make_weight_planes(strp_ctx* ctx, Arena& arena, const void* src, int src_kind, long long lds, int rows, int cols,
+                                      int transpose, int np, PlaneOp* out) {
+  const long long ldp = round_up(cols, 8);
+  STRP_TAKE(ctx, arena, scale, float, 64);
+  STRP_TAKE(ctx, arena, hi, unsigned short, (size_t)rows * ldp);
+  unsigned short* lo = nullptr;
+  if (np == 2) {
+    STRP_TAKE(ctx, arena, lo2, unsigned short, (size_t)rows * ldp);
+    lo = lo2;
+  }
+  STRP_TRY(weight_scale(ctx, src, src_kind, lds, transpose ? cols : rows, transpose ? rows : cols, scale));
+  STRP_TRY(split_small(ctx, src, src_kind, lds, rows, cols, transpose, scale, hi, lo, ldp));
+  *out = PlaneOp{hi, lo, ldp, rows, scale};
+  return STRP_OK;
+}
+
+// number of K splits of a token-contraction product: enough blocks to fill the chip and fp32
+// accumulation chains of at most 8192 tokens (partials are then summed in fp64)
+static int plan_splits(int ntiles, long long K) {
+  long long s_chain = (K + 8191) / 8192;
+  long long s_fill = (1024 + ntiles - 1) / ntiles;
+  long long s = s_chain > s_fill ? s_chain : s_fill;
+  long long s_max = K / 256 > 1 ? K / 256 : 1;
+  if (s > s_max) s = s_max;
+  return (int)s;
+}
+
+static size_t nt_partial_elems(int M, int N, long long K, int triangle) {
+  GemmP p;
+  memset(&p, 0, sizeof(p));
+  p.M = M; p.N = N; p.K = K; p.triangle = triangle;
+  gemm_plan_tiles(p, false, 1);
+  gemm_plan_tiles(p, false, plan_splits(p.ntiles, K));
+  return (size_t)p.splits * (size_t)M * (size_t)N;
+}
+
+// C = P Q^T over K (ROW planes); partials in the arena (by value: released on return), fp64 reduction.
+static strp_status nt_product(strp_ctx* ctx, Arena arena, const PlaneOp& P, const PlaneOp& Q, int M, int N, long long K, int triangle,
+                              bool bf16, float* outf, long long ldof, double* outd, long long ldod, double* diag, int accumulate) {
+  GemmP p;
+  memset(&p, 0, sizeof(p));
+  p.P = P; p.Q = Q; p.M = M; p.N = N; p.K = K; p.triangle = triangle;
+  p.epi = EPI_PARTIAL;
+  gemm_plan_tiles(p, false, 1);
+  gemm_plan_tiles(p, false, plan_splits(p.ntiles, K));
+  STRP_TAKE(ctx, arena, part, float, (size_t)p.splits * M * N);
+  p.out = part;
+  STRP_TRY(launch_gemm(ctx, p, false, bf16));
+  return launch_splitk_reduce(ctx, part, p.splits, M, N, triangle, outf, ldof, outd, ldod, diag, accumulate);
+}
+
 // Solve Wsub (Gram + lam I) = R with R = Lhs Rhs^T over the tokens.  Returns the fp64 solution
 // [m x n] (leading dimension n) in *sol_out; it lives in the arena passed by reference.
 struct RefitIn {
-  int side;
-  const float* Gram; long long ldg;       // fp32 Gram (used when Ld_ready == 0 and Gd == nullptr)
-  double* Ld; int Ld_ready;               // [n x n] fp64: holds Gram + lam I (Ld_ready == 1), the factor (2), or scratch (0)
+  const float* Gram; long long ldg;       // fp32 Gram (used when Ld_ready == 0)
+  double* Ld; int Ld_ready;               // [n x n] fp64: 0 = scratch, 1 = holds Gram + lam I, 2 = holds the factor
   double lam; const double* lam_dev;
-  Operand Lhs; int lhs_kind; Operand Rhs; int rhs_kind;
+  PlaneOp Lhs, Rhs;
   int m, n; long long T;
 };
 
@@ -477,17 +470,103 @@ static strp_status ridge_solve(strp_ctx* ctx, Arena& arena, const RefitIn& in, d
     STRP_TRY(chol_factor(ctx, in.Ld, n, n, invd, ctx->status_dev));
   }
   STRP_TAKE(ctx, arena, R, double, (size_t)m * n);
-  STRP_TRY(nt_product(ctx, arena, in.Lhs, in.lhs_kind, in.Rhs, in.rhs_kind, m, n, in.T, 0, nullptr, 0, R, n, nullptr, 0));
+  STRP_TRY(nt_product(ctx, arena, in.Lhs, in.Rhs, m, n, in.T, 0, false, nullptr, 0, R, n, nullptr, 0));
   STRP_TRY(chol_solve_right(ctx, in.Ld, n, n, invd, R, m, n));
   *sol_out = R;
   return STRP_OK;
 }
 
-static int nn_kind(int dtype, int other, int prec) { return kind_of(dtype, other, prec); }
+// Persistent per-module planes (caller-owned strp_module_state::cache), fixed at initialisation:
+// Y as ROW planes, X as ROW planes and as K8 planes.
+struct CacheView {
+  int nx, ny;
+  long long ldp;
+  PlaneOp Yrow, Xrow, Xk8;
+};
+static size_t cache_layout(const strp_module_desc* desc, int prec, char* base, CacheView* v) {
+  const long long d = desc->d, T = desc->T, ldp = round_up(T, 8);
+  const int nx = planes_for(desc->x_dtype, prec), ny = planes_for(STRP_F32, prec);
+  size_t off = 256;
+  auto take = [&](size_t elems) {
+    char* p = base ? base + off : nullptr;
+    off += (elems * 2 + 255) & ~size_t(255);
+    return (unsigned short*)p;
+  };
+  unsigned short* yh = take((size_t)d * ldp);
+  unsigned short* yl = ny == 2 ? take((size_t)d * ldp) : nullptr;
+  unsigned short* xh = take((size_t)d * ldp);
+  unsigned short* xl = nx == 2 ? take((size_t)d * ldp) : nullptr;
+  unsigned short* kh = take((size_t)d * T);
+  unsigned short* kl = nx == 2 ? take((size_t)d * T) : nullptr;
+  if (v) {
+    v->nx = nx; v->ny = ny; v->ldp = ldp;
+    v->Yrow = PlaneOp{yh, yl, ldp, (int)d, nullptr};
+    v->Xrow = PlaneOp{xh, xl, ldp, (int)d, nullptr};
+    v->Xk8 = PlaneOp{kh, kl, T, 0, nullptr};
+  }
+  return off;
+}
 
 }  // namespace strp
 
 extern "C" {
+
+size_t strp_module_cache_bytes(const strp_module_desc* desc) {
+  if (!desc || desc->d <= 0 || desc->f <= 0 || desc->T <= 0) return 0;
+  return cache_layout(desc, STRP_PREC_SPLIT, nullptr, nullptr);
+}
+
+size_t strp_workspace_bytes(const strp_module_desc* desc) {
+  if (!desc || desc->d <= 0 || desc->f <= 0 || desc->T <= 0) return 0;
+  const size_t d = desc->d, f = desc->f;
+  const size_t km = desc->k_max > 0 ? (size_t)desc->k_max : f;
+  const size_t kp = (size_t)round_up((long long)km, 8);
+  const long long T = desc->T;
+  const size_t ldp = (size_t)round_up(T, 8);
+  auto al = [](size_t bytes) { return (bytes + 255) & ~size_t(255); };
+  const size_t nmax = km > d ? km : d;
+  const size_t invd_max = ((nmax + NB - 1) / NB) * NB * NB * 8;
+  const size_t tilesT = (size_t)((T + 127) / 128);
+  const size_t red = al((((f + 127) / 128) * tilesT + f + 4096) * 16);
+  // initialisation: weight planes, relu(Z0) as K8 planes, H partials
+  size_t init = 256 + 2 * (al(256) + 2 * al(f * d * 2)) + 2 * al(f * (size_t)T * 2) + red +
+                al(nt_partial_elems((int)d, (int)d, T, 1) * 4) + al(d * 8) + al(invd_max);
+  // one iteration: everything every stage carves (stages reuse the arena, so this is an upper bound)
+  size_t part = 0;
+  auto upd = [&](size_t e) { if (e > part) part = e; };
+  upd(nt_partial_elems((int)km, (int)km, T, 1));
+  upd(nt_partial_elems((int)d, (int)km, T, 0));
+  upd(nt_partial_elems((int)km, (int)d, T, 0));
+  upd(nt_partial_elems((int)d, (int)d, (long long)kp, 1));
+  size_t step = 256 + al(4 * f * 8) + al(d * kp * 4) + al(km * d * 4) + 2 * (al(256) + 2 * al(d * kp * 2)) +
+                al(part * 4) + al(nmax * nmax * 8) + 2 * al(invd_max) + al(d * km * 8) * 2 + al(d * d * 8) +
+                3 * al(256) + 2 * al(km * d * 2) +
+                2 * al(kp * ldp * 2) /* ROW planes of kept rows */ + 2 * al(kp * (size_t)T * 2) /* K8 planes of kept rows */ +
+                2 * al(d * (size_t)T * 2) /* E */ + red;
+  return (init > step ? init : step) + (1 << 20);
+}
+
+strp_status strp_gram(strp_ctx* ctx, const void* A, strp_dtype dt, int32_t C, int64_t T, int64_t ldA, const int32_t* idx,
+                      int32_t s, float* G, int32_t ldG, double* diag, int accumulate) {
+  if (!ctx) return STRP_EINVAL;
+  if (!A || !G) return fail(ctx, STRP_EINVAL, "gram: null A or G");
+  if (dt != STRP_BF16 && dt != STRP_F32) return fail(ctx, STRP_EINVAL, "gram: unknown dtype");
+  if (C <= 0 || s <= 0 || s > C || T <= 0) return fail(ctx, STRP_EINVAL, "gram: need 0 < s <= C and T > 0");
+  if (!idx && s != C) return fail(ctx, STRP_EINVAL, "gram: idx == NULL requires s == C");
+  if (ldA < T || ldA % 8 || ldG < s) return fail(ctx, STRP_EINVAL, "gram: bad leading dimension");
+  if (!aligned16(A)) return fail(ctx, STRP_EINVAL, "gram: A not 16-byte aligned");
+  if (!ctx->ws) return fail(ctx, STRP_ENOMEM, "gram: no workspace set");
+  Arena arena(ctx);
+  PlaneOp op;
+  bool bf16 = false;
+  if (dt == STRP_BF16 && !idx) {  // a bf16 matrix is its own ROW plane: exact products on the bf16 cores
+    op = PlaneOp{(const unsigned short*)A, nullptr, (long long)ldA, C, nullptr};
+    bf16 = true;
+  } else {
+    STRP_TRY(make_row_planes(ctx, arena, A, dt, ldA, idx, s, T, 0, planes_for(dt, ctx->precision), &op));
+  }
+  return nt_product(ctx, arena, op, op, s, s, T, 1, bf16, G, ldG, nullptr, 0, diag, accumulate);
+}
 
 strp_status strp_refit(strp_ctx* ctx, strp_side side, const float* Gram, int32_t ldg, double lambda, double* chol, int chol_valid,
                        const void* Lhs, strp_dtype lhs_dtype, int64_t ld_lhs, const void* Rhs, strp_dtype rhs_dtype,
@@ -510,7 +589,7 @@ strp_status strp_refit(strp_ctx* ctx, strp_side side, const float* Gram, int32_t
   Arena arena(ctx);
   RefitIn ri;
   memset(&ri, 0, sizeof(ri));
-  ri.side = side; ri.Gram = Gram; ri.ldg = ldg; ri.lam = lambda; ri.lam_dev = nullptr;
+  ri.Gram = Gram; ri.ldg = ldg; ri.lam = lambda; ri.lam_dev = nullptr;
   if (chol) {
     ri.Ld = chol;
   } else {
@@ -518,15 +597,15 @@ strp_status strp_refit(strp_ctx* ctx, strp_side side, const float* Gram, int32_t
     ri.Ld = Ld;
   }
   ri.Ld_ready = chol_valid ? 2 : 0;
-  const int lk = kind_of(lhs_dtype, rhs_dtype, ctx->precision), rk = kind_of(rhs_dtype, lhs_dtype, ctx->precision);
+  const int prec = ctx->precision;
   if (side == STRP_SIDE_FC2) {
-    ri.Lhs = Operand{Lhs, (long long)ld_lhs, nullptr, out, 0};
-    ri.Rhs = Operand{Rhs, (long long)ld_rhs, idx, s, 0};
+    STRP_TRY(make_row_planes(ctx, arena, Lhs, lhs_dtype, ld_lhs, nullptr, out, T, 0, planes_for(lhs_dtype, prec), &ri.Lhs));
+    STRP_TRY(make_row_planes(ctx, arena, Rhs, rhs_dtype, ld_rhs, idx, s, T, 0, planes_for(rhs_dtype, prec), &ri.Rhs));
   } else {
-    ri.Lhs = Operand{Lhs, (long long)ld_lhs, idx, s, 0};
-    ri.Rhs = Operand{Rhs, (long long)ld_rhs, nullptr, in, 0};
+    STRP_TRY(make_row_planes(ctx, arena, Lhs, lhs_dtype, ld_lhs, idx, s, T, 0, planes_for(lhs_dtype, prec), &ri.Lhs));
+    STRP_TRY(make_row_planes(ctx, arena, Rhs, rhs_dtype, ld_rhs, nullptr, in, T, 0, planes_for(rhs_dtype, prec), &ri.Rhs));
   }
-  ri.lhs_kind = lk; ri.rhs_kind = rk; ri.m = m; ri.n = n; ri.T = T;
+  ri.m = m; ri.n = n; ri.T = T;
   double* sol = nullptr;
   STRP_TRY(ridge_solve(ctx, arena, ri, &sol));
   return scatter_weights(ctx, sol, n, side, idx, s, W, out, in);
@@ -537,55 +616,70 @@ strp_status strp_module_init(strp_ctx* ctx, const strp_module_desc* desc, strp_m
   STRP_TRY(check_desc(ctx, desc));
   if (!st || !params) return fail(ctx, STRP_EINVAL, "module_init: null state or params");
   if (!st->X || !st->W1hat || !st->W2hat || !st->Z || !st->A || !st->Z0 || !st->Y || !st->W1 || !st->W2 || !st->H || !st->cholH ||
-      !st->n2 || !st->score || !st->mask || !st->idx || !st->scalars)
+      !st->n2 || !st->score || !st->mask || !st->idx || !st->scalars || !st->cache)
     return fail(ctx, STRP_EINVAL, "module_init: null buffer in state");
   if (!aligned16(st->X) || !aligned16(st->W1hat) || !aligned16(st->W2hat) || !aligned16(st->Z) || !aligned16(st->A) ||
-      !aligned16(st->Z0) || !aligned16(st->Y))
-    return fail(ctx, STRP_EINVAL, "module_init: buffers must be 16-byte aligned");
+      !aligned16(st->Z0) || !aligned16(st->Y) || ((uintptr_t)st->cache & 255u))
+    return fail(ctx, STRP_EINVAL, "module_init: buffers must be 16-byte aligned (cache: 256)");
   if (!(params->delta >= 0.0)) return fail(ctx, STRP_EINVAL, "module_init: negative delta");
   if (!ctx->ws) return fail(ctx, STRP_ENOMEM, "module_init: no workspace set");
   const int d = desc->d, f = desc->f;
-  const long long T = desc->T;
+  const long long T = desc->T, lda = desc->lda;
   const int prec = ctx->precision;
+  const int npw = planes_for(desc->w_dtype, prec), npa = planes_for(STRP_F32, prec);
+  const int wkind = desc->w_dtype == STRP_BF16 ? SRC_BF16 : SRC_F32;
+  CacheView cv;
+  cache_layout(desc, prec, (char*)st->cache, &cv);
   Arena arena(ctx);
   double* sc = st->scalars;
   STRP_TRY(fill_zero(ctx, sc, SC_COUNT * sizeof(double)));
   STRP_TRY(launch_colnorm2(ctx, st->W2hat, desc->w_dtype, d, f, f, st->n2));
-
-  // Z0 = W1hat X, Z = Z0, A = relu(Z0), sum A^2
+  // X planes (persistent)
+  STRP_TRY(split_rows(ctx, st->X, desc->x_dtype, desc->ldx, nullptr, d, T, 0, 0, (unsigned short*)cv.Xrow.hi, (unsigned short*)cv.Xrow.lo,
+                      cv.ldp, (unsigned short*)cv.Xk8.hi, (unsigned short*)cv.Xk8.lo));
   {
-    GemmP p;
-    memset(&p, 0, sizeof(p));
-    p.P = Operand{st->W1hat, (long long)d, nullptr, f, 0};
-    p.Q = Operand{st->X, (long long)desc->ldx, nullptr, d, 0};
-    p.M = f; p.N = (int)T; p.K = d;
-    p.epi = EPI_INITZ; p.Zs = st->Z; p.As = st->A; p.Z0s = st->Z0; p.lda = desc->lda;
-    gemm_plan_tiles(p, true, 1);
     Arena a2 = arena;
-    STRP_TAKE(ctx, a2, red, double, 2 * (size_t)gemm_grid_blocks(p));
-    p.red = red;
-    STRP_TRY(launch_gemm(ctx, p, nn_kind(desc->w_dtype, desc->x_dtype, prec), nn_kind(desc->x_dtype, desc->w_dtype, prec), true));
-    STRP_TRY(launch_block_sum(ctx, red, gemm_grid_blocks(p), sc + SC_SUMA0, nullptr, 1.0, 1.0));
-    hipLaunchKernelGGL(axpby_scalar_kernel, dim3(1), dim3(1), 0, ctx->stream, sc, (int)SC_LAM2, params->delta / (double)f, (int)SC_SUMA0, 0.0, -1);
+    PlaneOp W1p, W2p, A0k8;
+    STRP_TRY(make_weight_planes(ctx, a2, st->W1hat, wkind, d, f, d, 0, npw, &W1p));
+    STRP_TRY(make_weight_planes(ctx, a2, st->W2hat, wkind, f, d, f, 0, npw, &W2p));
+    const long long f8 = round_up(f, 8);
+    STRP_TAKE(ctx, a2, a0h, unsigned short, (size_t)f8 * T);
+    unsigned short* a0l = nullptr;
+    if (npa == 2) {
+      STRP_TAKE(ctx, a2, a0l2, unsigned short, (size_t)f8 * T);
+      a0l = a0l2;
+    }
+    A0k8 = PlaneOp{a0h, a0l, T, 0, nullptr};
+    {  // Z0 = W1hat X, Z = Z0, A = relu(Z0) (+ K8 planes of A), sum A^2
+      GemmP p;
+      memset(&p, 0, sizeof(p));
+      p.P = W1p; p.Q = cv.Xk8;
+      p.M = f; p.N = (int)T; p.K = d;
+      p.epi = EPI_INITZ; p.Zs = st->Z; p.As = st->A; p.Z0s = st->Z0; p.lda = lda;
+      p.k8_hi = a0h; p.k8_lo = a0l; p.k8_ld = T;
+      gemm_plan_tiles(p, true, 1);
+      STRP_TAKE(ctx, a2, red, double, 2 * (size_t)gemm_grid_blocks(p));
+      p.red = red;
+      STRP_TRY(launch_gemm(ctx, p, true, false));
+      STRP_TRY(launch_block_sum(ctx, red, gemm_grid_blocks(p), sc + SC_SUMA0, nullptr, 1.0, 1.0));
+      hipLaunchKernelGGL(axpby_scalar_kernel, dim3(1), dim3(1), 0, ctx->stream, sc, (int)SC_LAM2, params->delta / (double)f, (int)SC_SUMA0, 0.0, -1);
+    }
+    {  // Y = W2hat A
+      GemmP p;
+      memset(&p, 0, sizeof(p));
+      p.P = W2p; p.Q = A0k8;
+      p.M = d; p.N = (int)T; p.K = f;
+      p.epi = EPI_STORE; p.out = st->Y; p.ldo = lda;
+      gemm_plan_tiles(p, true, 1);
+      STRP_TRY(launch_gemm(ctx, p, true, false));
+    }
   }
-  // Y = W2hat A
-  {
-    GemmP p;
-    memset(&p, 0, sizeof(p));
-    p.P = Operand{st->W2hat, (long long)f, nullptr, d, 0};
-    p.Q = Operand{st->A, (long long)desc->lda, nullptr, f, 0};
-    p.M = d; p.N = (int)T; p.K = f;
-    p.epi = EPI_STORE; p.out = st->Y; p.ldo = desc->lda;
-    gemm_plan_tiles(p, true, 1);
-    STRP_TRY(launch_gemm(ctx, p, nn_kind(desc->w_dtype, STRP_F32, prec), nn_kind(STRP_F32, desc->w_dtype, prec), true));
-  }
-  // H = X X^T (fp32 copy and fp64 system), lam1 = delta tr(H)/d, factor of H + lam1 I
-  {
+  STRP_TRY(split_rows(ctx, st->Y, STRP_F32, lda, nullptr, d, T, 0, 0, (unsigned short*)cv.Yrow.hi, (unsigned short*)cv.Yrow.lo, cv.ldp,
+                      nullptr, nullptr));
+  {  // H = X X^T (fp32 copy and fp64 system), lam1 = delta tr(H)/d, factor of H + lam1 I
     Arena a2 = arena;
     STRP_TAKE(ctx, a2, diag, double, (size_t)d);
-    Operand xo = {st->X, (long long)desc->ldx, nullptr, d, 0};
-    const int kx = kind_of(desc->x_dtype, desc->x_dtype, prec);
-    STRP_TRY(nt_product(ctx, a2, xo, kx, xo, kx, d, d, T, 1, st->H, d, st->cholH, d, diag, 0));
+    STRP_TRY(nt_product(ctx, a2, cv.Xrow, cv.Xrow, d, d, T, 1, false, st->H, d, st->cholH, d, diag, 0));
     hipLaunchKernelGGL(vec_sum_kernel, dim3(1), dim3(256), 0, ctx->stream, diag, d, params->delta / (double)d, sc + SC_LAM1, sc + SC_TRH);
     hipLaunchKernelGGL(add_diag_kernel, dim3(blocks_for(d)), dim3(256), 0, ctx->stream, st->cholH, (long long)d, d, 0.0, sc + SC_LAM1);
     STRP_TAKE(ctx, a2, invd, double, (size_t)((d + NB - 1) / NB) * NB * NB);
@@ -606,7 +700,7 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   STRP_TRY(check_desc(ctx, desc));
   if (!st || !params) return fail(ctx, STRP_EINVAL, "admm_step: null state or params");
   if (!st->X || !st->W2hat || !st->Z || !st->A || !st->Z0 || !st->Y || !st->W1 || !st->W2 || !st->cholH || !st->n2 || !st->score ||
-      !st->mask || !st->idx || !st->scalars)
+      !st->mask || !st->idx || !st->scalars || !st->cache)
     return fail(ctx, STRP_EINVAL, "admm_step: null buffer in state");
   const int d = desc->d, f = desc->f;
   const long long T = desc->T, lda = desc->lda;
@@ -619,8 +713,9 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   if (params->mode < STRP_SCORE_WANDA || params->mode > STRP_SCORE_GAIN) return fail(ctx, STRP_EINVAL, "admm_step: unknown score mode");
   if (!ctx->ws) return fail(ctx, STRP_ENOMEM, "admm_step: no workspace set");
   const int prec = ctx->precision;
-  const int kf32 = prec == STRP_PREC_SPLIT ? OP_F32_2 : OP_F32_1;
-  const int kx_h = kind_of(desc->x_dtype, STRP_F32, prec);  // X next to an fp32 operand
+  const int npa = planes_for(STRP_F32, prec);
+  CacheView cv;
+  cache_layout(desc, prec, (char*)st->cache, &cv);
   double* sc = st->scalars;
   const float alpha = (float)params->alpha, beta = (float)params->beta;
   Arena arena(ctx);
@@ -637,22 +732,18 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   const int s = st->s;
   const long long sp = round_up(s, 8);
 
-  // persistent (within this call) compact buffers
-  STRP_TAKE(ctx, arena, W2S, float, (size_t)d * sp);
-  STRP_TAKE(ctx, arena, W1S, float, (size_t)s * d);
-
   // ---- S1/S5: Gram of the kept A rows, fc2 refit -------------------------------------------
   if (stages & STRP_STAGE_REFIT2) {
     Arena a2 = arena;
     STRP_TAKE(ctx, a2, Gd, double, (size_t)s * s);
-    Operand ao = {st->A, lda, st->idx, s, 0};
-    Operand yo = {st->Y, lda, nullptr, d, 0};
-    STRP_TRY(nt_product(ctx, a2, ao, kf32, ao, kf32, s, s, T, 1, nullptr, 0, Gd, s, nullptr, 0));
+    PlaneOp Arow;
+    STRP_TRY(make_row_planes(ctx, a2, st->A, STRP_F32, lda, st->idx, s, T, 0, npa, &Arow));
+    STRP_TRY(nt_product(ctx, a2, Arow, Arow, s, s, T, 1, false, nullptr, 0, Gd, s, nullptr, 0));
     hipLaunchKernelGGL(add_diag_kernel, dim3(blocks_for(s)), dim3(256), 0, ctx->stream, Gd, (long long)s, s, 0.0, sc + SC_LAM2);
     RefitIn ri;
     memset(&ri, 0, sizeof(ri));
-    ri.side = STRP_SIDE_FC2; ri.Ld = Gd; ri.Ld_ready = 1;
-    ri.Lhs = yo; ri.lhs_kind = kf32; ri.Rhs = ao; ri.rhs_kind = kf32; ri.m = d; ri.n = s; ri.T = T;
+    ri.Ld = Gd; ri.Ld_ready = 1;
+    ri.Lhs = cv.Yrow; ri.Rhs = Arow; ri.m = d; ri.n = s; ri.T = T;
     double* sol = nullptr;
     STRP_TRY(ridge_solve(ctx, a2, ri, &sol));
     STRP_TRY(scatter_weights(ctx, sol, s, STRP_SIDE_FC2, st->idx, s, st->W2, d, f));
@@ -660,21 +751,34 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   // ---- S6: fc1 refit with the cached factor of H + lam1 I ------------------------------------
   if (stages & STRP_STAGE_REFIT1) {
     Arena a2 = arena;
-    Operand zo = {st->Z, lda, st->idx, s, 0};
-    Operand xo = {st->X, (long long)desc->ldx, nullptr, d, 0};
+    PlaneOp Zrow;
+    STRP_TRY(make_row_planes(ctx, a2, st->Z, STRP_F32, lda, st->idx, s, T, 0, npa, &Zrow));
     RefitIn ri;
     memset(&ri, 0, sizeof(ri));
-    ri.side = STRP_SIDE_FC1; ri.Ld = st->cholH; ri.Ld_ready = 2;
-    ri.Lhs = zo; ri.lhs_kind = kf32; ri.Rhs = xo; ri.rhs_kind = kx_h; ri.m = s; ri.n = d; ri.T = T;
-    if (desc->x_dtype == STRP_F32) ri.rhs_kind = kf32;
+    ri.Ld = st->cholH; ri.Ld_ready = 2;
+    ri.Lhs = Zrow; ri.Rhs = cv.Xrow; ri.m = s; ri.n = d; ri.T = T;
     double* sol = nullptr;
     STRP_TRY(ridge_solve(ctx, a2, ri, &sol));
     STRP_TRY(scatter_weights(ctx, sol, d, STRP_SIDE_FC1, st->idx, s, st->W1, f, d));
   }
-  if (stages & (STRP_STAGE_AUPD | STRP_STAGE_OBJ))
+  // compact kept weights and their planes (shared by the stages below)
+  PlaneOp W2Sp, W1Sp;
+  memset(&W2Sp, 0, sizeof(W2Sp));
+  memset(&W1Sp, 0, sizeof(W1Sp));
+  float* W2S = nullptr;
+  float* W1S = nullptr;
+  if (stages & (STRP_STAGE_AUPD | STRP_STAGE_OBJ)) {
+    STRP_TAKE(ctx, arena, w2s, float, (size_t)d * sp);
+    W2S = w2s;
     hipLaunchKernelGGL(gather_cols_kernel, dim3(blocks_for((long long)d * sp)), dim3(256), 0, ctx->stream, st->W2, d, f, st->idx, s, W2S, sp);
-  if (stages & (STRP_STAGE_ZUPD | STRP_STAGE_OBJ))
+    STRP_TRY(make_weight_planes(ctx, arena, W2S, SRC_F32, sp, d, s, 0, npa, &W2Sp));
+  }
+  if (stages & (STRP_STAGE_ZUPD | STRP_STAGE_OBJ)) {
+    STRP_TAKE(ctx, arena, w1s, float, (size_t)s * d);
+    W1S = w1s;
     hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks_for((long long)s * d)), dim3(256), 0, ctx->stream, st->W1, d, st->idx, s, W1S, (long long)d);
+    STRP_TRY(make_weight_planes(ctx, arena, W1S, SRC_F32, d, s, d, 0, npa, &W1Sp));
+  }
 
   // ---- S7: a-update in residual (Woodbury) form ------------------------------------------------
   //   A_S = relu(Z_S) + W^T M^-1 (Y - W relu(Z_S)),  M = (beta/alpha) I + W W^T,  W = W2[:, S];  A_j = relu(Z_j) for pruned j
@@ -683,34 +787,38 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     STRP_TAKE(ctx, a2, Md, double, (size_t)d * d);
     STRP_TAKE(ctx, a2, invd, double, (size_t)((d + NB - 1) / NB) * NB * NB);
     STRP_TAKE(ctx, a2, Bd, double, (size_t)s * d);
-    STRP_TAKE(ctx, a2, Bm, float, (size_t)s * d);
-    STRP_TAKE(ctx, a2, E, float, (size_t)d * lda);
-    Operand wo = {W2S, sp, nullptr, d, 0};
-    STRP_TRY(nt_product(ctx, a2, wo, kf32, wo, kf32, d, d, sp, 1, nullptr, 0, Md, d, nullptr, 0));
+    STRP_TRY(nt_product(ctx, a2, W2Sp, W2Sp, d, d, sp, 1, false, nullptr, 0, Md, d, nullptr, 0));
     hipLaunchKernelGGL(add_diag_kernel, dim3(blocks_for(d)), dim3(256), 0, ctx->stream, Md, (long long)d, d, params->beta / params->alpha, (const double*)nullptr);
     STRP_TRY(chol_factor(ctx, Md, d, d, invd, ctx->status_dev));
     hipLaunchKernelGGL(transpose_f32_f64_kernel, dim3(blocks_for((long long)d * s)), dim3(256), 0, ctx->stream, W2S, sp, d, s, Bd, (long long)d);
     STRP_TRY(chol_solve_right(ctx, Md, d, d, invd, Bd, s, d));
-    STRP_TRY(cast_f64_f32(ctx, Bd, d, Bm, d, s, d));
-    {  // E = Y - W relu(Z_S)
+    PlaneOp Bp, Zk8;
+    STRP_TRY(make_weight_planes(ctx, a2, Bd, SRC_F64, d, s, d, 0, npa, &Bp));
+    STRP_TRY(make_k8_planes(ctx, a2, st->Z, STRP_F32, lda, st->idx, s, T, 1, npa, &Zk8));
+    STRP_TAKE(ctx, a2, ekh, unsigned short, (size_t)d * T);
+    unsigned short* ekl = nullptr;
+    if (npa == 2) {
+      STRP_TAKE(ctx, a2, ekl2, unsigned short, (size_t)d * T);
+      ekl = ekl2;
+    }
+    {  // E = Y - W relu(Z_S), kept only as K8 planes
       GemmP p;
       memset(&p, 0, sizeof(p));
-      p.P = Operand{W2S, sp, nullptr, d, 0};
-      p.Q = Operand{st->Z, lda, st->idx, s, 1};
+      p.P = W2Sp; p.Q = Zk8;
       p.M = d; p.N = (int)T; p.K = s;
-      p.epi = EPI_RESID; p.Yin = st->Y; p.ldy = lda; p.out = E; p.ldo = lda; p.write_out = 1;
+      p.epi = EPI_RESID; p.Yin = st->Y; p.ldy = lda;
+      p.k8_hi = ekh; p.k8_lo = ekl; p.k8_ld = T;
       gemm_plan_tiles(p, true, 1);
-      STRP_TRY(launch_gemm(ctx, p, kf32, kf32, true));
+      STRP_TRY(launch_gemm(ctx, p, true, false));
     }
     {  // A_S = relu(Z_S) + B E
       GemmP p;
       memset(&p, 0, sizeof(p));
-      p.P = Operand{Bm, (long long)d, nullptr, s, 0};
-      p.Q = Operand{E, lda, nullptr, d, 0};
+      p.P = Bp; p.Q = PlaneOp{ekh, ekl, T, 0, nullptr};
       p.M = s; p.N = (int)T; p.K = d;
       p.epi = EPI_AUPD; p.Zs = st->Z; p.As = st->A; p.lda = lda; p.oidx = st->idx;
       gemm_plan_tiles(p, true, 1);
-      STRP_TRY(launch_gemm(ctx, p, kf32, kf32, true));
+      STRP_TRY(launch_gemm(ctx, p, true, false));
     }
     {
       ProfScope ps(ctx, "pruned_rows_a", 0.0, 8.0 * (double)(f - s) * (double)T);
@@ -723,8 +831,7 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     Arena a2 = arena;
     GemmP p;
     memset(&p, 0, sizeof(p));
-    p.P = Operand{W1S, (long long)d, nullptr, s, 0};
-    p.Q = Operand{st->X, (long long)desc->ldx, nullptr, d, 0};
+    p.P = W1Sp; p.Q = cv.Xk8;
     p.M = s; p.N = (int)T; p.K = d;
     p.epi = EPI_ZUPD; p.Zs = st->Z; p.As = st->A; p.lda = lda; p.oidx = st->idx; p.alpha = alpha; p.beta = beta;
     p.write_out = zupd ? 1 : 0;
@@ -732,8 +839,7 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     const int nb = gemm_grid_blocks(p);
     STRP_TAKE(ctx, a2, red, double, 2 * (size_t)(nb > f ? nb : f));
     p.red = red;
-    const int kq = desc->x_dtype == STRP_F32 ? kf32 : kx_h;
-    STRP_TRY(launch_gemm(ctx, p, kf32, kq, true));
+    STRP_TRY(launch_gemm(ctx, p, true, false));
     STRP_TRY(launch_block_sum(ctx, red, nb, sc + SC_TMP0, sc + SC_TMP1, 1.0, 1.0));
     {
       ProfScope ps(ctx, "pruned_rows_z", 0.0, 8.0 * (double)(f - s) * (double)T);
@@ -743,20 +849,21 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     hipLaunchKernelGGL(axpby_scalar_kernel, dim3(1), dim3(1), 0, ctx->stream, sc, (int)SC_T2, params->beta / (double)T, (int)SC_TMP0, params->beta / (double)T, (int)SC_TMP2);
     hipLaunchKernelGGL(axpby_scalar_kernel, dim3(1), dim3(1), 0, ctx->stream, sc, (int)SC_T3, params->alpha / (double)T, (int)SC_TMP1, params->alpha / (double)T, (int)SC_TMP3);
   }
-  // ---- S9: objective term 1 and ridge terms ------------------------------------------------------
+  // ---- S9: objective term 1 (one fp16 plane per operand is ample for a 1e-3 sum) and ridge terms ----
   if (stages & STRP_STAGE_OBJ) {
     Arena a2 = arena;
+    PlaneOp Ak8;
+    STRP_TRY(make_k8_planes(ctx, a2, st->A, STRP_F32, lda, st->idx, s, T, 0, 1, &Ak8));
     GemmP p;
     memset(&p, 0, sizeof(p));
-    p.P = Operand{W2S, sp, nullptr, d, 0};
-    p.Q = Operand{st->A, lda, st->idx, s, 0};
+    p.P = W2Sp; p.P.lo = nullptr; p.Q = Ak8;
     p.M = d; p.N = (int)T; p.K = s;
-    p.epi = EPI_RESID; p.Yin = st->Y; p.ldy = lda; p.write_out = 0;
+    p.epi = EPI_RESID; p.Yin = st->Y; p.ldy = lda;
     gemm_plan_tiles(p, true, 1);
     const int nb = gemm_grid_blocks(p);
     STRP_TAKE(ctx, a2, red, double, 2 * (size_t)(nb > 1024 ? nb : 1024));
     p.red = red;
-    STRP_TRY(launch_gemm(ctx, p, OP_F32_1, OP_F32_1, true));
+    STRP_TRY(launch_gemm(ctx, p, true, false));
     STRP_TRY(launch_block_sum(ctx, red, nb, sc + SC_T1, nullptr, params->alpha / (double)T, 1.0));
     hipLaunchKernelGGL(sumsq_kernel, dim3(1024), dim3(256), 0, ctx->stream, W2S, (long long)d * sp, red);
     STRP_TRY(launch_block_sum(ctx, red, 1024, sc + SC_W2SQ, nullptr, 1.0, 1.0));

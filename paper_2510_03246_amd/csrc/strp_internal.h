@@ -68,25 +68,24 @@ struct Arena {
   if (!var) return strp::fail((ctx), STRP_ENOMEM, "workspace too small for %s (%zu bytes more)",    \
                               #var, sizeof(type) * (size_t)(count))
 
-// ---- MFMA GEMM family (gemm_mfma.hip) ---------------------------------------------------
-// Operand kinds: how an operand reaches the 16-bit matrix cores.
-enum { OP_BF16 = 0,     // bf16 in memory, used as is (both operands must be OP_BF16)
-       OP_F32_1 = 1,    // fp32 in memory, rounded once to fp16
-       OP_F32_2 = 2,    // fp32 in memory, split into fp16 hi + scaled fp16 lo
-       OP_BF16_H = 3 }; // bf16 in memory, converted (exactly, in range) to fp16
-
-struct Operand {
-  const void* ptr;
-  long long ld;     // elements
-  const int* idx;   // optional row gather (rows of the stored matrix), device
-  int rows;         // logical rows (P: M; Q: N for token-contraction, K for token-parallel form)
-  int relu;         // apply max(x, 0) on load (fp32 kinds only)
+// ---- MFMA GEMM family on 16-bit operand planes (gemm_mfma.hip) -------------------------------
+// An operand as the matrix cores see it: one (hi) or two (hi, lo) planes of 16-bit elements.
+//   ROW layout: element (row, k) at row * ld + k                     (k contiguous; ld % 8 == 0)
+//   K8  layout: element (k, n)   at ((k / 8) * ld + n) * 8 + k % 8   (ld = number of columns)
+// scale (device, optional): the planes hold x * scale; the GEMM epilogue divides it out.
+struct PlaneOp {
+  const unsigned short* hi;
+  const unsigned short* lo;
+  long long ld;
+  int rows;            // ROW: rows available (row index is clamped to rows - 1); K8: unused
+  const float* scale;
 };
 
 enum { EPI_PARTIAL = 0, EPI_STORE = 1, EPI_INITZ = 2, EPI_RESID = 3, EPI_AUPD = 4, EPI_ZUPD = 5 };
+enum { SRC_F64 = 0, SRC_F32 = 1, SRC_BF16 = 2 };
 
 struct GemmP {
-  Operand P, Q;
+  PlaneOp P, Q;
   int M, N;
   long long K;
   int tilesM, tilesN, ntiles;
@@ -94,7 +93,7 @@ struct GemmP {
   int splits;
   long long kchunk;    // K range per split (multiple of the K tile)
   int epi;
-  float* out;          // PARTIAL: [splits][M][N]; STORE / RESID: [M x ldo]
+  float* out;          // PARTIAL: [splits][M][N]; STORE: [M x ldo]
   long long ldo;
   const float* Yin;    // RESID: Y
   long long ldy;
@@ -105,16 +104,19 @@ struct GemmP {
   const int* oidx;     // AUPD / ZUPD: output row m is state row oidx[m]
   float alpha, beta;
   double* red;         // per-block partial sums [gridDim.x][2] (INITZ, RESID, ZUPD)
-  int write_out;       // RESID: store the residual
+  int write_out;       // ZUPD: 1 = update Z, 0 = only accumulate the objective sums
+  unsigned short* k8_hi;  // optional K8 planes of the produced values (STORE: C, INITZ: relu(C), RESID: Y - C)
+  unsigned short* k8_lo;
+  long long k8_ld;
 };
 
 // Token-contraction form ("NT"): C[M x N] = sum_k P[m,k] Q[n,k]; writes split-K partials.
-// Token-parallel form ("NN"): C[M x N] = sum_k P[m,k] Q[k,n] with fused epilogue.
-strp_status launch_gemm(strp_ctx* ctx, GemmP& p, int kindP, int kindQ, bool nn);
+// Token-parallel form ("NN"): C[M x N] = sum_k P[m,k] Q[k,n] with fused epilogue (Q in K8 layout).
+strp_status launch_gemm(strp_ctx* ctx, GemmP& p, bool nn, bool bf16);
 int gemm_grid_blocks(const GemmP& p);
-void gemm_plan_tiles(GemmP& p, bool nn, int want_blocks);
+void gemm_plan_tiles(GemmP& p, bool nn, int want_splits);
 
-// Sum split-K partials in fp64; optional symmetric completion from the computed lower tiles.
+// Sum split-K partials in fp64; optional symmetric completion from the computed lower half.
 // outf / outd (either may be null): [M x ldo]; accumulate adds to outf's previous content.
 strp_status launch_splitk_reduce(strp_ctx* ctx, const float* part, int splits, int M, int N, int triangle,
                                  float* outf, long long ldof, double* outd, long long ldod, double* diag,
@@ -122,6 +124,17 @@ strp_status launch_splitk_reduce(strp_ctx* ctx, const float* part, int splits, i
 // Sum per-block fp64 partials red[nblocks][2] into dst[0], dst[1] (fixed order).
 strp_status launch_block_sum(strp_ctx* ctx, const double* red, int nblocks, double* dst0, double* dst1,
                              double scale0, double scale1);
+
+// fp32 / bf16 activation rows (optionally gathered by idx) -> fp16 planes; any output may be null.
+//   ROW planes [round_up(rows,8)][ld_row], K8 planes [round_up(rows,8)/8][T][8]; padding is zero.
+strp_status split_rows(strp_ctx* ctx, const void* src, int src_dtype, long long lds, const int* idx, int rows, long long T,
+                       int relu_row, int relu_k8, unsigned short* row_hi, unsigned short* row_lo, long long ld_row,
+                       unsigned short* k8_hi, unsigned short* k8_lo);
+// Small matrix (weights) -> ROW planes [rows][ldp] of src * (*scale_dev), zero padded; src_kind = SRC_*.
+strp_status split_small(strp_ctx* ctx, const void* src, int src_kind, long long lds, int rows, int cols, int transpose,
+                        const float* scale_dev, unsigned short* hi, unsigned short* lo, long long ldp);
+// *scale_out = power of two that brings max|src| into [2^11, 2^12).
+strp_status weight_scale(strp_ctx* ctx, const void* src, int src_kind, long long lds, int rows, int cols, float* scale_out);
 
 // ---- fp64 dense kernels (dense_f64.hip) ---------------------------------------------------
 constexpr int NB = 64;  // block order of the factorisation

@@ -24,7 +24,7 @@ STAGE_ALL = 63
 
 EXPORTS = [
     "strp_create", "strp_destroy", "strp_last_error", "strp_set_precision", "strp_set_workspace",
-    "strp_poll", "strp_workspace_bytes", "strp_profile_enable", "strp_profile_read", "strp_gram", "strp_score_alloc", "strp_mask_topk",
+    "strp_poll", "strp_workspace_bytes", "strp_module_cache_bytes", "strp_profile_enable", "strp_profile_read", "strp_gram", "strp_score_alloc", "strp_mask_topk",
     "strp_refit", "strp_module_init", "strp_admm_step",
 ]
 
@@ -51,7 +51,7 @@ class ModuleState(C.Structure):
     _fields_ = [("X", C.c_void_p), ("W1hat", C.c_void_p), ("W2hat", C.c_void_p), ("Z", C.c_void_p), ("A", C.c_void_p),
                 ("Z0", C.c_void_p), ("Y", C.c_void_p), ("W1", C.c_void_p), ("W2", C.c_void_p), ("H", C.c_void_p),
                 ("cholH", C.c_void_p), ("n2", C.c_void_p), ("score", C.c_void_p), ("mask", C.c_void_p),
-                ("idx", C.c_void_p), ("scalars", C.c_void_p), ("s", C.c_int32), ("iter", C.c_int32)]
+                ("idx", C.c_void_p), ("scalars", C.c_void_p), ("cache", C.c_void_p), ("s", C.c_int32), ("iter", C.c_int32)]
 
 
 class Params(C.Structure):
@@ -93,6 +93,8 @@ def load_library():
     lib.strp_profile_read.argtypes = [vp, C.POINTER(ProfileEntry), i32, C.POINTER(i32)]
     lib.strp_workspace_bytes.argtypes = [C.POINTER(ModuleDesc)]
     lib.strp_workspace_bytes.restype = C.c_size_t
+    lib.strp_module_cache_bytes.argtypes = [C.POINTER(ModuleDesc)]
+    lib.strp_module_cache_bytes.restype = C.c_size_t
     lib.strp_gram.argtypes = [vp, vp, C.c_int, i32, i64, i64, vp, i32, vp, i32, vp, C.c_int]
     lib.strp_score_alloc.argtypes = [vp, C.POINTER(ScoreIn), vp, vp, i32, i32, vp, vp, dbl, dbl, dbl, vp, vp]
     lib.strp_mask_topk.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
@@ -102,7 +104,7 @@ def load_library():
     lib.strp_admm_step.argtypes = [vp, C.POINTER(ModuleDesc), C.POINTER(ModuleState), C.POINTER(Params),
                                    C.POINTER(Report)]
     for name in EXPORTS:
-        if name not in ("strp_last_error", "strp_workspace_bytes"):
+        if name not in ("strp_last_error", "strp_workspace_bytes", "strp_module_cache_bytes"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -255,9 +257,10 @@ class FFNModule:
         self.idx = e(f, dt=torch.int32)
         self.scalars = torch.zeros(32, dtype=torch.float64, device=dev)
         self.desc = ModuleDesc(d, f, T, X.stride(0), lda, dtype_code(X), dtype_code(W1hat), k_max)
+        self.cache = torch.empty(int(ctx.lib.strp_module_cache_bytes(C.byref(self.desc))), dtype=torch.uint8, device=dev)
         st = ModuleState()
         for name in ("X", "W1hat", "W2hat", "Z", "A", "Z0", "Y", "W1", "W2", "H", "cholH", "n2", "score", "mask",
-                     "idx", "scalars"):
+                     "idx", "scalars", "cache"):
             setattr(st, name, getattr(self, name).data_ptr())
         st.s, st.iter = 0, 0
         self.state = st
