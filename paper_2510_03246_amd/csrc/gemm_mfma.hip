@@ -20,9 +20,19 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int LDK = BK + 8;      // LDS row pitch in 16-bit elements (144 bytes: conflict-free b128 reads)
-constexpr int NCH = BM * (BK / 8) / 256;  // 16-byte chunks per thread per plane per K tile (= 4)
+// Tile shapes (WT = 32x32 MFMA tiles per wavefront per dimension, 2x2 wavefronts per block):
+//   WT = 2: 128x128 block, K tile 64, two blocks per CU   (small problems)
+//   WT = 4: 256x256 block, K tile 32, one block per CU    (halves the L2->CU traffic per flop)
+template <int WT>
+struct Tile {
+  static constexpr int BM = 64 * WT, BN = 64 * WT;
+  static constexpr int BK = WT == 2 ? 64 : 32;
+  static constexpr int LDK = BK + 8;               // LDS row pitch in 16-bit elements (conflict-free b128 reads)
+  static constexpr int CPR = BK / 8;               // 16-byte chunks per row
+  static constexpr int NCH = BM * CPR / 256;       // chunks per thread per plane per K tile (= 4)
+  static constexpr int RSTEP = 256 / CPR;          // row distance between a thread's chunks (ROW loader)
+  static constexpr int KGS = 256 / BN;             // k groups covered by one pass of the block (K8 loader)
+};
 
 __device__ __forceinline__ unsigned short half_bits(float x) {
   _Float16 h = (_Float16)x;
@@ -41,32 +51,42 @@ __device__ __forceinline__ unsigned int pack2(unsigned short a, unsigned short b
   return (unsigned int)a | ((unsigned int)b << 16);
 }
 
-// ROW plane tile: [128 rows][64 k]; thread owns rows (tid>>3) + 32 i and the 8-element chunk tid&7
-template <int NP>
+// ROW plane tile: [128 rows][64 k]; thread owns rows (tid>>3) + 32 i and the 8-element chunk tid&7.
+// Loads are unconditional (row clamped, k clamped to the last valid chunk) and zeroed by select, so the
+// main loop carries no branches; pointers advance by one K tile per iteration.
+template <int NP, int WT>
 struct RowLoader {
-  const unsigned short* rp[NP][NCH];
+  static constexpr int NCH = Tile<WT>::NCH, BK = Tile<WT>::BK, LDK = Tile<WT>::LDK, BM = Tile<WT>::BM;
+  const unsigned short* rp[NP][NCH];   // points at (row, k + kc) of the tile to load next
   uint4 r[NP][NCH];
   int kc, row0;
+  long long kk;                        // k + kc of the tile to load next
 
-  __device__ __forceinline__ void init(const PlaneOp& op, int tile_row0) {
-    kc = (threadIdx.x & 7) * 8;
-    row0 = threadIdx.x >> 3;
+  __device__ __forceinline__ void init(const PlaneOp& op, int tile_row0, long long k0) {
+    kc = (threadIdx.x % Tile<WT>::CPR) * 8;
+    row0 = threadIdx.x / Tile<WT>::CPR;
+    kk = k0 + kc;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-      int row = tile_row0 + row0 + 32 * i;
+      int row = tile_row0 + row0 + Tile<WT>::RSTEP * i;
       row = row < op.rows ? row : op.rows - 1;
-      rp[0][i] = op.hi + (long long)row * op.ld;
-      if (NP == 2) rp[NP - 1][i] = op.lo + (long long)row * op.ld;
+      rp[0][i] = op.hi + (long long)row * op.ld + kk;
+      if (NP == 2) rp[NP - 1][i] = op.lo + (long long)row * op.ld + kk;
     }
   }
-  __device__ __forceinline__ void load(long long k, long long k1) {
-    const long long kk = k + kc;
+  __device__ __forceinline__ void load(long long k1) {
+    const bool valid = kk < k1;
+    const long long back = valid ? 0 : (kk - (k1 - 1)) ;   // step back into the row's valid range
 #pragma unroll
     for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
-      for (int i = 0; i < NCH; ++i) r[pl][i] = (kk < k1) ? *(const uint4*)(rp[pl][i] + kk) : make_uint4(0, 0, 0, 0);
-    if (kk < k1 && kk + 8 > k1) {  // ragged end of the contraction: zero the elements past k1
-      const int valid = (int)(k1 - kk);
+      for (int i = 0; i < NCH; ++i) {
+        uint4 v = *(const uint4*)(rp[pl][i] - ((back + 7) & ~7LL));
+        r[pl][i] = valid ? v : make_uint4(0, 0, 0, 0);
+        rp[pl][i] += BK;
+      }
+    if ((k1 & 7) && valid && kk + 8 > k1) {  // ragged end of the contraction: zero the elements past k1
+      const int nvalid = (int)(k1 - kk);
 #pragma unroll
       for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
@@ -74,49 +94,64 @@ struct RowLoader {
           unsigned int w[4] = {r[pl][i].x, r[pl][i].y, r[pl][i].z, r[pl][i].w};
 #pragma unroll
           for (int e = 0; e < 8; ++e)
-            if (e >= valid) w[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+            if (e >= nvalid) w[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
           r[pl][i] = make_uint4(w[0], w[1], w[2], w[3]);
         }
     }
+    kk += BK;
   }
   __device__ __forceinline__ void store(unsigned short (*s)[BM * LDK]) const {
 #pragma unroll
     for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
-      for (int i = 0; i < NCH; ++i) *(uint4*)(&s[pl][(row0 + 32 * i) * LDK + kc]) = r[pl][i];
+      for (int i = 0; i < NCH; ++i) *(uint4*)(&s[pl][(row0 + Tile<WT>::RSTEP * i) * LDK + kc]) = r[pl][i];
   }
 };
 
-// K8 plane tile: chunk (kg, n) of the tile is the 16 bytes at ((k/8 + kg) * ld + n0 + n) * 8 elements
-template <int NP>
+// K8 plane tile: chunk (kg, n) of the tile is the 16 bytes at ((k/8 + kg) * ld + n0 + n) * 8 elements.
+// Columns past N read column N-1 (their outputs are never stored); k groups past K read group 0 and are zeroed.
+template <int NP, int WT>
 struct K8Loader {
+  static constexpr int NCH = Tile<WT>::NCH, BK = Tile<WT>::BK, LDK = Tile<WT>::LDK, BN = Tile<WT>::BN, KGS = Tile<WT>::KGS;
+  const unsigned short* bp[NP];        // points at chunk (k/8 + kg0, ncol) of the tile to load next
+  const unsigned short* safe[NP];
   uint4 r[NP][NCH];
   int n, kg0;
-  long long ncol;
-  bool nvalid;
+  long long kk, gstep;                 // k of this thread's first chunk in the next tile; elements per KGS groups
 
-  __device__ __forceinline__ void init(const PlaneOp& op, int n0, int N) {
-    n = threadIdx.x & 127;
-    kg0 = threadIdx.x >> 7;
-    ncol = (long long)n0 + n;
-    nvalid = ncol < N;
+  __device__ __forceinline__ void init(const PlaneOp& op, int n0, int N, long long k0) {
+    n = threadIdx.x % BN;
+    kg0 = threadIdx.x / BN;
+    long long ncol = (long long)n0 + n;
+    ncol = ncol < N ? ncol : (long long)N - 1;
+    kk = k0 + kg0 * 8;
+    gstep = KGS * op.ld * 8;
+    bp[0] = op.hi + ((kk >> 3) * op.ld + ncol) * 8;
+    safe[0] = op.hi + ncol * 8;
+    if (NP == 2) {
+      bp[NP - 1] = op.lo + ((kk >> 3) * op.ld + ncol) * 8;
+      safe[NP - 1] = op.lo + ncol * 8;
+    }
   }
-  __device__ __forceinline__ void load(const PlaneOp& op, long long k, long long k1) {
+  __device__ __forceinline__ void load(long long k1) {
 #pragma unroll
     for (int pl = 0; pl < NP; ++pl) {
-      const unsigned short* base = pl == 0 ? op.hi : op.lo;
 #pragma unroll
       for (int i = 0; i < NCH; ++i) {
-        const long long kk = k + (kg0 + 2 * i) * 8;
-        r[pl][i] = (kk < k1 && nvalid) ? *(const uint4*)(base + ((kk >> 3) * op.ld + ncol) * 8) : make_uint4(0, 0, 0, 0);
+        const bool valid = kk + 8 * KGS * i < k1;
+        const unsigned short* src = valid ? bp[pl] + i * gstep : safe[pl];
+        uint4 v = *(const uint4*)src;
+        r[pl][i] = valid ? v : make_uint4(0, 0, 0, 0);
       }
+      bp[pl] += NCH * gstep;
     }
+    kk += BK;
   }
   __device__ __forceinline__ void store(unsigned short (*s)[BN * LDK]) const {
 #pragma unroll
     for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
-      for (int i = 0; i < NCH; ++i) *(uint4*)(&s[pl][n * LDK + (kg0 + 2 * i) * 8]) = r[pl][i];
+      for (int i = 0; i < NCH; ++i) *(uint4*)(&s[pl][n * LDK + (kg0 + KGS * i) * 8]) = r[pl][i];
   }
 };
 
@@ -135,8 +170,99 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
-template <int NPP, int NPQ, bool NN, bool BF>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
+// Epilogue of one 32x32 accumulator tile (passed by value so the accumulators never need an address).
+// Register e of lane l is output row m_tile + 8 (e / 4) + (e % 4), column n  (m_tile, n include the lane's share).
+template <int EPI>
+__device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16, float unscale, int m_tile, int n, int split,
+                                              double& red0, double& red1) {
+  const float ab = p.alpha + p.beta;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int mq = m_tile + 8 * q;  // rows mq .. mq+3
+    float outv[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int m = mq + r;
+      const float v = a16[4 * q + r] * unscale;
+      outv[r] = 0.0f;
+      if (m >= p.M || n >= p.N) continue;
+      if (EPI == EPI_PARTIAL) {
+        p.out[((long long)split * p.M + m) * p.N + n] = v;
+      } else if (EPI == EPI_STORE) {
+        p.out[(long long)m * p.ldo + n] = v;
+        outv[r] = v;
+      } else if (EPI == EPI_INITZ) {
+        const long long o = (long long)m * p.lda + n;
+        const float a = __builtin_fmaxf(v, 0.0f);
+        p.Z0s[o] = v;
+        p.Zs[o] = v;
+        p.As[o] = a;
+        outv[r] = a;
+        red0 += (double)a * (double)a;
+      } else if (EPI == EPI_RESID) {
+        const float rr = p.Yin[(long long)m * p.ldy + n] - v;
+        outv[r] = rr;
+        red0 += (double)rr * (double)rr;
+      } else if (EPI == EPI_AUPD) {
+        const long long o = (long long)p.oidx[m] * p.lda + n;
+        p.As[o] = __builtin_fmaxf(p.Zs[o], 0.0f) + v;
+      } else {  // EPI_ZUPD
+        const long long o = (long long)p.oidx[m] * p.lda + n;
+        const float a = p.As[o];
+        const float z1 = v;
+        float z;
+        if (p.write_out) {
+          const float z2 = (p.beta * a + p.alpha * z1) / ab;
+          const float cm = __builtin_fminf(z1, 0.0f);
+          const float costm = p.beta * a * a + p.alpha * (cm - z1) * (cm - z1);
+          const float cp = __builtin_fmaxf(z2, 0.0f);
+          const float costp = p.beta * (a - cp) * (a - cp) + p.alpha * (cp - z1) * (cp - z1);
+          z = costm < costp ? cm : cp;
+          p.Zs[o] = z;
+        } else {
+          z = p.Zs[o];
+        }
+        const float ra = a - __builtin_fmaxf(z, 0.0f);
+        const float rz = z - z1;
+        red0 += (double)ra * (double)ra;
+        red1 += (double)rz * (double)rz;
+      }
+    }
+    // optional K8-plane copy of the produced tile (its rows are the k axis of the consumer):
+    // this lane's four rows are half of one 16-byte chunk
+    if ((EPI == EPI_STORE || EPI == EPI_INITZ || EPI == EPI_RESID) && p.k8_hi && n < p.N && mq < p.M) {
+      unsigned short h[4], l[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) split_half(outv[r], h[r], l[r]);
+      const long long o = ((long long)(mq >> 3) * p.k8_ld + n) * 8 + (mq & 7);
+      *(uint2*)(p.k8_hi + o) = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
+      if (p.k8_lo) *(uint2*)(p.k8_lo + o) = make_uint2(pack2(l[0], l[1]), pack2(l[2], l[3]));
+    }
+  }
+}
+
+// Compile-time walk over the WT x WT tiles of a wavefront (constant indices keep the accumulators in registers).
+template <int EPI, int WT, int IJ>
+struct EpilogueWalk {
+  static __device__ __forceinline__ void run(const GemmP& p, floatx16 (&acc)[WT][WT], float unscale, int mbase, int nbase, int split,
+                                             double& red0, double& red1) {
+    epilogue_tile<EPI>(p, acc[IJ / WT][IJ % WT], unscale, mbase + (IJ / WT) * 32, nbase + (IJ % WT) * 32, split, red0, red1);
+    EpilogueWalk<EPI, WT, IJ + 1>::run(p, acc, unscale, mbase, nbase, split, red0, red1);
+  }
+};
+template <int EPI, int WT>
+struct EpilogueWalk<EPI, WT, WT * WT> {
+  static __device__ __forceinline__ void run(const GemmP&, floatx16 (&)[WT][WT], float, int, int, int, double&, double&) {}
+};
+template <int EPI, int WT>
+__device__ __forceinline__ void epilogue(const GemmP& p, floatx16 (&acc)[WT][WT], float unscale, int mbase, int nbase, int split,
+                                         double& red0, double& red1) {
+  EpilogueWalk<EPI, WT, 0>::run(p, acc, unscale, mbase, nbase, split, red0, red1);
+}
+
+template <int NPP, int NPQ, bool NN, bool BF, int WT>
+__global__ __launch_bounds__(256, WT == 4 ? 1 : 2) void gemm_kernel(const GemmP p) {
+  constexpr int BM = Tile<WT>::BM, BN = Tile<WT>::BN, BK = Tile<WT>::BK, LDK = Tile<WT>::LDK, KS = BK / 16;
   __shared__ __attribute__((aligned(16))) unsigned short sP[NPP][BM * LDK];
   __shared__ __attribute__((aligned(16))) unsigned short sQ[NPQ][BN * LDK];
   __shared__ double sred[4][2];
@@ -153,7 +279,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
     while (tm * (tm + 1) / 2 > t) --tm;
     tn = t - tm * (tm + 1) / 2;
   } else {
-    const int G = 8;
+    const int G = WT == 4 ? 4 : 8;
     const int per_group = G * p.tilesN;
     const int grp = t / per_group;
     const int first_m = grp * G;
@@ -168,145 +294,98 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
+  constexpr int WROWS = 32 * WT;   // rows (and columns) of the output owned by one wavefront
 
-  RowLoader<NPP> lp;
-  lp.init(p.P, m0);
-  RowLoader<NPQ> lq_row;
-  K8Loader<NPQ> lq_k8;
-  if (NN) lq_k8.init(p.Q, n0, p.N); else lq_row.init(p.Q, n0);
+  RowLoader<NPP, WT> lp;
+  lp.init(p.P, m0, k0);
+  RowLoader<NPQ, WT> lq_row;
+  K8Loader<NPQ, WT> lq_k8;
+  if (NN) lq_k8.init(p.Q, n0, p.N, k0); else lq_row.init(p.Q, n0, k0);
 
-  floatx16 acc[2][2];
+  floatx16 acc[WT][WT];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < WT; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < WT; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
+  // fragment addresses of this lane inside a tile (k step added per use)
+  const int offP = (wm * WROWS + (lane & 31)) * LDK + 8 * (lane >> 5);
+  const int offQ = (wn * WROWS + (lane & 31)) * LDK + 8 * (lane >> 5);
+  struct Frags { uint4 ph[WT], pl[WT], qh[WT], ql[WT]; };
+  auto read_frags = [&](Frags& f, int ks) {
+#pragma unroll
+    for (int i = 0; i < WT; ++i) {
+      const int off = offP + i * 32 * LDK + ks * 16;
+      f.ph[i] = *(const uint4*)(&sP[0][off]);
+      if (NPP == 2) f.pl[i] = *(const uint4*)(&sP[NPP - 1][off]);
+    }
+#pragma unroll
+    for (int j = 0; j < WT; ++j) {
+      const int off = offQ + j * 32 * LDK + ks * 16;
+      f.qh[j] = *(const uint4*)(&sQ[0][off]);
+      if (NPQ == 2) f.ql[j] = *(const uint4*)(&sQ[NPQ - 1][off]);
+    }
+  };
+  auto run_mfma = [&](const Frags& f) {
+    if (NPQ == 2) {
+#pragma unroll
+      for (int i = 0; i < WT; ++i)
+#pragma unroll
+        for (int j = 0; j < WT; ++j) acc[i][j] = mma<BF>(f.ph[i], f.ql[j], acc[i][j]);
+    }
+    if (NPP == 2) {
+#pragma unroll
+      for (int i = 0; i < WT; ++i)
+#pragma unroll
+        for (int j = 0; j < WT; ++j) acc[i][j] = mma<BF>(f.pl[i], f.qh[j], acc[i][j]);
+    }
+#pragma unroll
+    for (int i = 0; i < WT; ++i)
+#pragma unroll
+      for (int j = 0; j < WT; ++j) acc[i][j] = mma<BF>(f.ph[i], f.qh[j], acc[i][j]);
+  };
+
   if (k0 < k1) {
-    lp.load(k0, k1);
-    if (NN) lq_k8.load(p.Q, k0, k1); else lq_row.load(k0, k1);
+    lp.load(k1);
+    if (NN) lq_k8.load(k1); else lq_row.load(k1);
   }
   for (long long k = k0; k < k1; k += BK) {
     lp.store(sP);
     if (NN) lq_k8.store(sQ); else lq_row.store(sQ);
     __syncthreads();
     if (k + BK < k1) {  // next tile's global loads fly during the matrix work
-      lp.load(k + BK, k1);
-      if (NN) lq_k8.load(p.Q, k + BK, k1); else lq_row.load(k + BK, k1);
+      lp.load(k1);
+      if (NN) lq_k8.load(k1); else lq_row.load(k1);
     }
+    // software pipeline over the 16-deep steps: fragments of step ks+1 are read while step ks multiplies
+    Frags f[2];
+    read_frags(f[0], 0);
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      const int koff = ks * 16 + 8 * (lane >> 5);
-      uint4 ph[2], pl[2], qh[2], ql[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int off = (wm * 64 + i * 32 + (lane & 31)) * LDK + koff;
-        ph[i] = *(const uint4*)(&sP[0][off]);
-        if (NPP == 2) pl[i] = *(const uint4*)(&sP[NPP - 1][off]);
-      }
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int off = (wn * 64 + j * 32 + (lane & 31)) * LDK + koff;
-        qh[j] = *(const uint4*)(&sQ[0][off]);
-        if (NPQ == 2) ql[j] = *(const uint4*)(&sQ[NPQ - 1][off]);
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          if (NPQ == 2) acc[i][j] = mma<BF>(ph[i], ql[j], acc[i][j]);
-          if (NPP == 2) acc[i][j] = mma<BF>(pl[i], qh[j], acc[i][j]);
-          acc[i][j] = mma<BF>(ph[i], qh[j], acc[i][j]);
-        }
+    for (int ks = 0; ks < KS; ++ks) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (ks + 1 < KS) read_frags(f[(ks + 1) & 1], ks + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      run_mfma(f[ks & 1]);
     }
     __syncthreads();
   }
 
-  // ---- epilogue -----------------------------------------------------------------------------
+  // ---- epilogue (one specialised, fully unrolled body per epilogue kind) -------------------------
   float unscale = 1.0f;
   if (p.P.scale) unscale /= *p.P.scale;
   if (p.Q.scale) unscale /= *p.Q.scale;
   double red0 = 0.0, red1 = 0.0;
-  const float ab = p.alpha + p.beta;
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int n = n0 + wn * 64 + j * 32 + (lane & 31);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int mq = m0 + wm * 64 + i * 32 + 8 * q + 4 * (lane >> 5);  // rows mq .. mq+3
-        float outv[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int m = mq + r;
-          float v = acc[i][j][4 * q + r] * unscale;
-          outv[r] = 0.0f;
-          if (m >= p.M || n >= p.N) continue;
-          switch (p.epi) {
-            case EPI_PARTIAL:
-              p.out[((long long)split * p.M + m) * p.N + n] = v;
-              break;
-            case EPI_STORE:
-              p.out[(long long)m * p.ldo + n] = v;
-              outv[r] = v;
-              break;
-            case EPI_INITZ: {
-              const long long o = (long long)m * p.lda + n;
-              const float a = __builtin_fmaxf(v, 0.0f);
-              p.Z0s[o] = v;
-              p.Zs[o] = v;
-              p.As[o] = a;
-              outv[r] = a;
-              red0 += (double)a * (double)a;
-            } break;
-            case EPI_RESID: {
-              const float rr = p.Yin[(long long)m * p.ldy + n] - v;
-              outv[r] = rr;
-              red0 += (double)rr * (double)rr;
-            } break;
-            case EPI_AUPD: {
-              const long long o = (long long)p.oidx[m] * p.lda + n;
-              p.As[o] = __builtin_fmaxf(p.Zs[o], 0.0f) + v;
-            } break;
-            case EPI_ZUPD: {
-              const long long o = (long long)p.oidx[m] * p.lda + n;
-              const float a = p.As[o];
-              const float z1 = v;
-              float z;
-              if (p.write_out) {
-                const float z2 = (p.beta * a + p.alpha * z1) / ab;
-                const float cm = __builtin_fminf(z1, 0.0f);
-                const float costm = p.beta * a * a + p.alpha * (cm - z1) * (cm - z1);
-                const float cp = __builtin_fmaxf(z2, 0.0f);
-                const float costp = p.beta * (a - cp) * (a - cp) + p.alpha * (cp - z1) * (cp - z1);
-                z = costm < costp ? cm : cp;
-                p.Zs[o] = z;
-              } else {
-                z = p.Zs[o];
-              }
-              const float ra = a - __builtin_fmaxf(z, 0.0f);
-              const float rz = z - z1;
-              red0 += (double)ra * (double)ra;
-              red1 += (double)rz * (double)rz;
-            } break;
-            default:
-              break;
-          }
-        }
-        // optional K8-plane copy of the produced tile (its rows are the k axis of the consumer):
-        // this lane's four rows are half of one 16-byte chunk; rows >= M inside a chunk are zeros
-        if (p.k8_hi && n < p.N && mq < p.M) {
-          unsigned short h[4], l[4];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) split_half(outv[r], h[r], l[r]);
-          const long long o = ((long long)(mq >> 3) * p.k8_ld + n) * 8 + (mq & 7);
-          *(uint2*)(p.k8_hi + o) = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
-          if (p.k8_lo) *(uint2*)(p.k8_lo + o) = make_uint2(pack2(l[0], l[1]), pack2(l[2], l[3]));
-        }
-      }
-    }
+  const int mbase = m0 + wm * WROWS + 4 * (lane >> 5), nbase = n0 + wn * WROWS + (lane & 31);
+  switch (p.epi) {
+    case EPI_PARTIAL: epilogue<EPI_PARTIAL, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
+    case EPI_STORE: epilogue<EPI_STORE, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
+    case EPI_INITZ: epilogue<EPI_INITZ, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
+    case EPI_RESID: epilogue<EPI_RESID, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
+    case EPI_AUPD: epilogue<EPI_AUPD, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
+    default: epilogue<EPI_ZUPD, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
+  }
   if (p.red) {
     red0 = wave_sum(red0);
     red1 = wave_sum(red1);
@@ -326,6 +405,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmP p) {
 // host side
 // ---------------------------------------------------------------------------------------------
 void gemm_plan_tiles(GemmP& p, bool nn, int want_splits) {
+  // 256x256 tiles when they still give every CU a block; otherwise 128x128
+  {
+    const long long t4m = (p.M + 255) / 256, t4n = (p.N + 255) / 256;
+    const long long n4 = p.triangle ? t4m * (t4m + 1) / 2 : t4m * t4n;
+    p.wt = (p.force_wt == 4 && p.M >= 256 && p.N >= 256 && n4 * (want_splits > 1 ? want_splits : 1) >= 256) ? 4 : 2;
+  }
+  const int BM = 64 * p.wt, BN = 64 * p.wt, BK = p.wt == 2 ? 64 : 32;
   p.tilesM = (p.M + BM - 1) / BM;
   p.tilesN = (p.N + BN - 1) / BN;
   p.ntiles = p.triangle ? p.tilesM * (p.tilesM + 1) / 2 : p.tilesM * p.tilesN;
@@ -344,12 +430,15 @@ int gemm_grid_blocks(const GemmP& p) { return p.ntiles * p.splits; }
 
 template <int NPP, int NPQ, bool NN, bool BF>
 static void launch_one(strp_ctx* ctx, const GemmP& p) {
-  hipLaunchKernelGGL((gemm_kernel<NPP, NPQ, NN, BF>), dim3(gemm_grid_blocks(p)), dim3(256), 0, ctx->stream, p);
+  if (p.wt == 4)
+    hipLaunchKernelGGL((gemm_kernel<NPP, NPQ, NN, BF, 4>), dim3(gemm_grid_blocks(p)), dim3(256), 0, ctx->stream, p);
+  else
+    hipLaunchKernelGGL((gemm_kernel<NPP, NPQ, NN, BF, 2>), dim3(gemm_grid_blocks(p)), dim3(256), 0, ctx->stream, p);
 }
 
 strp_status launch_gemm(strp_ctx* ctx, GemmP& p, bool nn, bool bf16) {
   if (p.M <= 0 || p.N <= 0 || p.K <= 0) return fail(ctx, STRP_EINVAL, "gemm: empty shape");
-  if (p.ntiles <= 0 || p.splits <= 0) return fail(ctx, STRP_EINVAL, "gemm: tiles not planned");
+  if (p.ntiles <= 0 || p.splits <= 0 || (p.wt != 2 && p.wt != 4)) return fail(ctx, STRP_EINVAL, "gemm: tiles not planned");
   if (!p.P.hi || !p.Q.hi) return fail(ctx, STRP_EINVAL, "gemm: null operand plane");
   if ((p.M % 8) && p.k8_hi) return fail(ctx, STRP_EINVAL, "gemm: K8 output needs M %% 8 == 0");
   const int npp = p.P.lo ? 2 : 1, npq = p.Q.lo ? 2 : 1;

@@ -88,6 +88,8 @@ struct GemmP {
   PlaneOp P, Q;
   int M, N;
   long long K;
+  int force_wt;        // 4 requests the 256x256 tile (measured slower with one-deep prefetch; off by default)
+  int wt;              // 32x32 MFMA tiles per wavefront per dimension: 2 (128x128 blocks) or 4 (256x256), set by gemm_plan_tiles
   int tilesM, tilesN, ntiles;
   int triangle;        // P == Q, only tiles with tn <= tm are computed
   int splits;
