@@ -163,9 +163,10 @@ strp_status strp_mask_topk(strp_ctx* ctx, const float* score, int32_t n, int32_t
  * side == STRP_SIDE_FC1:  Lhs rows idx[0..s) of an [out x ld_lhs] matrix, Rhs [in x ld_rhs] (all
  *   rows), Gram [in x in];  W[idx, :] = Wsub, every other row of W zero.
  * Gram: fp32 symmetric, unregularised, leading dimension ldg.  W: [out x in] fp32, dense row-major.
- * chol (optional, fp64 [n x n], n = order of Gram): if chol_valid != 0 it holds the lower
- * Cholesky factor of Gram + lambda I from an earlier call and Gram is not read; otherwise the
- * factor is computed and, if chol != NULL, stored there for reuse.
+ * chol (optional, fp64 [n x n], n = order of Gram): factorisation cache.  It holds L^-1, the inverse
+ * of the lower Cholesky factor of Gram + lambda I (lower triangular, upper part zero).  If
+ * chol_valid != 0 it comes from an earlier call and Gram is not read; otherwise it is computed and,
+ * if chol != NULL, stored there for reuse.
  * Numeric failure (pivot <= 0) sets STRP_ENOTPD in the status word.
  */
 strp_status strp_refit(strp_ctx* ctx, strp_side side, const float* Gram, int32_t ldg, double lambda,
@@ -185,7 +186,7 @@ typedef struct {
   float* W1;           /* [f x d]     refitted fc1 (rows of pruned units zero)              */
   float* W2;           /* [d x f]     refitted fc2 (columns of pruned units zero)           */
   float* H;            /* [d x d]     X X^T                                                 */
-  double* cholH;       /* [d x d]     lower Cholesky factor of H + lam1 I                   */
+  double* cholH;       /* [d x d]     inverse of the lower Cholesky factor of H + lam1 I    */
   double* n2;          /* [f]         squared column norms of W2hat                         */
   float* score;        /* [f]         unit scores of the last selection                     */
   uint8_t* mask;       /* [f]         1 = kept                                              */
@@ -227,8 +228,8 @@ typedef struct {
 
 /*
  * strp_module_init -- Alg. 3 initialisation: Z0 = W1hat X, Z = Z0, A = relu(Z0), Y = W2hat A,
- * H = X X^T, lam1 = delta tr(H)/d, lam2 = delta |A|_F^2 / f, factor of H + lam1 I (the cached
- * pseudo-inverse of the listing), n2 = column norms of W2hat, W1 = W2 = 0, no mask.
+ * H = X X^T, lam1 = delta tr(H)/d, lam2 = delta |A|_F^2 / f, inverse Cholesky factor of H + lam1 I (the
+ * cached pseudo-inverse of the listing), n2 = column norms of W2hat, W1 = W2 = 0, no mask.
  */
 strp_status strp_module_init(strp_ctx* ctx, const strp_module_desc* desc, strp_module_state* st,
                              const strp_params* params);

@@ -1,139 +1,215 @@
-// fp64 dense kernels for the ridge systems: blocked Cholesky, right-side triangular solves built from
-// inverted 64x64 diagonal blocks plus rank-64 GEMM updates, and small cast / scatter helpers.
-// The Gram systems can reach condition numbers ~1e4, so factor and solve stay in fp64 (the chip's
-// vector fp64 rate equals its fp64 matrix rate, so these are plain FMA kernels staged through LDS).
+// fp64 dense kernels for the ridge systems: blocked Cholesky, inversion of the triangular factor by
+// recursive doubling, right-side solves as two triangular-aware GEMMs, and small cast / scatter helpers.
+// The Gram systems reach condition numbers ~1e4, so factor and solve stay in fp64.  The GEMM runs on the
+// fp64 matrix cores (v_mfma_f64_16x16x4_f64): same peak as the vector unit, far less LDS traffic per flop.
 #include "strp_internal.h"
 
 namespace strp {
 
-// ---------------------------------------------------------------------------------------------
-// dgemm: 64x64 tile per 256-thread block, 4x4 micro-tile per thread, K staged 16 at a time
-// ---------------------------------------------------------------------------------------------
-constexpr int DT = 64, DK = 16;
+typedef double doublex4 __attribute__((ext_vector_type(4)));
 
-__global__ __launch_bounds__(256) void dgemm_kernel(int M, int N, int K, double alpha, const double* A, long long rsa,
-                                                    long long csa, const double* B, long long rsb, long long csb,
-                                                    double beta, double* C, long long ldc, int lower) {
-  const int m0 = blockIdx.y * DT, n0 = blockIdx.x * DT;
-  if (lower && n0 > m0) return;
-  __shared__ double As[DK][DT + 2];
-  __shared__ double Bs[DK][DT + 2];
-  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
-  double acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+// ---------------------------------------------------------------------------------------------
+// dgemm: C = alpha * A * B + beta * C, element strides for A(m,k) and B(k,n), C row-major.
+//   block = 4 wavefronts (2x2), wavefront tile = WT x WT MFMA tiles of 16x16, K staged 16 at a time.
+//   batch (grid.z): operand pointers advance by sa / sb / sc elements per batch entry and the batch
+//   entry's M and K are clamped to lim_base - z * lim_step (ragged last block of a blocked algorithm).
+//   tri = 1: B is upper-triangular in (k, n) block terms (k < n0 + tile), tri = 2: k >= n0.
+//   lower != 0 skips output tiles entirely above the diagonal.
+// MFMA lane layout: A operand lane l = A[i = l % 16][k = l / 16], B operand lane l = B[k = l / 16][j = l % 16],
+// result register r of lane l = D[i = 4 r + l / 16][j = l % 16].
+// ---------------------------------------------------------------------------------------------
+struct DgemmP {
+  int M, N, K;
+  double alpha, beta;
+  const double* A; long long rsa, csa;
+  const double* B; long long rsb, csb;
+  double* C; long long ldc;
+  int lower, tri;
+  long long sa, sb, sc;
+  int lim_base, lim_step;   // lim_step == 0: no clamping
+  int clamp_k;              // clamp K like M (square ragged block)
+};
 
-  for (int k0 = 0; k0 < K; k0 += DK) {
+template <int WT>
+__global__ __launch_bounds__(256) void dgemm_kernel(const DgemmP p) {
+  constexpr int TS = 32 * WT;      // block tile (rows and columns)
+  constexpr int DK = 16;
+  constexpr int LD = TS + 4;
+  __shared__ double As[DK][LD];
+  __shared__ double Bs[DK][LD];
+  const int z = blockIdx.z;
+  int M = p.M, K = p.K;
+  if (p.lim_step) {
+    const int lim = p.lim_base - z * p.lim_step;
+    M = M < lim ? M : lim;
+    if (p.clamp_k) K = K < lim ? K : lim;
+  }
+  const int N = p.N;
+  const int m0 = blockIdx.y * TS, n0 = blockIdx.x * TS;
+  if (M <= 0 || m0 >= M) return;
+  if (p.lower && n0 >= m0 + TS) return;
+  const double* A = p.A + (long long)z * p.sa;
+  const double* B = p.B + (long long)z * p.sb;
+  double* C = p.C + (long long)z * p.sc;
+  int kbeg = 0, kend = K;
+  if (p.tri == 1) kend = (n0 + TS < K) ? n0 + TS : K;
+  if (p.tri == 2) kbeg = (n0 / DK) * DK;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  constexpr int EPT = TS * DK / 256;   // elements per thread per operand tile (8 or 4)
+  doublex4 acc[WT][WT];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < WT; ++i)
+#pragma unroll
+    for (int j = 0; j < WT; ++j) acc[i][j] = doublex4{0.0, 0.0, 0.0, 0.0};
+
+  double ra[EPT], rb[EPT];
+  auto gload = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) {
       const int e = tid + 256 * i;
       int m, k;
-      if (csa == 1) { m = e / DK; k = e % DK; } else { k = e / DT; m = e % DT; }
-      double v = 0.0;
-      if (m0 + m < M && k0 + k < K) v = A[(long long)(m0 + m) * rsa + (long long)(k0 + k) * csa];
-      As[k][m] = v;
+      if (p.csa == 1) { m = e / DK; k = e % DK; } else { k = e / TS; m = e % TS; }
+      ra[i] = (m0 + m < M && k0 + k < kend) ? A[(long long)(m0 + m) * p.rsa + (long long)(k0 + k) * p.csa] : 0.0;
       int n, kb;
-      if (csb == 1) { kb = e / DT; n = e % DT; } else { n = e / DK; kb = e % DK; }
-      double w = 0.0;
-      if (n0 + n < N && k0 + kb < K) w = B[(long long)(k0 + kb) * rsb + (long long)(n0 + n) * csb];
-      Bs[kb][n] = w;
+      if (p.csb == 1) { kb = e / TS; n = e % TS; } else { n = e / DK; kb = e % DK; }
+      rb[i] = (n0 + n < N && k0 + kb < kend) ? B[(long long)(k0 + kb) * p.rsb + (long long)(n0 + n) * p.csb] : 0.0;
     }
+  };
+  auto sstore = [&]() {
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) {
+      const int e = tid + 256 * i;
+      int m, k;
+      if (p.csa == 1) { m = e / DK; k = e % DK; } else { k = e / TS; m = e % TS; }
+      As[k][m] = ra[i];
+      int n, kb;
+      if (p.csb == 1) { kb = e / TS; n = e % TS; } else { n = e / DK; kb = e % DK; }
+      Bs[kb][n] = rb[i];
+    }
+  };
+  if (kbeg < kend) gload(kbeg);
+  for (int k0 = kbeg; k0 < kend; k0 += DK) {
+    sstore();
     __syncthreads();
+    if (k0 + DK < kend) gload(k0 + DK);
 #pragma unroll
-    for (int kk = 0; kk < DK; ++kk) {
-      double a[4], b[4];
+    for (int ks = 0; ks < DK / 4; ++ks) {
+      double af[WT], bf[WT];
+      const int kk = ks * 4 + (lane >> 4);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+      for (int i = 0; i < WT; ++i) af[i] = As[kk][wm * 16 * WT + i * 16 + (lane & 15)];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+      for (int j = 0; j < WT; ++j) bf[j] = Bs[kk][wn * 16 * WT + j * 16 + (lane & 15)];
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < WT; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fma(a[i], b[j], acc[i][j]);
+        for (int j = 0; j < WT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(af[i], bf[j], acc[i][j], 0, 0, 0);
     }
     __syncthreads();
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int m = m0 + ty * 4 + i;
-    if (m >= M) continue;
+  for (int i = 0; i < WT; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int n = n0 + tx * 4 + j;
-      if (n >= N) continue;
-      double* c = C + (long long)m * ldc + n;
-      *c = (beta == 0.0) ? alpha * acc[i][j] : alpha * acc[i][j] + beta * (*c);
+    for (int j = 0; j < WT; ++j) {
+      const int n = n0 + wn * 16 * WT + j * 16 + (lane & 15);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int m = m0 + wm * 16 * WT + i * 16 + 4 * r + (lane >> 4);
+        if (m < M && n < N) {
+          double* c = C + (long long)m * p.ldc + n;
+          const double v = p.alpha * acc[i][j][r];
+          *c = (p.beta == 0.0) ? v : v + p.beta * (*c);
+        }
+      }
     }
-  }
 }
 
-strp_status dgemm(strp_ctx* ctx, int M, int N, int K, double alpha, const double* A, long long rsa, long long csa,
-                  const double* B, long long rsb, long long csb, double beta, double* C, long long ldc, int lower) {
-  if (M <= 0 || N <= 0) return STRP_OK;
-  dim3 grid((N + DT - 1) / DT, (M + DT - 1) / DT);
-  hipLaunchKernelGGL(dgemm_kernel, grid, dim3(256), 0, ctx->stream, M, N, K, alpha, A, rsa, csa, B, rsb, csb, beta, C,
-                     ldc, lower);
+static strp_status dgemm_launch(strp_ctx* ctx, const DgemmP& p, int batch) {
+  if (p.M <= 0 || p.N <= 0 || batch <= 0) return STRP_OK;
+  const bool big = p.M > 64 && p.N > 64;
+  const int ts = big ? 128 : 64;
+  dim3 grid((p.N + ts - 1) / ts, (p.M + ts - 1) / ts, batch);
+  if (big)
+    hipLaunchKernelGGL((dgemm_kernel<4>), grid, dim3(256), 0, ctx->stream, p);
+  else
+    hipLaunchKernelGGL((dgemm_kernel<2>), grid, dim3(256), 0, ctx->stream, p);
   STRP_HIP(ctx, hipGetLastError());
   return STRP_OK;
 }
 
+strp_status dgemm(strp_ctx* ctx, int M, int N, int K, double alpha, const double* A, long long rsa, long long csa,
+                  const double* B, long long rsb, long long csb, double beta, double* C, long long ldc, int lower) {
+  DgemmP p;
+  memset(&p, 0, sizeof(p));
+  p.M = M; p.N = N; p.K = K; p.alpha = alpha; p.beta = beta;
+  p.A = A; p.rsa = rsa; p.csa = csa; p.B = B; p.rsb = rsb; p.csb = csb; p.C = C; p.ldc = ldc; p.lower = lower;
+  return dgemm_launch(ctx, p, 1);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Diagonal block: Cholesky of a jb x jb block (jb <= 64) in LDS and the inverse of its factor
+// (inverse by recursive doubling: V21 = -V22 (L21 V11) for blocks of 1, 2, 4, ... 32)
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld, int jb, double* invd, int32_t* status,
-                                                         int block_row0) {
+__global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld, int jb, double* invd, int32_t* status) {
   __shared__ double S[NB][NB + 1];
   __shared__ double V[NB][NB + 1];
-  __shared__ int bad;
-  const int tid = threadIdx.x;
-  if (tid == 0) bad = 0;
+  __shared__ double Tm[NB][NB + 1];
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   for (int e = tid; e < NB * NB; e += 256) {
-    const int i = e / NB, j = e % NB;
-    S[i][j] = (i < jb && j <= i) ? A[(long long)i * ld + j] : 0.0;
+    const int i = e >> 6, j = e & 63;
+    S[i][j] = (i < jb && j <= i) ? A[(long long)i * ld + j] : ((i == j) ? 1.0 : 0.0);
     V[i][j] = 0.0;
   }
   __syncthreads();
   for (int j = 0; j < jb; ++j) {
+    const double dj = S[j][j];
+    const bool ok = dj > 0.0;
+    const double piv = ok ? sqrt(dj) : 1.0;
+    __syncthreads();                      // everyone has read the pivot before it is overwritten
     if (tid == 0) {
-      const double dj = S[j][j];
-      if (!(dj > 0.0)) {
-        bad = 1;
-        atomicCAS(status, 0, (int)STRP_ENOTPD);
-        S[j][j] = 1.0;
-      } else {
-        S[j][j] = sqrt(dj);
-      }
+      S[j][j] = piv;
+      if (!ok) atomicCAS(status, 0, (int)STRP_ENOTPD);
     }
-    __syncthreads();
-    const double piv = S[j][j];
-    for (int i = j + 1 + tid; i < jb; i += 256) S[i][j] /= piv;
+    if (tid > j && tid < jb) S[tid][j] /= piv;
     __syncthreads();
     // trailing update of the lower triangle: S[i][k] -= S[i][j] * S[k][j], j < k <= i
-    const int rem = jb - j - 1;
-    for (int e = tid; e < rem * rem; e += 256) {
-      const int i = j + 1 + e / rem, k = j + 1 + e % rem;
-      if (k <= i) S[i][k] -= S[i][j] * S[k][j];
+    for (int i = j + 1 + ty; i < jb; i += 16) {
+      const double lij = S[i][j];
+      for (int k = j + 1 + tx; k <= i; k += 16) S[i][k] -= lij * S[k][j];
     }
     __syncthreads();
   }
-  // inverse of the lower factor, one column per thread (forward substitution)
-  if (tid < jb) {
-    const int c = tid;
-    for (int i = c; i < jb; ++i) {
-      double acc = (i == c) ? 1.0 : 0.0;
-      for (int k = c; k < i; ++k) acc -= S[i][k] * V[k][c];
-      V[i][c] = acc / S[i][i];
-    }
-  }
+  // inverse of the (padded to 64, identity beyond jb) lower factor
+  if (tid < NB) V[tid][tid] = 1.0 / S[tid][tid];
   __syncthreads();
+  for (int b = 1; b < NB; b <<= 1) {
+    // Tm[r2 + i][c] = sum_k L21[i][k] V11[k][c]   for every pair of blocks (r1 = 2 b p, r2 = r1 + b)
+    for (int e = tid; e < (NB / 2) * b; e += 256) {
+      const int c = e % b, row = e / b;           // row = p * b + i over all pairs
+      const int pr = row / b, i = row % b;
+      const int r1 = 2 * b * pr, r2 = r1 + b;
+      double acc = 0.0;
+      for (int k = c; k < b; ++k) acc += S[r2 + i][r1 + k] * V[r1 + k][r1 + c];
+      Tm[r2 + i][c] = acc;
+    }
+    __syncthreads();
+    for (int e = tid; e < (NB / 2) * b; e += 256) {
+      const int c = e % b, row = e / b;
+      const int pr = row / b, i = row % b;
+      const int r1 = 2 * b * pr, r2 = r1 + b;
+      double acc = 0.0;
+      for (int k = 0; k <= i; ++k) acc += V[r2 + i][r2 + k] * Tm[r2 + k][c];
+      V[r2 + i][r1 + c] = -acc;
+    }
+    __syncthreads();
+  }
   for (int e = tid; e < NB * NB; e += 256) {
-    const int i = e / NB, j = e % NB;
-    invd[e] = V[i][j];
+    const int i = e >> 6, j = e & 63;
+    invd[e] = (i < jb && j < jb) ? V[i][j] : 0.0;
     if (i < jb && j < jb) A[(long long)i * ld + j] = (j <= i) ? S[i][j] : 0.0;
   }
-  (void)block_row0;
 }
 
 // X[rows x jb] <- X * Mt, Mt[k][c] = trans ? Linv[c][k] : Linv[k][c]; one block per 64 rows
@@ -143,7 +219,7 @@ __global__ __launch_bounds__(256) void panel_mul_kernel(double* X, long long ldx
   __shared__ double Ms[NB][NB + 1];
   const int tid = threadIdx.x, r0 = blockIdx.x * NB;
   for (int e = tid; e < NB * NB; e += 256) {
-    const int i = e / NB, j = e % NB;
+    const int i = e >> 6, j = e & 63;
     Xs[i][j] = (r0 + i < rows && j < jb) ? X[(long long)(r0 + i) * ldx + j] : 0.0;
     Ms[i][j] = trans ? invd[j * NB + i] : invd[e];
   }
@@ -191,7 +267,7 @@ strp_status chol_factor(strp_ctx* ctx, double* A, int n, long long ld, double* i
     const int jb = (n - j0 < NB) ? (n - j0) : NB;
     double* Ajj = A + (long long)j0 * ld + j0;
     double* inv = invd + (long long)(j0 / NB) * NB * NB;
-    hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(256), 0, ctx->stream, Ajj, ld, jb, inv, status, j0);
+    hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(256), 0, ctx->stream, Ajj, ld, jb, inv, status);
     STRP_HIP(ctx, hipGetLastError());
     const int rest = n - j0 - jb;
     if (rest > 0) {
@@ -204,28 +280,57 @@ strp_status chol_factor(strp_ctx* ctx, double* A, int n, long long ld, double* i
   return STRP_OK;
 }
 
-strp_status chol_solve_right(strp_ctx* ctx, const double* L, int n, long long ldl, const double* invd, double* X, int m,
-                             long long ldx) {
-  ProfScope ps(ctx, "chol_solve_f64", 2.0 * (double)m * n * n, 8.0 * ((double)n * n * 0.5 + 2.0 * (double)m * n));
-  // V L^T = X  (column blocks ascending), then  X L = V  (descending); both in place.
-  for (int j0 = 0; j0 < n; j0 += NB) {
-    const int jb = (n - j0 < NB) ? (n - j0) : NB;
-    const double* inv = invd + (long long)(j0 / NB) * NB * NB;
-    STRP_TRY(panel_mul(ctx, X + j0, ldx, m, jb, inv, 1));
-    const int j1 = j0 + jb, rest = n - j1;
-    if (rest > 0)
-      STRP_TRY(dgemm(ctx, m, rest, jb, -1.0, X + j0, ldx, 1, L + (long long)j1 * ldl + j0, 1, ldl, 1.0, X + j1, ldx, 0));
-  }
-  const int nblk = (n + NB - 1) / NB;
-  for (int b = nblk - 1; b >= 0; --b) {
-    const int j0 = b * NB;
-    const int jb = (n - j0 < NB) ? (n - j0) : NB;
-    const double* inv = invd + (long long)b * NB * NB;
-    STRP_TRY(panel_mul(ctx, X + j0, ldx, m, jb, inv, 0));
-    if (j0 > 0)
-      STRP_TRY(dgemm(ctx, m, j0, jb, -1.0, X + j0, ldx, 1, L + (long long)j0 * ldl, ldl, 1, 1.0, X, ldx, 0));
+// Linv = L^-1 (lower triangular, n x n, leading dimension n) from the factor and its inverted 64-blocks.
+// tmp: n x n fp64 scratch.  Doubling: for block size b = 64, 128, ...: V21 = -V22 (L21 V11) for every pair of
+// adjacent diagonal blocks, all pairs of a level in one batched launch.
+__global__ __launch_bounds__(256) void place_diag_blocks_kernel(const double* invd, int n, double* Linv) {
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (long long)n * n) return;
+  const int i = (int)(e / n), j = (int)(e % n);
+  double v = 0.0;
+  if ((i / NB) == (j / NB)) v = invd[(long long)(i / NB) * NB * NB + (i % NB) * NB + (j % NB)];
+  Linv[e] = v;
+}
+
+strp_status tri_inverse(strp_ctx* ctx, const double* L, int n, long long ldl, const double* invd, double* Linv, double* tmp) {
+  ProfScope ps(ctx, "tri_inverse_f64", (double)n * n * n / 3.0, 24.0 * (double)n * n);
+  hipLaunchKernelGGL(place_diag_blocks_kernel, dim3((unsigned)(((long long)n * n + 255) / 256)), dim3(256), 0, ctx->stream, invd, n, Linv);
+  STRP_HIP(ctx, hipGetLastError());
+  for (int b = NB; b < n; b <<= 1) {
+    const int pairs = (n - b + 2 * b - 1) / (2 * b);   // pairs whose second block is non-empty
+    DgemmP p;
+    memset(&p, 0, sizeof(p));
+    // tmp21 = L21 V11
+    p.M = b; p.N = b; p.K = b; p.alpha = 1.0; p.beta = 0.0;
+    p.A = L + (long long)b * ldl; p.rsa = ldl; p.csa = 1;
+    p.B = Linv; p.rsb = n; p.csb = 1;
+    p.C = tmp + (long long)b * n; p.ldc = n;
+    p.sa = 2LL * b * ldl + 2LL * b; p.sb = 2LL * b * n + 2LL * b; p.sc = p.sb;
+    p.lim_base = n - b; p.lim_step = 2 * b; p.lower = 0;
+    STRP_TRY(dgemm_launch(ctx, p, pairs));
+    // V21 = -V22 tmp21   (M and K both limited to the rows of the second block)
+    p.alpha = -1.0;
+    p.A = Linv + (long long)b * n + b; p.rsa = n; p.csa = 1; p.sa = p.sb;
+    p.B = tmp + (long long)b * n; p.rsb = n; p.csb = 1;
+    p.C = Linv + (long long)b * n; p.ldc = n;
+    p.clamp_k = 1;
+    STRP_TRY(dgemm_launch(ctx, p, pairs));
   }
   return STRP_OK;
+}
+
+// X <- X (L L^T)^-1 = (X Linv^T) Linv for X [m x n] (leading dimension n); tmp: m x n scratch.
+strp_status apply_inverse_right(strp_ctx* ctx, const double* Linv, int n, double* X, int m, double* tmp) {
+  ProfScope ps(ctx, "chol_solve_f64", 2.0 * (double)m * n * n, 8.0 * ((double)n * n + 4.0 * (double)m * n));
+  DgemmP p;
+  memset(&p, 0, sizeof(p));
+  p.M = m; p.N = n; p.K = n; p.alpha = 1.0; p.beta = 0.0;
+  // tmp[m, j] = sum_{k <= j} X[m, k] Linv[j, k]
+  p.A = X; p.rsa = n; p.csa = 1; p.B = Linv; p.rsb = 1; p.csb = n; p.C = tmp; p.ldc = n; p.tri = 1;
+  STRP_TRY(dgemm_launch(ctx, p, 1));
+  // X[m, j] = sum_{k >= j} tmp[m, k] Linv[k, j]
+  p.A = tmp; p.B = Linv; p.rsb = n; p.csb = 1; p.C = X; p.tri = 2;
+  return dgemm_launch(ctx, p, 1);
 }
 
 // ---------------------------------------------------------------------------------------------

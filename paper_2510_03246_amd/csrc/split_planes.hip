@@ -1,0 +1,203 @@
+// Split kernels: fp32 / bf16 / fp64 sources -> fp16 operand planes in the panel-major chunk layout
+//   offset(k, r) = (((r / 128) * KG + k / 8) * 128 + r % 128) * 8 + k % 8
+// (see gemm_mfma.hip).  All padding (rows up to a full panel, k up to a full group) is written as zero.
+#include "strp_internal.h"
+
+namespace strp {
+
+__device__ __forceinline__ unsigned short sp_half_bits(float x) {
+  _Float16 h = (_Float16)x;
+  return __builtin_bit_cast(unsigned short, h);
+}
+__device__ __forceinline__ void sp_split_half(float x, unsigned short& hi, unsigned short& lo) {
+  x = __builtin_fminf(__builtin_fmaxf(x, -65504.0f), 65504.0f);
+  _Float16 h = (_Float16)x;
+  hi = __builtin_bit_cast(unsigned short, h);
+  lo = sp_half_bits(x - (float)h);
+}
+__device__ __forceinline__ unsigned int sp_pack2(unsigned short a, unsigned short b) {
+  return (unsigned int)a | ((unsigned int)b << 16);
+}
+
+// Activations [rows x T] (optionally gathered by idx): one thread converts 8 rows x 8 tokens.
+//   T-planes (contraction over tokens,   k = token,   r = channel row): [ceil(rows/128)][ceil(T/8)][128][8]
+//   C-planes (contraction over channels, k = channel, r = token):       [ceil(T/128)][ceil(rows/8)][128][8]
+// grid.x walks token groups of 8 (256 per block), grid.y row groups of 8 (covering the padded panel rows).
+template <bool SRC_BF16>
+__global__ __launch_bounds__(256) void split_act_kernel(const void* src, long long lds, const int* idx, int rows, long long T,
+                                                        int relu_t, int relu_c, unsigned short* t_hi, unsigned short* t_lo,
+                                                        unsigned short* c_hi, unsigned short* c_lo) {
+  const int rg = blockIdx.y;                                        // row group
+  const long long tg = (long long)blockIdx.x * 256 + threadIdx.x;  // token group
+  const long long TG = (T + 7) >> 3;
+  const long long TGa = (TG + 1) & ~1LL;                            // allocated token groups (even)
+  const long long TGpad = ((T + 127) >> 7) << 4;                    // token groups covered by whole token panels
+  const int KGc = (rows + 7) >> 3;
+  const int KGa = (KGc + 1) & ~1;                                   // allocated channel groups (even)
+  if (tg >= TGpad) return;
+  float v[8][8];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const int row = rg * 8 + r;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) v[r][c] = 0.0f;
+    if (row < rows && tg < TG) {
+      const long long srow = idx ? (long long)idx[row] : (long long)row;
+      const long long t0 = tg * 8;
+      if (SRC_BF16) {
+        const uint4 w = *(const uint4*)((const unsigned short*)src + srow * lds + t0);
+        const unsigned int ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          v[r][2 * c] = __builtin_bit_cast(float, ww[c] << 16);
+          v[r][2 * c + 1] = __builtin_bit_cast(float, ww[c] & 0xffff0000u);
+        }
+      } else {
+        const float4 a = *(const float4*)((const float*)src + srow * lds + t0);
+        const float4 b = *(const float4*)((const float*)src + srow * lds + t0 + 4);
+        v[r][0] = a.x; v[r][1] = a.y; v[r][2] = a.z; v[r][3] = a.w;
+        v[r][4] = b.x; v[r][5] = b.y; v[r][6] = b.z; v[r][7] = b.w;
+      }
+#pragma unroll
+      for (int c = 0; c < 8; ++c)
+        if (t0 + c >= T) v[r][c] = 0.0f;
+    }
+  }
+  if (t_hi && tg < TGa) {  // chunk (k-group = tg, row): the 8 rows of this thread are 8 consecutive chunks
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const int row = rg * 8 + r;
+      unsigned short h[8], l[8];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) sp_split_half(relu_t ? __builtin_fmaxf(v[r][c], 0.0f) : v[r][c], h[c], l[c]);
+      const long long o = ((((long long)(row >> 7)) * TGa + tg) * 128 + (row & 127)) * 8;
+      *(uint4*)(t_hi + o) = make_uint4(sp_pack2(h[0], h[1]), sp_pack2(h[2], h[3]), sp_pack2(h[4], h[5]), sp_pack2(h[6], h[7]));
+      if (t_lo) *(uint4*)(t_lo + o) = make_uint4(sp_pack2(l[0], l[1]), sp_pack2(l[2], l[3]), sp_pack2(l[4], l[5]), sp_pack2(l[6], l[7]));
+    }
+  }
+  if (c_hi && rg < KGa) {  // chunk (k-group = rg, token): the 8 tokens of this thread are 8 consecutive chunks
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const long long tok = tg * 8 + c;
+      unsigned short h[8], l[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) sp_split_half(relu_c ? __builtin_fmaxf(v[r][c], 0.0f) : v[r][c], h[r], l[r]);
+      const long long o = (((tok >> 7) * KGa + rg) * 128 + (tok & 127)) * 8;
+      *(uint4*)(c_hi + o) = make_uint4(sp_pack2(h[0], h[1]), sp_pack2(h[2], h[3]), sp_pack2(h[4], h[5]), sp_pack2(h[6], h[7]));
+      if (c_lo) *(uint4*)(c_lo + o) = make_uint4(sp_pack2(l[0], l[1]), sp_pack2(l[2], l[3]), sp_pack2(l[4], l[5]), sp_pack2(l[6], l[7]));
+    }
+  }
+}
+
+strp_status split_act(strp_ctx* ctx, const void* src, int src_dtype, long long lds, const int* idx, int rows, long long T,
+                      int relu_t, int relu_c, unsigned short* t_hi, unsigned short* t_lo, unsigned short* c_hi,
+                      unsigned short* c_lo) {
+  if (rows <= 0 || T <= 0) return fail(ctx, STRP_EINVAL, "split_act: empty");
+  if (lds % 8) return fail(ctx, STRP_EINVAL, "split_act: source pitch must be a multiple of 8");
+  const long long TGpad = ((T + 127) >> 7) << 4;
+  const int rgroups = t_hi ? (int)(((rows + 127) / 128) * 16) : (int)plane_kg(rows);
+  dim3 grid((unsigned)((TGpad + 255) / 256), (unsigned)rgroups);
+  const double es = src_dtype == STRP_BF16 ? 2.0 : 4.0;
+  const double wb = (t_hi ? 2.0 : 0.0) + (t_lo ? 2.0 : 0.0) + (c_hi ? 2.0 : 0.0) + (c_lo ? 2.0 : 0.0);
+  ProfScope ps(ctx, "split_act", 0.0, (es + wb) * (double)rows * (double)T);
+  if (src_dtype == STRP_BF16)
+    hipLaunchKernelGGL((split_act_kernel<true>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, relu_c, t_hi, t_lo, c_hi, c_lo);
+  else
+    hipLaunchKernelGGL((split_act_kernel<false>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, relu_c, t_hi, t_lo, c_hi, c_lo);
+  STRP_HIP(ctx, hipGetLastError());
+  return STRP_OK;
+}
+
+__device__ __forceinline__ double small_src(const double* s, long long i) { return s[i]; }
+__device__ __forceinline__ double small_src(const float* s, long long i) { return (double)s[i]; }
+__device__ __forceinline__ double small_src(const unsigned short* s, long long i) {
+  return (double)__builtin_bit_cast(float, (unsigned int)s[i] << 16);
+}
+
+
+// Small matrices (weights): planes of src * scale with k = column (contraction), r = row:
+// [ceil(rows/128)][ceil(cols/8)][128][8], zero padded.  transpose != 0 reads src[c][r].
+// scale_dev (device, may be null = 1) is a power of two chosen by weight_scale.
+template <typename TS>
+__global__ __launch_bounds__(256) void split_small_kernel(const TS* src, long long lds, int rows, int cols, int transpose,
+                                                          const float* scale_dev, unsigned short* hi, unsigned short* lo) {
+  const int KG = (int)((((cols + 7) >> 3) + 1) & ~1);
+  const long long total = (long long)((rows + 127) >> 7) * KG * 1024;
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= total) return;
+  const int j = (int)(e & 7);
+  const int rr = (int)((e >> 3) & 127);
+  const long long pg = e >> 10;
+  const int g = (int)(pg % KG), pan = (int)(pg / KG);
+  const int r = pan * 128 + rr, c = g * 8 + j;
+  double x = 0.0;
+  if (r < rows && c < cols) x = transpose ? small_src(src, (long long)c * lds + r) : small_src(src, (long long)r * lds + c);
+  x *= scale_dev ? (double)*scale_dev : 1.0;
+  x = fmin(fmax(x, -65504.0), 65504.0);
+  const _Float16 h = (_Float16)x;
+  hi[e] = __builtin_bit_cast(unsigned short, h);
+  if (lo) {
+    const _Float16 l = (_Float16)(x - (double)h);
+    lo[e] = __builtin_bit_cast(unsigned short, l);
+  }
+}
+
+strp_status split_small(strp_ctx* ctx, const void* src, int src_kind, long long lds, int rows, int cols, int transpose,
+                        const float* scale_dev, unsigned short* hi, unsigned short* lo) {
+  const long long tot = (long long)plane_elems(rows, cols);
+  dim3 grid((unsigned)((tot + 255) / 256)), block(256);
+  if (src_kind == SRC_F64)
+    hipLaunchKernelGGL((split_small_kernel<double>), grid, block, 0, ctx->stream, (const double*)src, lds, rows, cols, transpose, scale_dev, hi, lo);
+  else if (src_kind == SRC_F32)
+    hipLaunchKernelGGL((split_small_kernel<float>), grid, block, 0, ctx->stream, (const float*)src, lds, rows, cols, transpose, scale_dev, hi, lo);
+  else
+    hipLaunchKernelGGL((split_small_kernel<unsigned short>), grid, block, 0, ctx->stream, (const unsigned short*)src, lds, rows, cols, transpose, scale_dev, hi, lo);
+  STRP_HIP(ctx, hipGetLastError());
+  return STRP_OK;
+}
+
+// scale = 2^e with max|x| * scale in [2^11, 2^12): keeps fp16 hi far from overflow and lo out of the subnormals.
+// Pass 1: grid-wide max of |x| through an integer atomic on the float bits (order-preserving for x >= 0).
+template <typename TS>
+__global__ __launch_bounds__(256) void absmax_kernel(const TS* src, long long lds, int rows, int cols, unsigned int* slot) {
+  float m = 0.0f;
+  const long long n = (long long)rows * cols;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+    const long long r = i / cols, c = i % cols;
+    m = __builtin_fmaxf(m, __builtin_fabsf((float)small_src(src, r * lds + c)));
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = __builtin_fmaxf(m, __shfl_down(m, o, 64));
+  if ((threadIdx.x & 63) == 0 && m > 0.0f) atomicMax(slot, __builtin_bit_cast(unsigned int, m));
+}
+// Pass 2: the slot (max bits) becomes the scale (float) in place.
+__global__ void scale_from_max_kernel(unsigned int* slot) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const float m = __builtin_bit_cast(float, *slot);
+  float s = 1.0f;
+  if (m > 0.0f && m < 3.0e38f) {
+    int e;
+    (void)frexpf(m, &e);        // m = q * 2^e, q in [0.5, 1)
+    s = ldexpf(1.0f, 12 - e);   // m * s in [2^11, 2^12)
+  }
+  *slot = __builtin_bit_cast(unsigned int, s);
+}
+
+strp_status weight_scale(strp_ctx* ctx, const void* src, int src_kind, long long lds, int rows, int cols, float* scale_out) {
+  STRP_TRY(fill_zero(ctx, scale_out, 4));
+  unsigned int* slot = (unsigned int*)scale_out;
+  long long blocks = ((long long)rows * cols + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  dim3 grid((unsigned)blocks), block(256);
+  if (src_kind == SRC_F64)
+    hipLaunchKernelGGL((absmax_kernel<double>), grid, block, 0, ctx->stream, (const double*)src, lds, rows, cols, slot);
+  else if (src_kind == SRC_F32)
+    hipLaunchKernelGGL((absmax_kernel<float>), grid, block, 0, ctx->stream, (const float*)src, lds, rows, cols, slot);
+  else
+    hipLaunchKernelGGL((absmax_kernel<unsigned short>), grid, block, 0, ctx->stream, (const unsigned short*)src, lds, rows, cols, slot);
+  hipLaunchKernelGGL(scale_from_max_kernel, dim3(1), dim3(1), 0, ctx->stream, slot);
+  STRP_HIP(ctx, hipGetLastError());
+  return STRP_OK;
+}
+
+}  // namespace strp

@@ -174,36 +174,6 @@ __global__ void axpby_scalar_kernel(double* sc, int dst, double a, int s0, doubl
   if (threadIdx.x == 0 && blockIdx.x == 0) sc[dst] = a * sc[s0] + (s1 >= 0 ? b * sc[s1] : 0.0);
 }
 
-// inverse of each 64x64 diagonal block of a stored lower factor (for a cached factor)
-__global__ __launch_bounds__(64) void diag_inverse_kernel(const double* L, int n, long long ld, double* invd) {
-  __shared__ double S[NB][NB + 1];
-  __shared__ double V[NB][NB + 1];
-  const int j0 = blockIdx.x * NB;
-  const int jb = (n - j0 < NB) ? (n - j0) : NB;
-  const int c = threadIdx.x;
-  for (int i = 0; i < NB; ++i) {
-    S[i][c] = (i < jb && c <= i && c < jb) ? L[(long long)(j0 + i) * ld + j0 + c] : 0.0;
-    V[i][c] = 0.0;
-  }
-  __syncthreads();
-  if (c < jb) {
-    for (int i = c; i < jb; ++i) {
-      double acc = (i == c) ? 1.0 : 0.0;
-      for (int k = c; k < i; ++k) acc -= S[i][k] * V[k][c];
-      V[i][c] = acc / S[i][i];
-    }
-  }
-  __syncthreads();
-  double* out = invd + (long long)blockIdx.x * NB * NB;
-  for (int i = 0; i < NB; ++i) out[i * NB + c] = V[i][c];
-}
-
-static strp_status diag_inverses(strp_ctx* ctx, const double* L, int n, long long ld, double* invd) {
-  hipLaunchKernelGGL(diag_inverse_kernel, dim3((n + NB - 1) / NB), dim3(64), 0, ctx->stream, L, n, ld, invd);
-  STRP_HIP(ctx, hipGetLastError());
-  return STRP_OK;
-}
-
 static unsigned blocks_for(long long n) { return (unsigned)((n + 255) / 256); }
 
 // scalar slots of strp_module_state::scalars
@@ -367,50 +337,50 @@ namespace strp {
 
 static inline int planes_for(int dtype, int prec) { return (dtype == STRP_F32 && prec == STRP_PREC_SPLIT) ? 2 : 1; }
 
-// ROW planes of `rows` (optionally gathered) activation rows, carved from the arena.
-static strp_status make_row_planes(strp_ctx* ctx, Arena& arena, const void* src, int dtype, long long lds, const int* idx, int rows,
-                                   long long T, int relu, int np, PlaneOp* out) {
-  const long long rows8 = round_up(rows, 8), ldp = round_up(T, 8);
-  STRP_TAKE(ctx, arena, hi, unsigned short, (size_t)rows8 * ldp);
+// Planes of `rows` (optionally gathered) activation rows for a product that contracts over the tokens.
+static strp_status make_t_planes(strp_ctx* ctx, Arena& arena, const void* src, int dtype, long long lds, const int* idx, int rows,
+                                 long long T, int relu, int np, PlaneOp* out) {
+  const size_t n = plane_elems(rows, T);
+  STRP_TAKE(ctx, arena, hi, unsigned short, n);
   unsigned short* lo = nullptr;
   if (np == 2) {
-    STRP_TAKE(ctx, arena, lo2, unsigned short, (size_t)rows8 * ldp);
+    STRP_TAKE(ctx, arena, lo2, unsigned short, n);
     lo = lo2;
   }
-  STRP_TRY(split_rows(ctx, src, dtype, lds, idx, rows, T, relu, 0, hi, lo, ldp, nullptr, nullptr));
-  *out = PlaneOp{hi, lo, ldp, (int)rows8, nullptr};
+  STRP_TRY(split_act(ctx, src, dtype, lds, idx, rows, T, relu, 0, hi, lo, nullptr, nullptr));
+  *out = PlaneOp{hi, lo, plane_kg(T), (rows + 127) / 128, nullptr};
   return STRP_OK;
 }
 
-// K8 planes of `rows` (optionally gathered) activation rows: the rows are the contraction axis of the consumer.
-static strp_status make_k8_planes(strp_ctx* ctx, Arena& arena, const void* src, int dtype, long long lds, const int* idx, int rows,
-                                  long long T, int relu, int np, PlaneOp* out) {
-  const long long rows8 = round_up(rows, 8);
-  STRP_TAKE(ctx, arena, hi, unsigned short, (size_t)rows8 * T);
+// Planes of `rows` (optionally gathered) activation rows for a product that contracts over those rows.
+static strp_status make_c_planes(strp_ctx* ctx, Arena& arena, const void* src, int dtype, long long lds, const int* idx, int rows,
+                                 long long T, int relu, int np, PlaneOp* out) {
+  const size_t n = plane_elems(T, rows);
+  STRP_TAKE(ctx, arena, hi, unsigned short, n);
   unsigned short* lo = nullptr;
   if (np == 2) {
-    STRP_TAKE(ctx, arena, lo2, unsigned short, (size_t)rows8 * T);
+    STRP_TAKE(ctx, arena, lo2, unsigned short, n);
     lo = lo2;
   }
-  STRP_TRY(split_rows(ctx, src, dtype, lds, idx, rows, T, 0, relu, nullptr, nullptr, 0, hi, lo));
-  *out = PlaneOp{hi, lo, T, 0, nullptr};
+  STRP_TRY(split_act(ctx, src, dtype, lds, idx, rows, T, 0, relu, nullptr, nullptr, hi, lo));
+  *out = PlaneOp{hi, lo, plane_kg(rows), (int)((T + 127) / 128), nullptr};
   return STRP_OK;
 }
 
-// ROW planes [rows][round_up(cols, 8)] of a small matrix (weights), scaled by a device-chosen power of two.
+// Planes of a small matrix (weights; k = column, r = row), scaled by a device-chosen power of two.
 static strp_status make_weight_planes(strp_ctx* ctx, Arena& arena, const void* src, int src_kind, long long lds, int rows, int cols,
                                       int transpose, int np, PlaneOp* out) {
-  const long long ldp = round_up(cols, 8);
+  const size_t n = plane_elems(rows, cols);
   STRP_TAKE(ctx, arena, scale, float, 64);
-  STRP_TAKE(ctx, arena, hi, unsigned short, (size_t)rows * ldp);
+  STRP_TAKE(ctx, arena, hi, unsigned short, n);
   unsigned short* lo = nullptr;
   if (np == 2) {
-    STRP_TAKE(ctx, arena, lo2, unsigned short, (size_t)rows * ldp);
+    STRP_TAKE(ctx, arena, lo2, unsigned short, n);
     lo = lo2;
   }
   STRP_TRY(weight_scale(ctx, src, src_kind, lds, transpose ? cols : rows, transpose ? rows : cols, scale));
-  STRP_TRY(split_small(ctx, src, src_kind, lds, rows, cols, transpose, scale, hi, lo, ldp));
-  *out = PlaneOp{hi, lo, ldp, rows, scale};
+  STRP_TRY(split_small(ctx, src, src_kind, lds, rows, cols, transpose, scale, hi, lo));
+  *out = PlaneOp{hi, lo, plane_kg(cols), (rows + 127) / 128, scale};
   return STRP_OK;
 }
 
@@ -429,49 +399,56 @@ static size_t nt_partial_elems(int M, int N, long long K, int triangle) {
   GemmP p;
   memset(&p, 0, sizeof(p));
   p.M = M; p.N = N; p.K = K; p.triangle = triangle;
-  gemm_plan_tiles(p, false, 1);
-  gemm_plan_tiles(p, false, plan_splits(p.ntiles, K));
+  gemm_plan_tiles(p, 1);
+  gemm_plan_tiles(p, plan_splits(p.ntiles, K));
   return (size_t)p.splits * (size_t)M * (size_t)N;
 }
 
 // C = P Q^T over K (ROW planes); partials in the arena (by value: released on return), fp64 reduction.
 static strp_status nt_product(strp_ctx* ctx, Arena arena, const PlaneOp& P, const PlaneOp& Q, int M, int N, long long K, int triangle,
-                              bool bf16, float* outf, long long ldof, double* outd, long long ldod, double* diag, int accumulate) {
+                              float* outf, long long ldof, double* outd, long long ldod, double* diag, int accumulate) {
   GemmP p;
   memset(&p, 0, sizeof(p));
   p.P = P; p.Q = Q; p.M = M; p.N = N; p.K = K; p.triangle = triangle;
   p.epi = EPI_PARTIAL;
-  gemm_plan_tiles(p, false, 1);
-  gemm_plan_tiles(p, false, plan_splits(p.ntiles, K));
+  gemm_plan_tiles(p, 1);
+  gemm_plan_tiles(p, plan_splits(p.ntiles, K));
   STRP_TAKE(ctx, arena, part, float, (size_t)p.splits * M * N);
   p.out = part;
-  STRP_TRY(launch_gemm(ctx, p, false, bf16));
+  STRP_TRY(launch_gemm(ctx, p));
   return launch_splitk_reduce(ctx, part, p.splits, M, N, triangle, outf, ldof, outd, ldod, diag, accumulate);
 }
 
 // Solve Wsub (Gram + lam I) = R with R = Lhs Rhs^T over the tokens.  Returns the fp64 solution
 // [m x n] (leading dimension n) in *sol_out; it lives in the arena passed by reference.
 struct RefitIn {
-  const float* Gram; long long ldg;       // fp32 Gram (used when Ld_ready == 0)
-  double* Ld; int Ld_ready;               // [n x n] fp64: 0 = scratch, 1 = holds Gram + lam I, 2 = holds the factor
+  const float* Gram; long long ldg;       // fp32 Gram (used when sys_ready == 0)
+  double* sys; int sys_ready;             // [n x n] fp64 scratch: 0 = empty, 1 = holds Gram + lam I
+  double* Linv; int linv_ready;           // [n x n] fp64 inverse of the Cholesky factor (output, or input if linv_ready)
   double lam; const double* lam_dev;
   PlaneOp Lhs, Rhs;
   int m, n; long long T;
 };
 
-static strp_status ridge_solve(strp_ctx* ctx, Arena& arena, const RefitIn& in, double** sol_out) {
-  const int n = in.n, m = in.m;
+// Factor the system in `sys` (which must hold Gram + lam I) and leave the inverse of its Cholesky factor in Linv.
+static strp_status factor_and_invert(strp_ctx* ctx, Arena arena, double* sys, int n, double* Linv) {
   const int nblk = (n + NB - 1) / NB;
   STRP_TAKE(ctx, arena, invd, double, (size_t)nblk * NB * NB);
-  if (in.Ld_ready == 2) {
-    STRP_TRY(diag_inverses(ctx, in.Ld, n, n, invd));
-  } else {
-    if (in.Ld_ready == 0) STRP_TRY(f32_to_f64_ridge(ctx, in.Gram, in.ldg, in.Ld, n, n, in.lam, in.lam_dev));
-    STRP_TRY(chol_factor(ctx, in.Ld, n, n, invd, ctx->status_dev));
+  STRP_TAKE(ctx, arena, tmp, double, (size_t)n * n);
+  STRP_TRY(chol_factor(ctx, sys, n, n, invd, ctx->status_dev));
+  return tri_inverse(ctx, sys, n, n, invd, Linv, tmp);
+}
+
+static strp_status ridge_solve(strp_ctx* ctx, Arena& arena, const RefitIn& in, double** sol_out) {
+  const int n = in.n, m = in.m;
+  if (!in.linv_ready) {
+    if (in.sys_ready == 0) STRP_TRY(f32_to_f64_ridge(ctx, in.Gram, in.ldg, in.sys, n, n, in.lam, in.lam_dev));
+    STRP_TRY(factor_and_invert(ctx, arena, in.sys, n, in.Linv));
   }
   STRP_TAKE(ctx, arena, R, double, (size_t)m * n);
-  STRP_TRY(nt_product(ctx, arena, in.Lhs, in.Rhs, m, n, in.T, 0, false, nullptr, 0, R, n, nullptr, 0));
-  STRP_TRY(chol_solve_right(ctx, in.Ld, n, n, invd, R, m, n));
+  STRP_TAKE(ctx, arena, tmp, double, (size_t)m * n);
+  STRP_TRY(nt_product(ctx, arena, in.Lhs, in.Rhs, m, n, in.T, 0, nullptr, 0, R, n, nullptr, 0));
+  STRP_TRY(apply_inverse_right(ctx, in.Linv, n, R, m, tmp));
   *sol_out = R;
   return STRP_OK;
 }
@@ -480,11 +457,10 @@ static strp_status ridge_solve(strp_ctx* ctx, Arena& arena, const RefitIn& in, d
 // Y as ROW planes, X as ROW planes and as K8 planes.
 struct CacheView {
   int nx, ny;
-  long long ldp;
-  PlaneOp Yrow, Xrow, Xk8;
+  PlaneOp Yt, Xt, Xc;   // Y and X for token-contraction products; X for the channel-contraction product W1 X
 };
 static size_t cache_layout(const strp_module_desc* desc, int prec, char* base, CacheView* v) {
-  const long long d = desc->d, T = desc->T, ldp = round_up(T, 8);
+  const long long d = desc->d, T = desc->T;
   const int nx = planes_for(desc->x_dtype, prec), ny = planes_for(STRP_F32, prec);
   size_t off = 256;
   auto take = [&](size_t elems) {
@@ -492,17 +468,17 @@ static size_t cache_layout(const strp_module_desc* desc, int prec, char* base, C
     off += (elems * 2 + 255) & ~size_t(255);
     return (unsigned short*)p;
   };
-  unsigned short* yh = take((size_t)d * ldp);
-  unsigned short* yl = ny == 2 ? take((size_t)d * ldp) : nullptr;
-  unsigned short* xh = take((size_t)d * ldp);
-  unsigned short* xl = nx == 2 ? take((size_t)d * ldp) : nullptr;
-  unsigned short* kh = take((size_t)d * T);
-  unsigned short* kl = nx == 2 ? take((size_t)d * T) : nullptr;
+  unsigned short* yh = take(plane_elems(d, T));
+  unsigned short* yl = ny == 2 ? take(plane_elems(d, T)) : nullptr;
+  unsigned short* xh = take(plane_elems(d, T));
+  unsigned short* xl = nx == 2 ? take(plane_elems(d, T)) : nullptr;
+  unsigned short* kh = take(plane_elems(T, d));
+  unsigned short* kl = nx == 2 ? take(plane_elems(T, d)) : nullptr;
   if (v) {
-    v->nx = nx; v->ny = ny; v->ldp = ldp;
-    v->Yrow = PlaneOp{yh, yl, ldp, (int)d, nullptr};
-    v->Xrow = PlaneOp{xh, xl, ldp, (int)d, nullptr};
-    v->Xk8 = PlaneOp{kh, kl, T, 0, nullptr};
+    v->nx = nx; v->ny = ny;
+    v->Yt = PlaneOp{yh, yl, plane_kg(T), (int)((d + 127) / 128), nullptr};
+    v->Xt = PlaneOp{xh, xl, plane_kg(T), (int)((d + 127) / 128), nullptr};
+    v->Xc = PlaneOp{kh, kl, plane_kg(d), (int)((T + 127) / 128), nullptr};
   }
   return off;
 }
@@ -522,15 +498,14 @@ size_t strp_workspace_bytes(const strp_module_desc* desc) {
   const size_t km = desc->k_max > 0 ? (size_t)desc->k_max : f;
   const size_t kp = (size_t)round_up((long long)km, 8);
   const long long T = desc->T;
-  const size_t ldp = (size_t)round_up(T, 8);
   auto al = [](size_t bytes) { return (bytes + 255) & ~size_t(255); };
   const size_t nmax = km > d ? km : d;
   const size_t invd_max = ((nmax + NB - 1) / NB) * NB * NB * 8;
   const size_t tilesT = (size_t)((T + 127) / 128);
   const size_t red = al((((f + 127) / 128) * tilesT + f + 4096) * 16);
-  // initialisation: weight planes, relu(Z0) as K8 planes, H partials
-  size_t init = 256 + 2 * (al(256) + 2 * al(f * d * 2)) + 2 * al(f * (size_t)T * 2) + red +
-                al(nt_partial_elems((int)d, (int)d, T, 1) * 4) + al(d * 8) + al(invd_max);
+  // initialisation: weight planes, relu(Z0) planes, H partials
+  size_t init = 256 + 2 * (al(256) + 2 * al(plane_elems(f, d) * 2)) + 2 * al(plane_elems(T, f) * 2) + red +
+                al(nt_partial_elems((int)d, (int)d, T, 1) * 4) + al(d * 8) + al(invd_max) + 2 * al(d * d * 8);
   // one iteration: everything every stage carves (stages reuse the arena, so this is an upper bound)
   size_t part = 0;
   auto upd = [&](size_t e) { if (e > part) part = e; };
@@ -538,11 +513,12 @@ size_t strp_workspace_bytes(const strp_module_desc* desc) {
   upd(nt_partial_elems((int)d, (int)km, T, 0));
   upd(nt_partial_elems((int)km, (int)d, T, 0));
   upd(nt_partial_elems((int)d, (int)d, (long long)kp, 1));
-  size_t step = 256 + al(4 * f * 8) + al(d * kp * 4) + al(km * d * 4) + 2 * (al(256) + 2 * al(d * kp * 2)) +
-                al(part * 4) + al(nmax * nmax * 8) + 2 * al(invd_max) + al(d * km * 8) * 2 + al(d * d * 8) +
-                3 * al(256) + 2 * al(km * d * 2) +
-                2 * al(kp * ldp * 2) /* ROW planes of kept rows */ + 2 * al(kp * (size_t)T * 2) /* K8 planes of kept rows */ +
-                2 * al(d * (size_t)T * 2) /* E */ + red;
+  size_t step = 256 + al(4 * f * 8) + al(d * kp * 4) + al(km * d * 4) +
+                (al(256) + 2 * al(plane_elems(d, km) * 2)) + 2 * (al(256) + 2 * al(plane_elems(km, d) * 2)) +
+                al(part * 4) + 3 * al(nmax * nmax * 8) + 2 * al(invd_max) + al(d * km * 8) * 4 + 2 * al(d * d * 8) +
+                2 * al(plane_elems(km, T) * 2) /* kept rows, token contraction */ +
+                2 * al(plane_elems(T, km) * 2) /* kept rows, channel contraction */ +
+                2 * al(plane_elems(T, d) * 2) /* E */ + red;
   return (init > step ? init : step) + (1 << 20);
 }
 
@@ -558,14 +534,8 @@ strp_status strp_gram(strp_ctx* ctx, const void* A, strp_dtype dt, int32_t C, in
   if (!ctx->ws) return fail(ctx, STRP_ENOMEM, "gram: no workspace set");
   Arena arena(ctx);
   PlaneOp op;
-  bool bf16 = false;
-  if (dt == STRP_BF16 && !idx) {  // a bf16 matrix is its own ROW plane: exact products on the bf16 cores
-    op = PlaneOp{(const unsigned short*)A, nullptr, (long long)ldA, C, nullptr};
-    bf16 = true;
-  } else {
-    STRP_TRY(make_row_planes(ctx, arena, A, dt, ldA, idx, s, T, 0, planes_for(dt, ctx->precision), &op));
-  }
-  return nt_product(ctx, arena, op, op, s, s, T, 1, bf16, G, ldG, nullptr, 0, diag, accumulate);
+  STRP_TRY(make_t_planes(ctx, arena, A, dt, ldA, idx, s, T, 0, planes_for(dt, ctx->precision), &op));
+  return nt_product(ctx, arena, op, op, s, s, T, 1, G, ldG, nullptr, 0, diag, accumulate);
 }
 
 strp_status strp_refit(strp_ctx* ctx, strp_side side, const float* Gram, int32_t ldg, double lambda, double* chol, int chol_valid,
@@ -591,19 +561,23 @@ strp_status strp_refit(strp_ctx* ctx, strp_side side, const float* Gram, int32_t
   memset(&ri, 0, sizeof(ri));
   ri.Gram = Gram; ri.ldg = ldg; ri.lam = lambda; ri.lam_dev = nullptr;
   if (chol) {
-    ri.Ld = chol;
+    ri.Linv = chol;
   } else {
-    STRP_TAKE(ctx, arena, Ld, double, (size_t)n * n);
-    ri.Ld = Ld;
+    STRP_TAKE(ctx, arena, Linv, double, (size_t)n * n);
+    ri.Linv = Linv;
   }
-  ri.Ld_ready = chol_valid ? 2 : 0;
+  ri.linv_ready = chol_valid ? 1 : 0;
+  if (!chol_valid) {
+    STRP_TAKE(ctx, arena, sys, double, (size_t)n * n);
+    ri.sys = sys;
+  }
   const int prec = ctx->precision;
   if (side == STRP_SIDE_FC2) {
-    STRP_TRY(make_row_planes(ctx, arena, Lhs, lhs_dtype, ld_lhs, nullptr, out, T, 0, planes_for(lhs_dtype, prec), &ri.Lhs));
-    STRP_TRY(make_row_planes(ctx, arena, Rhs, rhs_dtype, ld_rhs, idx, s, T, 0, planes_for(rhs_dtype, prec), &ri.Rhs));
+    STRP_TRY(make_t_planes(ctx, arena, Lhs, lhs_dtype, ld_lhs, nullptr, out, T, 0, planes_for(lhs_dtype, prec), &ri.Lhs));
+    STRP_TRY(make_t_planes(ctx, arena, Rhs, rhs_dtype, ld_rhs, idx, s, T, 0, planes_for(rhs_dtype, prec), &ri.Rhs));
   } else {
-    STRP_TRY(make_row_planes(ctx, arena, Lhs, lhs_dtype, ld_lhs, idx, s, T, 0, planes_for(lhs_dtype, prec), &ri.Lhs));
-    STRP_TRY(make_row_planes(ctx, arena, Rhs, rhs_dtype, ld_rhs, nullptr, in, T, 0, planes_for(rhs_dtype, prec), &ri.Rhs));
+    STRP_TRY(make_t_planes(ctx, arena, Lhs, lhs_dtype, ld_lhs, idx, s, T, 0, planes_for(lhs_dtype, prec), &ri.Lhs));
+    STRP_TRY(make_t_planes(ctx, arena, Rhs, rhs_dtype, ld_rhs, nullptr, in, T, 0, planes_for(rhs_dtype, prec), &ri.Rhs));
   }
   ri.m = m; ri.n = n; ri.T = T;
   double* sol = nullptr;
@@ -635,32 +609,31 @@ strp_status strp_module_init(strp_ctx* ctx, const strp_module_desc* desc, strp_m
   STRP_TRY(fill_zero(ctx, sc, SC_COUNT * sizeof(double)));
   STRP_TRY(launch_colnorm2(ctx, st->W2hat, desc->w_dtype, d, f, f, st->n2));
   // X planes (persistent)
-  STRP_TRY(split_rows(ctx, st->X, desc->x_dtype, desc->ldx, nullptr, d, T, 0, 0, (unsigned short*)cv.Xrow.hi, (unsigned short*)cv.Xrow.lo,
-                      cv.ldp, (unsigned short*)cv.Xk8.hi, (unsigned short*)cv.Xk8.lo));
+  STRP_TRY(split_act(ctx, st->X, desc->x_dtype, desc->ldx, nullptr, d, T, 0, 0, (unsigned short*)cv.Xt.hi, (unsigned short*)cv.Xt.lo,
+                     (unsigned short*)cv.Xc.hi, (unsigned short*)cv.Xc.lo));
   {
     Arena a2 = arena;
     PlaneOp W1p, W2p, A0k8;
     STRP_TRY(make_weight_planes(ctx, a2, st->W1hat, wkind, d, f, d, 0, npw, &W1p));
     STRP_TRY(make_weight_planes(ctx, a2, st->W2hat, wkind, f, d, f, 0, npw, &W2p));
-    const long long f8 = round_up(f, 8);
-    STRP_TAKE(ctx, a2, a0h, unsigned short, (size_t)f8 * T);
+    STRP_TAKE(ctx, a2, a0h, unsigned short, plane_elems(T, f));
     unsigned short* a0l = nullptr;
     if (npa == 2) {
-      STRP_TAKE(ctx, a2, a0l2, unsigned short, (size_t)f8 * T);
+      STRP_TAKE(ctx, a2, a0l2, unsigned short, plane_elems(T, f));
       a0l = a0l2;
     }
-    A0k8 = PlaneOp{a0h, a0l, T, 0, nullptr};
+    A0k8 = PlaneOp{a0h, a0l, plane_kg(f), (int)((T + 127) / 128), nullptr};
     {  // Z0 = W1hat X, Z = Z0, A = relu(Z0) (+ K8 planes of A), sum A^2
       GemmP p;
       memset(&p, 0, sizeof(p));
-      p.P = W1p; p.Q = cv.Xk8;
+      p.P = W1p; p.Q = cv.Xc;
       p.M = f; p.N = (int)T; p.K = d;
       p.epi = EPI_INITZ; p.Zs = st->Z; p.As = st->A; p.Z0s = st->Z0; p.lda = lda;
-      p.k8_hi = a0h; p.k8_lo = a0l; p.k8_ld = T;
-      gemm_plan_tiles(p, true, 1);
+      p.k8_hi = a0h; p.k8_lo = a0l; p.k8_kg = plane_kg(f);
+      gemm_plan_tiles(p, 1);
       STRP_TAKE(ctx, a2, red, double, 2 * (size_t)gemm_grid_blocks(p));
       p.red = red;
-      STRP_TRY(launch_gemm(ctx, p, true, false));
+      STRP_TRY(launch_gemm(ctx, p));
       STRP_TRY(launch_block_sum(ctx, red, gemm_grid_blocks(p), sc + SC_SUMA0, nullptr, 1.0, 1.0));
       hipLaunchKernelGGL(axpby_scalar_kernel, dim3(1), dim3(1), 0, ctx->stream, sc, (int)SC_LAM2, params->delta / (double)f, (int)SC_SUMA0, 0.0, -1);
     }
@@ -670,20 +643,20 @@ strp_status strp_module_init(strp_ctx* ctx, const strp_module_desc* desc, strp_m
       p.P = W2p; p.Q = A0k8;
       p.M = d; p.N = (int)T; p.K = f;
       p.epi = EPI_STORE; p.out = st->Y; p.ldo = lda;
-      gemm_plan_tiles(p, true, 1);
-      STRP_TRY(launch_gemm(ctx, p, true, false));
+      gemm_plan_tiles(p, 1);
+      STRP_TRY(launch_gemm(ctx, p));
     }
   }
-  STRP_TRY(split_rows(ctx, st->Y, STRP_F32, lda, nullptr, d, T, 0, 0, (unsigned short*)cv.Yrow.hi, (unsigned short*)cv.Yrow.lo, cv.ldp,
-                      nullptr, nullptr));
+  STRP_TRY(split_act(ctx, st->Y, STRP_F32, lda, nullptr, d, T, 0, 0, (unsigned short*)cv.Yt.hi, (unsigned short*)cv.Yt.lo, nullptr,
+                     nullptr));
   {  // H = X X^T (fp32 copy and fp64 system), lam1 = delta tr(H)/d, factor of H + lam1 I
     Arena a2 = arena;
     STRP_TAKE(ctx, a2, diag, double, (size_t)d);
-    STRP_TRY(nt_product(ctx, a2, cv.Xrow, cv.Xrow, d, d, T, 1, false, st->H, d, st->cholH, d, diag, 0));
+    STRP_TAKE(ctx, a2, Hd, double, (size_t)d * d);
+    STRP_TRY(nt_product(ctx, a2, cv.Xt, cv.Xt, d, d, T, 1, st->H, d, Hd, d, diag, 0));
     hipLaunchKernelGGL(vec_sum_kernel, dim3(1), dim3(256), 0, ctx->stream, diag, d, params->delta / (double)d, sc + SC_LAM1, sc + SC_TRH);
-    hipLaunchKernelGGL(add_diag_kernel, dim3(blocks_for(d)), dim3(256), 0, ctx->stream, st->cholH, (long long)d, d, 0.0, sc + SC_LAM1);
-    STRP_TAKE(ctx, a2, invd, double, (size_t)((d + NB - 1) / NB) * NB * NB);
-    STRP_TRY(chol_factor(ctx, st->cholH, d, d, invd, ctx->status_dev));
+    hipLaunchKernelGGL(add_diag_kernel, dim3(blocks_for(d)), dim3(256), 0, ctx->stream, Hd, (long long)d, d, 0.0, sc + SC_LAM1);
+    STRP_TRY(factor_and_invert(ctx, a2, Hd, d, st->cholH));
   }
   STRP_TRY(fill_zero(ctx, st->W1, sizeof(float) * (size_t)f * d));
   STRP_TRY(fill_zero(ctx, st->W2, sizeof(float) * (size_t)f * d));
@@ -737,13 +710,14 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     Arena a2 = arena;
     STRP_TAKE(ctx, a2, Gd, double, (size_t)s * s);
     PlaneOp Arow;
-    STRP_TRY(make_row_planes(ctx, a2, st->A, STRP_F32, lda, st->idx, s, T, 0, npa, &Arow));
-    STRP_TRY(nt_product(ctx, a2, Arow, Arow, s, s, T, 1, false, nullptr, 0, Gd, s, nullptr, 0));
+    STRP_TRY(make_t_planes(ctx, a2, st->A, STRP_F32, lda, st->idx, s, T, 0, npa, &Arow));
+    STRP_TRY(nt_product(ctx, a2, Arow, Arow, s, s, T, 1, nullptr, 0, Gd, s, nullptr, 0));
     hipLaunchKernelGGL(add_diag_kernel, dim3(blocks_for(s)), dim3(256), 0, ctx->stream, Gd, (long long)s, s, 0.0, sc + SC_LAM2);
     RefitIn ri;
     memset(&ri, 0, sizeof(ri));
-    ri.Ld = Gd; ri.Ld_ready = 1;
-    ri.Lhs = cv.Yrow; ri.Rhs = Arow; ri.m = d; ri.n = s; ri.T = T;
+    STRP_TAKE(ctx, a2, Ginv, double, (size_t)s * s);
+    ri.sys = Gd; ri.sys_ready = 1; ri.Linv = Ginv; ri.linv_ready = 0;
+    ri.Lhs = cv.Yt; ri.Rhs = Arow; ri.m = d; ri.n = s; ri.T = T;
     double* sol = nullptr;
     STRP_TRY(ridge_solve(ctx, a2, ri, &sol));
     STRP_TRY(scatter_weights(ctx, sol, s, STRP_SIDE_FC2, st->idx, s, st->W2, d, f));
@@ -752,11 +726,11 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   if (stages & STRP_STAGE_REFIT1) {
     Arena a2 = arena;
     PlaneOp Zrow;
-    STRP_TRY(make_row_planes(ctx, a2, st->Z, STRP_F32, lda, st->idx, s, T, 0, npa, &Zrow));
+    STRP_TRY(make_t_planes(ctx, a2, st->Z, STRP_F32, lda, st->idx, s, T, 0, npa, &Zrow));
     RefitIn ri;
     memset(&ri, 0, sizeof(ri));
-    ri.Ld = st->cholH; ri.Ld_ready = 2;
-    ri.Lhs = Zrow; ri.Rhs = cv.Xrow; ri.m = s; ri.n = d; ri.T = T;
+    ri.Linv = st->cholH; ri.linv_ready = 1;
+    ri.Lhs = Zrow; ri.Rhs = cv.Xt; ri.m = s; ri.n = d; ri.T = T;
     double* sol = nullptr;
     STRP_TRY(ridge_solve(ctx, a2, ri, &sol));
     STRP_TRY(scatter_weights(ctx, sol, d, STRP_SIDE_FC1, st->idx, s, st->W1, f, d));
@@ -785,20 +759,21 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   if (stages & STRP_STAGE_AUPD) {
     Arena a2 = arena;
     STRP_TAKE(ctx, a2, Md, double, (size_t)d * d);
-    STRP_TAKE(ctx, a2, invd, double, (size_t)((d + NB - 1) / NB) * NB * NB);
+    STRP_TAKE(ctx, a2, Minv, double, (size_t)d * d);
     STRP_TAKE(ctx, a2, Bd, double, (size_t)s * d);
-    STRP_TRY(nt_product(ctx, a2, W2Sp, W2Sp, d, d, sp, 1, false, nullptr, 0, Md, d, nullptr, 0));
+    STRP_TAKE(ctx, a2, Btmp, double, (size_t)s * d);
+    STRP_TRY(nt_product(ctx, a2, W2Sp, W2Sp, d, d, sp, 1, nullptr, 0, Md, d, nullptr, 0));
     hipLaunchKernelGGL(add_diag_kernel, dim3(blocks_for(d)), dim3(256), 0, ctx->stream, Md, (long long)d, d, params->beta / params->alpha, (const double*)nullptr);
-    STRP_TRY(chol_factor(ctx, Md, d, d, invd, ctx->status_dev));
+    STRP_TRY(factor_and_invert(ctx, a2, Md, d, Minv));
     hipLaunchKernelGGL(transpose_f32_f64_kernel, dim3(blocks_for((long long)d * s)), dim3(256), 0, ctx->stream, W2S, sp, d, s, Bd, (long long)d);
-    STRP_TRY(chol_solve_right(ctx, Md, d, d, invd, Bd, s, d));
+    STRP_TRY(apply_inverse_right(ctx, Minv, d, Bd, s, Btmp));
     PlaneOp Bp, Zk8;
     STRP_TRY(make_weight_planes(ctx, a2, Bd, SRC_F64, d, s, d, 0, npa, &Bp));
-    STRP_TRY(make_k8_planes(ctx, a2, st->Z, STRP_F32, lda, st->idx, s, T, 1, npa, &Zk8));
-    STRP_TAKE(ctx, a2, ekh, unsigned short, (size_t)d * T);
+    STRP_TRY(make_c_planes(ctx, a2, st->Z, STRP_F32, lda, st->idx, s, T, 1, npa, &Zk8));
+    STRP_TAKE(ctx, a2, ekh, unsigned short, plane_elems(T, d));
     unsigned short* ekl = nullptr;
     if (npa == 2) {
-      STRP_TAKE(ctx, a2, ekl2, unsigned short, (size_t)d * T);
+      STRP_TAKE(ctx, a2, ekl2, unsigned short, plane_elems(T, d));
       ekl = ekl2;
     }
     {  // E = Y - W relu(Z_S), kept only as K8 planes
@@ -807,18 +782,18 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
       p.P = W2Sp; p.Q = Zk8;
       p.M = d; p.N = (int)T; p.K = s;
       p.epi = EPI_RESID; p.Yin = st->Y; p.ldy = lda;
-      p.k8_hi = ekh; p.k8_lo = ekl; p.k8_ld = T;
-      gemm_plan_tiles(p, true, 1);
-      STRP_TRY(launch_gemm(ctx, p, true, false));
+      p.k8_hi = ekh; p.k8_lo = ekl; p.k8_kg = plane_kg(d);
+      gemm_plan_tiles(p, 1);
+      STRP_TRY(launch_gemm(ctx, p));
     }
     {  // A_S = relu(Z_S) + B E
       GemmP p;
       memset(&p, 0, sizeof(p));
-      p.P = Bp; p.Q = PlaneOp{ekh, ekl, T, 0, nullptr};
+      p.P = Bp; p.Q = PlaneOp{ekh, ekl, plane_kg(d), (int)((T + 127) / 128), nullptr};
       p.M = s; p.N = (int)T; p.K = d;
       p.epi = EPI_AUPD; p.Zs = st->Z; p.As = st->A; p.lda = lda; p.oidx = st->idx;
-      gemm_plan_tiles(p, true, 1);
-      STRP_TRY(launch_gemm(ctx, p, true, false));
+      gemm_plan_tiles(p, 1);
+      STRP_TRY(launch_gemm(ctx, p));
     }
     {
       ProfScope ps(ctx, "pruned_rows_a", 0.0, 8.0 * (double)(f - s) * (double)T);
@@ -831,15 +806,15 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     Arena a2 = arena;
     GemmP p;
     memset(&p, 0, sizeof(p));
-    p.P = W1Sp; p.Q = cv.Xk8;
+    p.P = W1Sp; p.Q = cv.Xc;
     p.M = s; p.N = (int)T; p.K = d;
     p.epi = EPI_ZUPD; p.Zs = st->Z; p.As = st->A; p.lda = lda; p.oidx = st->idx; p.alpha = alpha; p.beta = beta;
     p.write_out = zupd ? 1 : 0;
-    gemm_plan_tiles(p, true, 1);
+    gemm_plan_tiles(p, 1);
     const int nb = gemm_grid_blocks(p);
     STRP_TAKE(ctx, a2, red, double, 2 * (size_t)(nb > f ? nb : f));
     p.red = red;
-    STRP_TRY(launch_gemm(ctx, p, true, false));
+    STRP_TRY(launch_gemm(ctx, p));
     STRP_TRY(launch_block_sum(ctx, red, nb, sc + SC_TMP0, sc + SC_TMP1, 1.0, 1.0));
     {
       ProfScope ps(ctx, "pruned_rows_z", 0.0, 8.0 * (double)(f - s) * (double)T);
@@ -853,17 +828,17 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   if (stages & STRP_STAGE_OBJ) {
     Arena a2 = arena;
     PlaneOp Ak8;
-    STRP_TRY(make_k8_planes(ctx, a2, st->A, STRP_F32, lda, st->idx, s, T, 0, 1, &Ak8));
+    STRP_TRY(make_c_planes(ctx, a2, st->A, STRP_F32, lda, st->idx, s, T, 0, 1, &Ak8));
     GemmP p;
     memset(&p, 0, sizeof(p));
     p.P = W2Sp; p.P.lo = nullptr; p.Q = Ak8;
     p.M = d; p.N = (int)T; p.K = s;
     p.epi = EPI_RESID; p.Yin = st->Y; p.ldy = lda;
-    gemm_plan_tiles(p, true, 1);
+    gemm_plan_tiles(p, 1);
     const int nb = gemm_grid_blocks(p);
     STRP_TAKE(ctx, a2, red, double, 2 * (size_t)(nb > 1024 ? nb : 1024));
     p.red = red;
-    STRP_TRY(launch_gemm(ctx, p, true, false));
+    STRP_TRY(launch_gemm(ctx, p));
     STRP_TRY(launch_block_sum(ctx, red, nb, sc + SC_T1, nullptr, params->alpha / (double)T, 1.0));
     hipLaunchKernelGGL(sumsq_kernel, dim3(1024), dim3(256), 0, ctx->stream, W2S, (long long)d * sp, red);
     STRP_TRY(launch_block_sum(ctx, red, 1024, sc + SC_W2SQ, nullptr, 1.0, 1.0));

@@ -68,27 +68,34 @@ struct Arena {
   if (!var) return strp::fail((ctx), STRP_ENOMEM, "workspace too small for %s (%zu bytes more)",    \
                               #var, sizeof(type) * (size_t)(count))
 
-// ---- MFMA GEMM family on 16-bit operand planes (gemm_mfma.hip) -------------------------------
-// An operand as the matrix cores see it: one (hi) or two (hi, lo) planes of 16-bit elements.
-//   ROW layout: element (row, k) at row * ld + k                     (k contiguous; ld % 8 == 0)
-//   K8  layout: element (k, n)   at ((k / 8) * ld + n) * 8 + k % 8   (ld = number of columns)
+// ---- MFMA GEMM family on 16-bit operand planes (gemm_mfma.hip, split_planes.hip) -----------------
+// An operand as the matrix cores see it: one (hi) or two (hi, lo) fp16 planes in the panel-major chunk layout
+//   offset(k, r) = (((r / 128) * kg + k / 8) * 128 + r % 128) * 8 + k % 8
+// k = contraction index, r = output row (P) or output column (Q); npan panels of 128 rows, kg k-groups of 8
+// (kg = plane_kg(K): even, padding zero).
 // scale (device, optional): the planes hold x * scale; the GEMM epilogue divides it out.
 struct PlaneOp {
   const unsigned short* hi;
   const unsigned short* lo;
-  long long ld;
-  int rows;            // ROW: rows available (row index is clamped to rows - 1); K8: unused
+  long long kg;
+  int npan;
   const float* scale;
 };
+// k-groups allocated for a contraction of length K: an even number, the pad group zero-filled
+// (the pipelined kernel moves two k-groups per stage without tail logic)
+static inline long long plane_kg(long long K) { return (((K + 7) / 8) + 1) & ~1LL; }
+static inline size_t plane_elems(long long rows, long long K) {
+  return (size_t)((rows + 127) / 128) * (size_t)plane_kg(K) * 1024;
+}
 
 enum { EPI_PARTIAL = 0, EPI_STORE = 1, EPI_INITZ = 2, EPI_RESID = 3, EPI_AUPD = 4, EPI_ZUPD = 5 };
 enum { SRC_F64 = 0, SRC_F32 = 1, SRC_BF16 = 2 };
 
 struct GemmP {
-  PlaneOp P, Q;
+  PlaneOp P, Q;        // C[m, n] = sum_k P(k, m) Q(k, n)
   int M, N;
   long long K;
-  int force_wt;        // 4 requests the 256x256 tile (measured slower with one-deep prefetch; off by default)
+  int force_wt;        // 4 requests the 256x256 tile (off by default)
   int wt;              // 32x32 MFMA tiles per wavefront per dimension: 2 (128x128 blocks) or 4 (256x256), set by gemm_plan_tiles
   int tilesM, tilesN, ntiles;
   int triangle;        // P == Q, only tiles with tn <= tm are computed
@@ -107,16 +114,14 @@ struct GemmP {
   float alpha, beta;
   double* red;         // per-block partial sums [gridDim.x][2] (INITZ, RESID, ZUPD)
   int write_out;       // ZUPD: 1 = update Z, 0 = only accumulate the objective sums
-  unsigned short* k8_hi;  // optional K8 planes of the produced values (STORE: C, INITZ: relu(C), RESID: Y - C)
-  unsigned short* k8_lo;
-  long long k8_ld;
+  unsigned short* k8_hi;  // optional operand planes of the produced values with k = output row, r = output column
+  unsigned short* k8_lo;  //   (STORE: C, INITZ: relu(C), RESID: Y - C); k8_kg = M / 8 groups, ceil(N/128) panels
+  long long k8_kg;
 };
 
-// Token-contraction form ("NT"): C[M x N] = sum_k P[m,k] Q[n,k]; writes split-K partials.
-// Token-parallel form ("NN"): C[M x N] = sum_k P[m,k] Q[k,n] with fused epilogue (Q in K8 layout).
-strp_status launch_gemm(strp_ctx* ctx, GemmP& p, bool nn, bool bf16);
+strp_status launch_gemm(strp_ctx* ctx, GemmP& p);
 int gemm_grid_blocks(const GemmP& p);
-void gemm_plan_tiles(GemmP& p, bool nn, int want_splits);
+void gemm_plan_tiles(GemmP& p, int want_splits);
 
 // Sum split-K partials in fp64; optional symmetric completion from the computed lower half.
 // outf / outd (either may be null): [M x ldo]; accumulate adds to outf's previous content.
@@ -127,14 +132,15 @@ strp_status launch_splitk_reduce(strp_ctx* ctx, const float* part, int splits, i
 strp_status launch_block_sum(strp_ctx* ctx, const double* red, int nblocks, double* dst0, double* dst1,
                              double scale0, double scale1);
 
-// fp32 / bf16 activation rows (optionally gathered by idx) -> fp16 planes; any output may be null.
-//   ROW planes [round_up(rows,8)][ld_row], K8 planes [round_up(rows,8)/8][T][8]; padding is zero.
-strp_status split_rows(strp_ctx* ctx, const void* src, int src_dtype, long long lds, const int* idx, int rows, long long T,
-                       int relu_row, int relu_k8, unsigned short* row_hi, unsigned short* row_lo, long long ld_row,
-                       unsigned short* k8_hi, unsigned short* k8_lo);
-// Small matrix (weights) -> ROW planes [rows][ldp] of src * (*scale_dev), zero padded; src_kind = SRC_*.
+// fp32 / bf16 activation rows (optionally gathered by idx) -> fp16 planes; any output pair may be null.
+//   t_* : contraction over tokens   (k = token,   r = row):   plane_elems(rows, T)
+//   c_* : contraction over channels (k = row,     r = token): plane_elems(T, rows)
+strp_status split_act(strp_ctx* ctx, const void* src, int src_dtype, long long lds, const int* idx, int rows, long long T,
+                      int relu_t, int relu_c, unsigned short* t_hi, unsigned short* t_lo, unsigned short* c_hi,
+                      unsigned short* c_lo);
+// Small matrix (weights) -> planes with k = column, r = row: plane_elems(rows, cols); src_kind = SRC_*.
 strp_status split_small(strp_ctx* ctx, const void* src, int src_kind, long long lds, int rows, int cols, int transpose,
-                        const float* scale_dev, unsigned short* hi, unsigned short* lo, long long ldp);
+                        const float* scale_dev, unsigned short* hi, unsigned short* lo);
 // *scale_out = power of two that brings max|src| into [2^11, 2^12).
 strp_status weight_scale(strp_ctx* ctx, const void* src, int src_kind, long long lds, int rows, int cols, float* scale_out);
 
@@ -143,9 +149,10 @@ constexpr int NB = 64;  // block order of the factorisation
 // In-place lower Cholesky of the n x n fp64 matrix A (ld), A += 0 (caller adds the ridge).
 // invd: [ceil(n/NB)][NB*NB] inverses of the diagonal blocks of L.  status: device word.
 strp_status chol_factor(strp_ctx* ctx, double* A, int n, long long ld, double* invd, int32_t* status);
-// In place X <- X (L L^T)^-1 for X [m x n] (ldx), L lower factor with block inverses invd.
-strp_status chol_solve_right(strp_ctx* ctx, const double* L, int n, long long ldl, const double* invd,
-                             double* X, int m, long long ldx);
+// Linv [n x n, ld n] = L^-1 from the factor and its inverted diagonal blocks; tmp: n x n scratch.
+strp_status tri_inverse(strp_ctx* ctx, const double* L, int n, long long ldl, const double* invd, double* Linv, double* tmp);
+// In place X <- X (L L^T)^-1 = (X Linv^T) Linv for X [m x n] (ld n); tmp: m x n scratch.
+strp_status apply_inverse_right(strp_ctx* ctx, const double* Linv, int n, double* X, int m, double* tmp);
 // C[M x N] = alpha * A * B + beta * C with arbitrary element strides; lower != 0 skips tiles above
 // the diagonal.
 strp_status dgemm(strp_ctx* ctx, int M, int N, int K, double alpha, const double* A, long long rsa,

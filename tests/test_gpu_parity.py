@@ -197,7 +197,7 @@ def test_refit_parity_both_sides(ctx):
     ref1 = orc.refit_fc1(Z32, st.X, idx, st.H, st.lam1, cfg.d, cfg.f)
     assert rel_fro(W1.cpu().numpy(), ref1) < 1e-4
     Lref = np.linalg.cholesky(st.H + st.lam1 * np.eye(cfg.d))
-    assert rel_fro(np.tril(chol.cpu().numpy()), Lref) < 1e-5
+    assert rel_fro(np.tril(chol.cpu().numpy()), np.linalg.inv(Lref)) < 1e-5     # the cache is the inverse factor
     W1b = torch.empty_like(W1)
     ctx.strp_refit(strp.SIDE_FC1, None, st.lam1, Zd, Xd, T, idx_d, W1b, chol=chol, chol_valid=True)
     assert rel_fro(W1b.cpu().numpy(), ref1) < 1e-4
@@ -253,7 +253,7 @@ def test_module_init_parity(ctx, name, d, f, T):
     assert np.isclose(sc[0], st.lam1, rtol=1e-5) and np.isclose(sc[1], st.lam2, rtol=1e-5)
     assert np.allclose(mod.n2.cpu().numpy(), np.sum(st.W2hat ** 2, axis=0), rtol=1e-12)
     Lref = np.linalg.cholesky(st.H + st.lam1 * np.eye(d))
-    assert rel_fro(np.tril(mod.cholH.cpu().numpy()), Lref) < 1e-5
+    assert rel_fro(np.tril(mod.cholH.cpu().numpy()), np.linalg.inv(Lref)) < 1e-5
 
 
 def test_free_running_config1(ctx):
