@@ -18,12 +18,9 @@
 // right-hand sides) use split-K partials, token-parallel products use the fused epilogues.
 #include <stdlib.h>
 
-#include "strp_internal.h"
+#include "gemm_epilogue.h"
 
 namespace strp {
-
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 // Tile shapes (WT = 32x32 MFMA tiles per wavefront per dimension):
 //   WT = 2: 128x128 block (one panel per operand), K tile 64, two blocks per CU
@@ -37,23 +34,6 @@ struct Tile {
   static constexpr int NCH = ROWS * G / 256;       // 16-byte chunks per thread per plane per K tile (= 4)
   static constexpr int GSTEP = 256 / ROWS;         // k-groups covered by one pass of the block's threads (2 or 1)
 };
-
-__device__ __forceinline__ unsigned short half_bits(float x) {
-  _Float16 h = (_Float16)x;
-  return __builtin_bit_cast(unsigned short, h);
-}
-__device__ __forceinline__ float clamp_half_range(float x) {
-  return __builtin_fminf(__builtin_fmaxf(x, -65504.0f), 65504.0f);
-}
-__device__ __forceinline__ void split_half(float x, unsigned short& hi, unsigned short& lo) {
-  x = clamp_half_range(x);
-  _Float16 h = (_Float16)x;
-  hi = __builtin_bit_cast(unsigned short, h);
-  lo = half_bits(x - (float)h);
-}
-__device__ __forceinline__ unsigned int pack2(unsigned short a, unsigned short b) {
-  return (unsigned int)a | ((unsigned int)b << 16);
-}
 
 // Operand tile loader: thread t owns row t % 128 of panel (t / 128) % PANS and k-groups g0 + GSTEP * i.
 // Loads are unconditional (panel clamped to the last one, k-groups past the end read group 0 and are zeroed
@@ -108,102 +88,6 @@ struct PlaneLoader {
 
 __device__ __forceinline__ floatx16 mma(uint4 a, uint4 b, floatx16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
-}
-
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
-  return v;
-}
-
-// Epilogue of one 32x32 accumulator tile (passed by value so the accumulators never need an address).
-// Register e of lane l is output row m_tile + 8 (e / 4) + (e % 4), column n  (m_tile, n include the lane's share).
-template <int EPI>
-__device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16, float unscale, int m_tile, int n, int split,
-                                              double& red0, double& red1) {
-  const float ab = p.alpha + p.beta;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int mq = m_tile + 8 * q;  // rows mq .. mq+3
-    float outv[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int m = mq + r;
-      const float v = a16[4 * q + r] * unscale;
-      outv[r] = 0.0f;
-      if (m >= p.M || n >= p.N) continue;
-      if (EPI == EPI_PARTIAL) {
-        p.out[((long long)split * p.M + m) * p.N + n] = v;
-      } else if (EPI == EPI_STORE) {
-        p.out[(long long)m * p.ldo + n] = v;
-        outv[r] = v;
-      } else if (EPI == EPI_INITZ) {
-        const long long o = (long long)m * p.lda + n;
-        const float a = __builtin_fmaxf(v, 0.0f);
-        p.Z0s[o] = v;
-        p.Zs[o] = v;
-        p.As[o] = a;
-        outv[r] = a;
-        red0 += (double)a * (double)a;
-      } else if (EPI == EPI_RESID) {
-        const float rr = p.Yin[(long long)m * p.ldy + n] - v;
-        outv[r] = rr;
-        red0 += (double)rr * (double)rr;
-      } else if (EPI == EPI_AUPD) {
-        const long long o = (long long)p.oidx[m] * p.lda + n;
-        p.As[o] = __builtin_fmaxf(p.Zs[o], 0.0f) + v;
-      } else {  // EPI_ZUPD
-        const long long o = (long long)p.oidx[m] * p.lda + n;
-        const float a = p.As[o];
-        const float z1 = v;
-        float z;
-        if (p.write_out) {
-          const float z2 = (p.beta * a + p.alpha * z1) / ab;
-          const float cm = __builtin_fminf(z1, 0.0f);
-          const float costm = p.beta * a * a + p.alpha * (cm - z1) * (cm - z1);
-          const float cp = __builtin_fmaxf(z2, 0.0f);
-          const float costp = p.beta * (a - cp) * (a - cp) + p.alpha * (cp - z1) * (cp - z1);
-          z = costm < costp ? cm : cp;
-          p.Zs[o] = z;
-        } else {
-          z = p.Zs[o];
-        }
-        const float ra = a - __builtin_fmaxf(z, 0.0f);
-        const float rz = z - z1;
-        red0 += (double)ra * (double)ra;
-        red1 += (double)rz * (double)rz;
-      }
-    }
-    // optional operand-plane copy of the produced tile (its rows are the contraction axis of the consumer):
-    // this lane's four rows are half of one 16-byte chunk
-    if ((EPI == EPI_STORE || EPI == EPI_INITZ || EPI == EPI_RESID) && p.k8_hi && n < p.N && mq < p.M) {
-      unsigned short h[4], l[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) split_half(outv[r], h[r], l[r]);
-      const long long o = ((((long long)(n >> 7) * p.k8_kg + (mq >> 3)) << 7) + (n & 127)) * 8 + (mq & 7);
-      *(uint2*)(p.k8_hi + o) = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
-      if (p.k8_lo) *(uint2*)(p.k8_lo + o) = make_uint2(pack2(l[0], l[1]), pack2(l[2], l[3]));
-    }
-  }
-}
-
-// Compile-time walk over the WT x WT tiles of a wavefront (constant indices keep the accumulators in registers).
-template <int EPI, int WT, int IJ>
-struct EpilogueWalk {
-  static __device__ __forceinline__ void run(const GemmP& p, floatx16 (&acc)[WT][WT], float unscale, int mbase, int nbase, int split,
-                                             double& red0, double& red1) {
-    epilogue_tile<EPI>(p, acc[IJ / WT][IJ % WT], unscale, mbase + (IJ / WT) * 32, nbase + (IJ % WT) * 32, split, red0, red1);
-    EpilogueWalk<EPI, WT, IJ + 1>::run(p, acc, unscale, mbase, nbase, split, red0, red1);
-  }
-};
-template <int EPI, int WT>
-struct EpilogueWalk<EPI, WT, WT * WT> {
-  static __device__ __forceinline__ void run(const GemmP&, floatx16 (&)[WT][WT], float, int, int, int, double&, double&) {}
-};
-template <int EPI, int WT>
-__device__ __forceinline__ void epilogue(const GemmP& p, floatx16 (&acc)[WT][WT], float unscale, int mbase, int nbase, int split,
-                                         double& red0, double& red1) {
-  EpilogueWalk<EPI, WT, 0>::run(p, acc, unscale, mbase, nbase, split, red0, red1);
 }
 
 template <int NPP, int NPQ, int WT>
@@ -326,12 +210,12 @@ __global__ __launch_bounds__(256, WT == 4 ? 1 : 2) void gemm_kernel(const GemmP 
   double red0 = 0.0, red1 = 0.0;
   const int mbase = m0 + wm * WROWS + 4 * (lane >> 5), nbase = n0 + wn * WROWS + (lane & 31);
   switch (p.epi) {
-    case EPI_PARTIAL: epilogue<EPI_PARTIAL, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
-    case EPI_STORE: epilogue<EPI_STORE, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
-    case EPI_INITZ: epilogue<EPI_INITZ, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
-    case EPI_RESID: epilogue<EPI_RESID, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
-    case EPI_AUPD: epilogue<EPI_AUPD, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
-    default: epilogue<EPI_ZUPD, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
+    case EPI_PARTIAL: epilogue<EPI_PARTIAL, WT, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
+    case EPI_STORE: epilogue<EPI_STORE, WT, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
+    case EPI_INITZ: epilogue<EPI_INITZ, WT, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
+    case EPI_RESID: epilogue<EPI_RESID, WT, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
+    case EPI_AUPD: epilogue<EPI_AUPD, WT, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
+    default: epilogue<EPI_ZUPD, WT, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
   }
   if (p.red) {
     red0 = wave_sum(red0);
@@ -353,11 +237,12 @@ __global__ __launch_bounds__(256, WT == 4 ? 1 : 2) void gemm_kernel(const GemmP 
 // ---------------------------------------------------------------------------------------------
 void gemm_plan_tiles(GemmP& p, int want_splits) {
   {
-    static const int env_wt = getenv("STRP_TILE") ? atoi(getenv("STRP_TILE")) : 0;  // tuning knob: 256 selects the large tile
-    if (env_wt == 256) p.force_wt = 4;
+    // 256x256 tiles with the LDS-DMA pipeline when they still give most CUs a block; STRP_TILE=128 forces the small tile
+    static const int env_wt = getenv("STRP_TILE") ? atoi(getenv("STRP_TILE")) : 0;
     const long long t4m = (p.M + 255) / 256, t4n = (p.N + 255) / 256;
     const long long n4 = p.triangle ? t4m * (t4m + 1) / 2 : t4m * t4n;
-    p.wt = (p.force_wt == 4 && p.M >= 256 && p.N >= 256 && n4 * (want_splits > 1 ? want_splits : 1) >= 256) ? 4 : 2;
+    const bool big = p.M >= 256 && p.N >= 256 && n4 * (want_splits > 1 ? want_splits : 1) >= 192 && p.K >= 256;
+    p.wt = (big && env_wt != 128 && p.force_wt != 2) ? 4 : 2;
   }
   const int ROWS = 64 * p.wt, BK = p.wt == 2 ? 64 : 32;
   p.tilesM = (p.M + ROWS - 1) / ROWS;
@@ -385,10 +270,12 @@ __global__ __launch_bounds__(256) void zero_pad_group_kernel(unsigned short* hi,
   if (lo) *(uint4*)(lo + o) = make_uint4(0, 0, 0, 0);
 }
 
+void launch_gemm_dma(strp_ctx* ctx, const GemmP& p, int npp, int npq);   // gemm_dma.hip
+
 template <int NPP, int NPQ>
 static void launch_one(strp_ctx* ctx, const GemmP& p) {
   if (p.wt == 4)
-    hipLaunchKernelGGL((gemm_kernel<NPP, NPQ, 4>), dim3(gemm_grid_blocks(p)), dim3(256), 0, ctx->stream, p);
+    launch_gemm_dma(ctx, p, NPP, NPQ);
   else
     hipLaunchKernelGGL((gemm_kernel<NPP, NPQ, 2>), dim3(gemm_grid_blocks(p)), dim3(256), 0, ctx->stream, p);
 }
@@ -397,7 +284,7 @@ strp_status launch_gemm(strp_ctx* ctx, GemmP& p) {
   if (p.M <= 0 || p.N <= 0 || p.K <= 0) return fail(ctx, STRP_EINVAL, "gemm: empty shape");
   if (p.ntiles <= 0 || p.splits <= 0 || (p.wt != 2 && p.wt != 4)) return fail(ctx, STRP_EINVAL, "gemm: tiles not planned");
   if (!p.P.hi || !p.Q.hi) return fail(ctx, STRP_EINVAL, "gemm: null operand plane");
-  if (p.P.kg * 8 < p.K || p.Q.kg * 8 < p.K) return fail(ctx, STRP_EINVAL, "gemm: operand planes shorter than K");
+  if (p.P.kg * 8 < p.K || p.Q.kg * 8 < p.K || (p.P.kg & 1) || (p.Q.kg & 1)) return fail(ctx, STRP_EINVAL, "gemm: operand planes shorter than K or odd group count");
   if ((long long)p.P.npan * 128 < p.M || (long long)p.Q.npan * 128 < p.N) return fail(ctx, STRP_EINVAL, "gemm: operand planes narrower than the output");
   if ((p.M % 8) && p.k8_hi) return fail(ctx, STRP_EINVAL, "gemm: plane output needs M %% 8 == 0");
   if (p.epi != EPI_PARTIAL && p.splits != 1) return fail(ctx, STRP_EINVAL, "gemm: fused epilogues do not split K");

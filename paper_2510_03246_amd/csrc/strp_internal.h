@@ -95,7 +95,7 @@ struct GemmP {
   PlaneOp P, Q;        // C[m, n] = sum_k P(k, m) Q(k, n)
   int M, N;
   long long K;
-  int force_wt;        // 4 requests the 256x256 tile (off by default)
+  int force_wt;        // 2 forces the 128x128 register-staged kernel
   int wt;              // 32x32 MFMA tiles per wavefront per dimension: 2 (128x128 blocks) or 4 (256x256), set by gemm_plan_tiles
   int tilesM, tilesN, ntiles;
   int triangle;        // P == Q, only tiles with tn <= tm are computed

@@ -50,7 +50,7 @@ def mask_mismatch_outside_ties(score64, mask_gpu, k, rel=1e-6):
 # strp_gram
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype,C,T,s", [("f32", 300, 1003, 170), ("bf16", 260, 2050, 260), ("f32", 64, 96, 1),
-                                         ("f32", 140, 8200, 129)])
+                                         ("f32", 140, 8200, 129), ("f32", 1100, 16392, 1000), ("bf16", 1024, 12296, 1024)])
 def test_gram_parity(ctx, dtype, C, T, s):
     g = torch.Generator(device="cuda").manual_seed(C * 7 + T)
     A = torch.randn((C, T), generator=g, device="cuda") * (1 + torch.arange(C, device="cuda")[:, None] % 5)
@@ -355,6 +355,29 @@ def test_free_running_reselect_medium(ctx):
         bad = mask_mismatch_outside_ties(st.score, mod.mask.cpu().numpy(), k, rel=1e-5)
         assert not bad, (it, bad)
         assert abs(rep.J_ridge - float(np.sum(terms))) <= TOL_J * float(np.sum(terms))
+    err = _compare_state(mod, st, T)
+    assert max(err.values()) < TOL_F, err
+
+
+def test_large_tile_pipeline_path(ctx):
+    """Sizes at which the 256x256 LDS-DMA pipelined kernel is selected (ragged in every dimension)."""
+    base = inputs.CONFIGS["opt125m"]
+    d, f, T = 520, 2056, 8200
+    cfg = type(base)(**{**base.__dict__, "d": d, "f": f, "T": T, "n_outlier": 5})
+    m = inputs.make_ffn_module(cfg, 0, 4, "cuda")
+    mod = strp.FFNModule(ctx, m["W1hat"], m["W2hat"], m["X"], T)
+    k = 777
+    p = _params(k, strp.WANDA, reselect=0)
+    mod.init(p)
+    st = _oracle_state(m)
+    err = _compare_state(mod, st, T, ("Z", "A", "Y"))
+    assert max(err.values()) < 1e-5, err
+    for it in range(2):
+        rep = mod.step(p)
+        terms = orc.admm_step(st, k, 1.0, 1.0, orc.WANDA, select=(it == 0))
+        assert rep.status == strp.OK
+        assert abs(rep.J_ridge - float(np.sum(terms))) <= TOL_J * float(np.sum(terms))
+    assert not mask_mismatch_outside_ties(st.score, mod.mask.cpu().numpy(), k)
     err = _compare_state(mod, st, T)
     assert max(err.values()) < TOL_F, err
 
