@@ -140,11 +140,11 @@ static strp_status dgemm_launch(strp_ctx* ctx, const DgemmP& p, int batch) {
 }
 
 strp_status dgemm(strp_ctx* ctx, int M, int N, int K, double alpha, const double* A, long long rsa, long long csa,
-                  const double* B, long long rsb, long long csb, double beta, double* C, long long ldc, int lower) {
+                  const double* B, long long rsb, long long csb, double beta, double* C, long long ldc, int lower, int tri) {
   DgemmP p;
   memset(&p, 0, sizeof(p));
   p.M = M; p.N = N; p.K = K; p.alpha = alpha; p.beta = beta;
-  p.A = A; p.rsa = rsa; p.csa = csa; p.B = B; p.rsb = rsb; p.csb = csb; p.C = C; p.ldc = ldc; p.lower = lower;
+  p.A = A; p.rsa = rsa; p.csa = csa; p.B = B; p.rsb = rsb; p.csb = csb; p.C = C; p.ldc = ldc; p.lower = lower; p.tri = tri;
   return dgemm_launch(ctx, p, 1);
 }
 
@@ -152,47 +152,51 @@ strp_status dgemm(strp_ctx* ctx, int M, int N, int K, double alpha, const double
 // Diagonal block: Cholesky of a jb x jb block (jb <= 64) in LDS and the inverse of its factor
 // (inverse by recursive doubling: V21 = -V22 (L21 V11) for blocks of 1, 2, 4, ... 32)
 // ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ double rsqrt_f64(double d) {
+  double y = __builtin_amdgcn_rsq(d);
+  y = y * (1.5 - 0.5 * d * y * y);
+  y = y * (1.5 - 0.5 * d * y * y);
+  return y;
+}
+
+// One barrier per column: the working block S keeps UNSCALED columns (the trailing update only needs
+// S[i][j] S[k][j] / d_j), the scaled factor goes to Lm; every thread derives 1/sqrt(d_j) itself.
 __global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld, int jb, double* invd, int32_t* status) {
-  __shared__ double S[NB][NB + 1];
-  __shared__ double V[NB][NB + 1];
-  __shared__ double Tm[NB][NB + 1];
+  __shared__ double S[NB][NB + 1];    // working block, later the temporary of the inversion
+  __shared__ double Lm[NB][NB + 1];   // factor (identity beyond jb)
+  __shared__ double V[NB][NB + 1];    // inverse of the factor
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   for (int e = tid; e < NB * NB; e += 256) {
     const int i = e >> 6, j = e & 63;
     S[i][j] = (i < jb && j <= i) ? A[(long long)i * ld + j] : ((i == j) ? 1.0 : 0.0);
+    Lm[i][j] = 0.0;
     V[i][j] = 0.0;
   }
   __syncthreads();
-  for (int j = 0; j < jb; ++j) {
+  for (int j = 0; j < NB; ++j) {
     const double dj = S[j][j];
     const bool ok = dj > 0.0;
-    const double piv = ok ? sqrt(dj) : 1.0;
-    __syncthreads();                      // everyone has read the pivot before it is overwritten
-    if (tid == 0) {
-      S[j][j] = piv;
-      if (!ok) atomicCAS(status, 0, (int)STRP_ENOTPD);
-    }
-    if (tid > j && tid < jb) S[tid][j] /= piv;
-    __syncthreads();
-    // trailing update of the lower triangle: S[i][k] -= S[i][j] * S[k][j], j < k <= i
-    for (int i = j + 1 + ty; i < jb; i += 16) {
-      const double lij = S[i][j];
+    const double rs = ok ? rsqrt_f64(dj) : 1.0;
+    const double invdj = rs * rs;
+    if (tid == 0 && !ok && j < jb) atomicCAS(status, 0, (int)STRP_ENOTPD);
+    if (tid >= j && tid < NB) Lm[tid][j] = S[tid][j] * rs;          // column j of the factor (diagonal: d * rs = sqrt d)
+    for (int i = j + 1 + ty; i < NB; i += 16) {
+      const double lij = S[i][j] * invdj;
       for (int k = j + 1 + tx; k <= i; k += 16) S[i][k] -= lij * S[k][j];
     }
     __syncthreads();
   }
-  // inverse of the (padded to 64, identity beyond jb) lower factor
-  if (tid < NB) V[tid][tid] = 1.0 / S[tid][tid];
+  // inverse of the lower factor by doubling: V21 = -V22 (L21 V11) for diagonal blocks of 1, 2, 4, ..., 32
+  if (tid < NB) V[tid][tid] = 1.0 / Lm[tid][tid];
   __syncthreads();
   for (int b = 1; b < NB; b <<= 1) {
-    // Tm[r2 + i][c] = sum_k L21[i][k] V11[k][c]   for every pair of blocks (r1 = 2 b p, r2 = r1 + b)
     for (int e = tid; e < (NB / 2) * b; e += 256) {
-      const int c = e % b, row = e / b;           // row = p * b + i over all pairs
+      const int c = e % b, row = e / b;           // row = p * b + i over all pairs p
       const int pr = row / b, i = row % b;
       const int r1 = 2 * b * pr, r2 = r1 + b;
       double acc = 0.0;
-      for (int k = c; k < b; ++k) acc += S[r2 + i][r1 + k] * V[r1 + k][r1 + c];
-      Tm[r2 + i][c] = acc;
+      for (int k = c; k < b; ++k) acc += Lm[r2 + i][r1 + k] * V[r1 + k][r1 + c];
+      S[r2 + i][c] = acc;
     }
     __syncthreads();
     for (int e = tid; e < (NB / 2) * b; e += 256) {
@@ -200,7 +204,7 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld
       const int pr = row / b, i = row % b;
       const int r1 = 2 * b * pr, r2 = r1 + b;
       double acc = 0.0;
-      for (int k = 0; k <= i; ++k) acc += V[r2 + i][r2 + k] * Tm[r2 + k][c];
+      for (int k = 0; k <= i; ++k) acc += V[r2 + i][r2 + k] * S[r2 + k][c];
       V[r2 + i][r1 + c] = -acc;
     }
     __syncthreads();
@@ -208,7 +212,7 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld
   for (int e = tid; e < NB * NB; e += 256) {
     const int i = e >> 6, j = e & 63;
     invd[e] = (i < jb && j < jb) ? V[i][j] : 0.0;
-    if (i < jb && j < jb) A[(long long)i * ld + j] = (j <= i) ? S[i][j] : 0.0;
+    if (i < jb && j < jb) A[(long long)i * ld + j] = (j <= i) ? Lm[i][j] : 0.0;
   }
 }
 

@@ -66,7 +66,9 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
         red0 += (double)rr * (double)rr;
       } else if (EPI == EPI_AUPD) {
         const long long o = (long long)p.oidx[m] * p.lda + n;
-        p.As[o] = __builtin_fmaxf(p.Zs[o], 0.0f) + v;
+        const float a = __builtin_fmaxf(p.Zs[o], 0.0f) + v;
+        p.As[o] = a;
+        outv[r] = a;
       } else {  // EPI_ZUPD
         const long long o = (long long)p.oidx[m] * p.lda + n;
         const float a = p.As[o];
@@ -90,8 +92,8 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
       }
     }
     // optional operand-plane copy of the produced tile (its rows are the contraction axis of the consumer):
-    // this lane's four rows are half of one 16-byte chunk
-    if ((EPI == EPI_STORE || EPI == EPI_INITZ || EPI == EPI_RESID) && p.k8_hi && n < p.N && mq < p.M) {
+    // this lane's four rows are half of one 16-byte chunk; rows past M inside the last chunk are written as zeros
+    if ((EPI == EPI_STORE || EPI == EPI_INITZ || EPI == EPI_RESID || EPI == EPI_AUPD) && p.k8_hi && n < p.N && (mq & ~7) < p.M) {
       unsigned short h[4], l[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) split_half(outv[r], h[r], l[r]);

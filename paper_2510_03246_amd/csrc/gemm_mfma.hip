@@ -286,7 +286,6 @@ strp_status launch_gemm(strp_ctx* ctx, GemmP& p) {
   if (!p.P.hi || !p.Q.hi) return fail(ctx, STRP_EINVAL, "gemm: null operand plane");
   if (p.P.kg * 8 < p.K || p.Q.kg * 8 < p.K || (p.P.kg & 1) || (p.Q.kg & 1)) return fail(ctx, STRP_EINVAL, "gemm: operand planes shorter than K or odd group count");
   if ((long long)p.P.npan * 128 < p.M || (long long)p.Q.npan * 128 < p.N) return fail(ctx, STRP_EINVAL, "gemm: operand planes narrower than the output");
-  if ((p.M % 8) && p.k8_hi) return fail(ctx, STRP_EINVAL, "gemm: plane output needs M %% 8 == 0");
   if (p.epi != EPI_PARTIAL && p.splits != 1) return fail(ctx, STRP_EINVAL, "gemm: fused epilogues do not split K");
   const int npp = p.P.lo ? 2 : 1, npq = p.Q.lo ? 2 : 1;
   static const char* const epi_names[] = {"partial", "store", "initz", "resid", "aupd", "zupd"};

@@ -118,6 +118,7 @@ __device__ __forceinline__ double small_src(const unsigned short* s, long long i
 // Small matrices (weights): planes of src * scale with k = column (contraction), r = row:
 // [ceil(rows/128)][ceil(cols/8)][128][8], zero padded.  transpose != 0 reads src[c][r].
 // scale_dev (device, may be null = 1) is a power of two chosen by weight_scale.
+// transpose == 2: src is symmetric and only its lower triangle is valid (reads src[max(r,c)][min(r,c)]).
 template <typename TS>
 __global__ __launch_bounds__(256) void split_small_kernel(const TS* src, long long lds, int rows, int cols, int transpose,
                                                           const float* scale_dev, unsigned short* hi, unsigned short* lo) {
@@ -131,7 +132,10 @@ __global__ __launch_bounds__(256) void split_small_kernel(const TS* src, long lo
   const int g = (int)(pg % KG), pan = (int)(pg / KG);
   const int r = pan * 128 + rr, c = g * 8 + j;
   double x = 0.0;
-  if (r < rows && c < cols) x = transpose ? small_src(src, (long long)c * lds + r) : small_src(src, (long long)r * lds + c);
+  if (r < rows && c < cols) {
+    if (transpose == 2) x = r >= c ? small_src(src, (long long)r * lds + c) : small_src(src, (long long)c * lds + r);
+    else x = transpose ? small_src(src, (long long)c * lds + r) : small_src(src, (long long)r * lds + c);
+  }
   x *= scale_dev ? (double)*scale_dev : 1.0;
   x = fmin(fmax(x, -65504.0), 65504.0);
   const _Float16 h = (_Float16)x;

@@ -108,6 +108,23 @@ __global__ __launch_bounds__(256) void transpose_f32_f64_kernel(const float* src
 // Rows of pruned units (mask == 0): W2[:, j] = 0 and W1[j, :] = 0 decouple them.
 //   phase 0 (a-update): A_j = relu(Z_j)
 //   phase 1 (z-update): exact z rule with z1 = 0; accumulates (A - relu Z)^2 and (Z - 0)^2
+//   phase 2: both in one pass over the row (A_j = relu(Z_j), then the z rule on the new A_j)
+__device__ __forceinline__ void pruned_elem(float& zv, float& av, int phase, float alpha, float beta, int write, double& r0, double& r1) {
+  if (phase != 1) av = __builtin_fmaxf(zv, 0.0f);
+  if (phase != 0) {
+    if (write) {
+      const float z2 = beta * av / (alpha + beta);
+      const float costm = beta * av * av;
+      const float cp = __builtin_fmaxf(z2, 0.0f);
+      const float costp = beta * (av - cp) * (av - cp) + alpha * cp * cp;
+      zv = costm < costp ? 0.0f : cp;
+    }
+    const float ra = av - __builtin_fmaxf(zv, 0.0f);
+    r0 += (double)ra * (double)ra;
+    r1 += (double)zv * (double)zv;
+  }
+}
+
 __global__ __launch_bounds__(256) void pruned_rows_kernel(const uint8_t* mask, float* Z, float* A, long long lda, long long T, int phase,
                                                           float alpha, float beta, int write, double* red) {
   const int j = blockIdx.x;
@@ -115,26 +132,23 @@ __global__ __launch_bounds__(256) void pruned_rows_kernel(const uint8_t* mask, f
   if (!mask[j]) {
     float* z = Z + (long long)j * lda;
     float* a = A + (long long)j * lda;
-    for (long long t = threadIdx.x; t < T; t += 256) {
-      if (phase == 0) {
-        a[t] = __builtin_fmaxf(z[t], 0.0f);
-      } else {
-        const float av = a[t];
-        float zv;
-        if (write) {
-          const float z2 = beta * av / (alpha + beta);
-          const float costm = beta * av * av;
-          const float cp = __builtin_fmaxf(z2, 0.0f);
-          const float costp = beta * (av - cp) * (av - cp) + alpha * cp * cp;
-          zv = costm < costp ? 0.0f : cp;
-          z[t] = zv;
-        } else {
-          zv = z[t];
-        }
-        const float ra = av - __builtin_fmaxf(zv, 0.0f);
-        r0 += (double)ra * (double)ra;
-        r1 += (double)zv * (double)zv;
-      }
+    const long long T4 = T >> 2;
+    for (long long c = threadIdx.x; c < T4; c += 256) {
+      float4 zv = ((const float4*)z)[c];
+      float4 av = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (phase == 1) av = ((const float4*)a)[c];
+      pruned_elem(zv.x, av.x, phase, alpha, beta, write, r0, r1);
+      pruned_elem(zv.y, av.y, phase, alpha, beta, write, r0, r1);
+      pruned_elem(zv.z, av.z, phase, alpha, beta, write, r0, r1);
+      pruned_elem(zv.w, av.w, phase, alpha, beta, write, r0, r1);
+      if (phase != 1) ((float4*)a)[c] = av;
+      if (phase != 0 && write) ((float4*)z)[c] = zv;
+    }
+    for (long long t = T4 * 4 + threadIdx.x; t < T; t += 256) {
+      float zv = z[t], av = phase == 1 ? a[t] : 0.0f;
+      pruned_elem(zv, av, phase, alpha, beta, write, r0, r1);
+      if (phase != 1) a[t] = av;
+      if (phase != 0 && write) z[t] = zv;
     }
   }
   if (red) {
@@ -754,21 +768,43 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     STRP_TRY(make_weight_planes(ctx, arena, W1S, SRC_F32, d, s, d, 0, npa, &W1Sp));
   }
 
+  // A_S as single-plane operand of the objective product: written by the a-update epilogue when both stages run
+  const bool fuse_obj_planes = (stages & STRP_STAGE_AUPD) && (stages & STRP_STAGE_OBJ);
+  const bool fuse_pruned = (stages & STRP_STAGE_AUPD) && (stages & STRP_STAGE_ZUPD);
+  unsigned short* akh = nullptr;
+  if (fuse_obj_planes) {
+    STRP_TAKE(ctx, arena, akh2, unsigned short, plane_elems(T, s));
+    akh = akh2;
+  }
   // ---- S7: a-update in residual (Woodbury) form ------------------------------------------------
   //   A_S = relu(Z_S) + W^T M^-1 (Y - W relu(Z_S)),  M = (beta/alpha) I + W W^T,  W = W2[:, S];  A_j = relu(Z_j) for pruned j
   if (stages & STRP_STAGE_AUPD) {
     Arena a2 = arena;
     STRP_TAKE(ctx, a2, Md, double, (size_t)d * d);
-    STRP_TAKE(ctx, a2, Minv, double, (size_t)d * d);
-    STRP_TAKE(ctx, a2, Bd, double, (size_t)s * d);
-    STRP_TAKE(ctx, a2, Btmp, double, (size_t)s * d);
+    STRP_TAKE(ctx, a2, Linv, double, (size_t)d * d);
+    STRP_TAKE(ctx, a2, Bf, float, (size_t)s * d);
     STRP_TRY(nt_product(ctx, a2, W2Sp, W2Sp, d, d, sp, 1, nullptr, 0, Md, d, nullptr, 0));
     hipLaunchKernelGGL(add_diag_kernel, dim3(blocks_for(d)), dim3(256), 0, ctx->stream, Md, (long long)d, d, params->beta / params->alpha, (const double*)nullptr);
-    STRP_TRY(factor_and_invert(ctx, a2, Md, d, Minv));
-    hipLaunchKernelGGL(transpose_f32_f64_kernel, dim3(blocks_for((long long)d * s)), dim3(256), 0, ctx->stream, W2S, sp, d, s, Bd, (long long)d);
-    STRP_TRY(apply_inverse_right(ctx, Minv, d, Bd, s, Btmp));
+    STRP_TRY(factor_and_invert(ctx, a2, Md, d, Linv));
+    // M is well conditioned (its spectrum lies in [beta/alpha, beta/alpha + |W|^2]): form M^-1 = Linv^T Linv
+    // (lower half, fp64) and B = W^T M^-1 on the fp16-split matrix cores instead of a third fp64 solve
+    STRP_TRY(fill_zero(ctx, Md, sizeof(double) * (size_t)d * d));
+    STRP_TRY(dgemm(ctx, d, d, d, 1.0, Linv, 1, d, Linv, d, 1, 0.0, Md, d, 1, 2));
     PlaneOp Bp, Zk8;
-    STRP_TRY(make_weight_planes(ctx, a2, Bd, SRC_F64, d, s, d, 0, npa, &Bp));
+    {
+      Arena a3 = a2;
+      PlaneOp Wt, Mi;
+      STRP_TRY(make_weight_planes(ctx, a3, W2S, SRC_F32, sp, s, d, 1, npa, &Wt));
+      STRP_TRY(make_weight_planes(ctx, a3, Md, SRC_F64, d, d, d, 2, npa, &Mi));
+      GemmP p;
+      memset(&p, 0, sizeof(p));
+      p.P = Wt; p.Q = Mi;
+      p.M = s; p.N = d; p.K = d;
+      p.epi = EPI_STORE; p.out = Bf; p.ldo = d;
+      gemm_plan_tiles(p, 1);
+      STRP_TRY(launch_gemm(ctx, p));
+    }
+    STRP_TRY(make_weight_planes(ctx, a2, Bf, SRC_F32, d, s, d, 0, npa, &Bp));
     STRP_TRY(make_c_planes(ctx, a2, st->Z, STRP_F32, lda, st->idx, s, T, 1, npa, &Zk8));
     STRP_TAKE(ctx, a2, ekh, unsigned short, plane_elems(T, d));
     unsigned short* ekl = nullptr;
@@ -792,10 +828,11 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
       p.P = Bp; p.Q = PlaneOp{ekh, ekl, plane_kg(d), (int)((T + 127) / 128), nullptr};
       p.M = s; p.N = (int)T; p.K = d;
       p.epi = EPI_AUPD; p.Zs = st->Z; p.As = st->A; p.lda = lda; p.oidx = st->idx;
+      p.k8_hi = akh; p.k8_lo = nullptr; p.k8_kg = plane_kg(s);
       gemm_plan_tiles(p, 1);
       STRP_TRY(launch_gemm(ctx, p));
     }
-    {
+    if (!fuse_pruned) {
       ProfScope ps(ctx, "pruned_rows_a", 0.0, 8.0 * (double)(f - s) * (double)T);
       hipLaunchKernelGGL(pruned_rows_kernel, dim3(f), dim3(256), 0, ctx->stream, st->mask, st->Z, st->A, lda, T, 0, alpha, beta, 1, (double*)nullptr);
     }
@@ -817,8 +854,9 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     STRP_TRY(launch_gemm(ctx, p));
     STRP_TRY(launch_block_sum(ctx, red, nb, sc + SC_TMP0, sc + SC_TMP1, 1.0, 1.0));
     {
-      ProfScope ps(ctx, "pruned_rows_z", 0.0, 8.0 * (double)(f - s) * (double)T);
-      hipLaunchKernelGGL(pruned_rows_kernel, dim3(f), dim3(256), 0, ctx->stream, st->mask, st->Z, st->A, lda, T, 1, alpha, beta, zupd ? 1 : 0, red);
+      ProfScope ps(ctx, fuse_pruned ? "pruned_rows_az" : "pruned_rows_z", 0.0, (fuse_pruned ? 12.0 : 8.0) * (double)(f - s) * (double)T);
+      hipLaunchKernelGGL(pruned_rows_kernel, dim3(f), dim3(256), 0, ctx->stream, st->mask, st->Z, st->A, lda, T, fuse_pruned ? 2 : 1, alpha, beta,
+                         zupd ? 1 : 0, red);
     }
     STRP_TRY(launch_block_sum(ctx, red, f, sc + SC_TMP2, sc + SC_TMP3, 1.0, 1.0));
     hipLaunchKernelGGL(axpby_scalar_kernel, dim3(1), dim3(1), 0, ctx->stream, sc, (int)SC_T2, params->beta / (double)T, (int)SC_TMP0, params->beta / (double)T, (int)SC_TMP2);
@@ -828,7 +866,11 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   if (stages & STRP_STAGE_OBJ) {
     Arena a2 = arena;
     PlaneOp Ak8;
-    STRP_TRY(make_c_planes(ctx, a2, st->A, STRP_F32, lda, st->idx, s, T, 0, 1, &Ak8));
+    if (fuse_obj_planes) {
+      Ak8 = PlaneOp{akh, nullptr, plane_kg(s), (int)((T + 127) / 128), nullptr};
+    } else {
+      STRP_TRY(make_c_planes(ctx, a2, st->A, STRP_F32, lda, st->idx, s, T, 0, 1, &Ak8));
+    }
     GemmP p;
     memset(&p, 0, sizeof(p));
     p.P = W2Sp; p.P.lo = nullptr; p.Q = Ak8;

@@ -154,10 +154,10 @@ strp_status tri_inverse(strp_ctx* ctx, const double* L, int n, long long ldl, co
 // In place X <- X (L L^T)^-1 = (X Linv^T) Linv for X [m x n] (ld n); tmp: m x n scratch.
 strp_status apply_inverse_right(strp_ctx* ctx, const double* Linv, int n, double* X, int m, double* tmp);
 // C[M x N] = alpha * A * B + beta * C with arbitrary element strides; lower != 0 skips tiles above
-// the diagonal.
+// the diagonal; tri = 1: only k < n0 + tile contributes, tri = 2: only k >= n0 (triangular B).
 strp_status dgemm(strp_ctx* ctx, int M, int N, int K, double alpha, const double* A, long long rsa,
                   long long csa, const double* B, long long rsb, long long csb, double beta, double* C,
-                  long long ldc, int lower);
+                  long long ldc, int lower, int tri = 0);
 // Ad[i*ld+j] = (double)Af[i*ldf+j] + (i==j ? lam (or *lam_dev if non-null) : 0)
 strp_status f32_to_f64_ridge(strp_ctx* ctx, const float* Af, long long ldf, double* Ad, long long ld, int n,
                              double lam, const double* lam_dev);
