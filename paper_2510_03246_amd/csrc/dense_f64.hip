@@ -159,40 +159,67 @@ __device__ __forceinline__ double rsqrt_f64(double d) {
   return y;
 }
 
-// One barrier per column: the working block S keeps UNSCALED columns (the trailing update only needs
-// S[i][j] S[k][j] / d_j), the scaled factor goes to Lm; every thread derives 1/sqrt(d_j) itself.
+// Thread (ty, tx) of the 16x16 block keeps the 16 elements (ty + 16 ii, tx + 16 kk) of the working block in
+// registers for the whole factorisation; per column only the column itself is exchanged through LDS (double
+// buffered, one barrier per column).  The trailing update uses the UNSCALED column: a_ik -= a_ij a_kj / d_j.
 __global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld, int jb, double* invd, int32_t* status) {
-  __shared__ double S[NB][NB + 1];    // working block, later the temporary of the inversion
+  __shared__ double S[NB][NB + 1];    // temporary of the inversion
   __shared__ double Lm[NB][NB + 1];   // factor (identity beyond jb)
   __shared__ double V[NB][NB + 1];    // inverse of the factor
+  __shared__ double col[2][NB];
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  double a[4][4];
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int i = ty + 16 * ii, k = tx + 16 * kk;
+      a[ii][kk] = (i < jb && k <= i) ? A[(long long)i * ld + k] : ((i == k) ? 1.0 : 0.0);
+    }
   for (int e = tid; e < NB * NB; e += 256) {
-    const int i = e >> 6, j = e & 63;
-    S[i][j] = (i < jb && j <= i) ? A[(long long)i * ld + j] : ((i == j) ? 1.0 : 0.0);
-    Lm[i][j] = 0.0;
-    V[i][j] = 0.0;
+    Lm[e >> 6][e & 63] = 0.0;
+    V[e >> 6][e & 63] = 0.0;
   }
-  __syncthreads();
   for (int j = 0; j < NB; ++j) {
-    const double dj = S[j][j];
+    double* cj = col[j & 1];
+    if (tx == (j & 15)) {       // owners of column j publish it (rows ty + 16 ii)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        if (kk == (j >> 4)) {
+#pragma unroll
+          for (int ii = 0; ii < 4; ++ii) cj[ty + 16 * ii] = a[ii][kk];
+        }
+    }
+    __syncthreads();
+    const double dj = cj[j];
     const bool ok = dj > 0.0;
     const double rs = ok ? rsqrt_f64(dj) : 1.0;
     const double invdj = rs * rs;
     if (tid == 0 && !ok && j < jb) atomicCAS(status, 0, (int)STRP_ENOTPD);
-    if (tid >= j && tid < NB) Lm[tid][j] = S[tid][j] * rs;          // column j of the factor (diagonal: d * rs = sqrt d)
-    for (int i = j + 1 + ty; i < NB; i += 16) {
-      const double lij = S[i][j] * invdj;
-      for (int k = j + 1 + tx; k <= i; k += 16) S[i][k] -= lij * S[k][j];
+    if (tid >= j && tid < NB) Lm[tid][j] = cj[tid] * rs;   // column j of the factor (diagonal: d * rs = sqrt d)
+    double ci[4], ck[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      ci[q] = cj[ty + 16 * q] * invdj;
+      ck[q] = cj[tx + 16 * q];
     }
-    __syncthreads();
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const int i = ty + 16 * ii, k = tx + 16 * kk;
+        if (k > j && k <= i) a[ii][kk] -= ci[ii] * ck[kk];
+      }
   }
+  __syncthreads();
   // inverse of the lower factor by doubling: V21 = -V22 (L21 V11) for diagonal blocks of 1, 2, 4, ..., 32
   if (tid < NB) V[tid][tid] = 1.0 / Lm[tid][tid];
   __syncthreads();
-  for (int b = 1; b < NB; b <<= 1) {
+  for (int lb = 0; (1 << lb) < NB; ++lb) {
+    const int b = 1 << lb;
     for (int e = tid; e < (NB / 2) * b; e += 256) {
-      const int c = e % b, row = e / b;           // row = p * b + i over all pairs p
-      const int pr = row / b, i = row % b;
+      const int c = e & (b - 1), row = e >> lb;   // row = p * b + i over all pairs p
+      const int pr = row >> lb, i = row & (b - 1);
       const int r1 = 2 * b * pr, r2 = r1 + b;
       double acc = 0.0;
       for (int k = c; k < b; ++k) acc += Lm[r2 + i][r1 + k] * V[r1 + k][r1 + c];
@@ -200,8 +227,8 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld
     }
     __syncthreads();
     for (int e = tid; e < (NB / 2) * b; e += 256) {
-      const int c = e % b, row = e / b;
-      const int pr = row / b, i = row % b;
+      const int c = e & (b - 1), row = e >> lb;
+      const int pr = row >> lb, i = row & (b - 1);
       const int r1 = 2 * b * pr, r2 = r1 + b;
       double acc = 0.0;
       for (int k = 0; k <= i; ++k) acc += V[r2 + i][r2 + k] * S[r2 + k][c];
