@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--tokens", type=int, default=0, help="override T (0: the configuration's 128 x 2048)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="before the timed region run one elementwise copy kernel that reads 1 GiB and writes 1 GiB, "
+                         "as the known-size reference for scaling hardware byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the per-module ADMM path on ONE GPU (modules and token shards would be "
@@ -74,6 +77,12 @@ def main():
     torch.cuda.synchronize()
     if ctx.poll() != strp.OK:
         raise RuntimeError("device status word not clean after warm-up")
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.mul(src, 1.0)      # one elementwise kernel: 2^30 bytes in, 2^30 bytes out
+        torch.cuda.synchronize()
+        del src, dst
 
     ctx.profile_enable(True)
     torch.cuda.synchronize()
