@@ -13,7 +13,9 @@ typedef double doublex4 __attribute__((ext_vector_type(4)));
 //   block = 4 wavefronts (2x2), wavefront tile = WT x WT MFMA tiles of 16x16, K staged 16 at a time.
 //   batch (grid.z): operand pointers advance by sa / sb / sc elements per batch entry and the batch
 //   entry's M and K are clamped to lim_base - z * lim_step (ragged last block of a blocked algorithm).
-//   tri = 1: B is upper-triangular in (k, n) block terms (k < n0 + tile), tri = 2: k >= n0.
+//   tri restricts the K range of a tile to where a triangular operand is non-zero:
+//     1: k < n0 + tile (B upper in (k, n)),  2: k >= n0 (B lower),  3: k >= m0 (A upper in (m, k)),
+//     4: k < m0 + tile (A lower).
 //   lower != 0 skips output tiles entirely above the diagonal.
 // MFMA lane layout: A operand lane l = A[i = l % 16][k = l / 16], B operand lane l = B[k = l / 16][j = l % 16],
 // result register r of lane l = D[i = 4 r + l / 16][j = l % 16].
@@ -35,8 +37,10 @@ __global__ __launch_bounds__(256) void dgemm_kernel(const DgemmP p) {
   constexpr int TS = 32 * WT;      // block tile (rows and columns)
   constexpr int DK = 16;
   constexpr int LD = TS + 4;
-  __shared__ double As[DK][LD];
-  __shared__ double Bs[DK][LD];
+  // double-buffered operand tiles: one barrier per K tile; 66 KB at TS = 128, i.e. two blocks per CU, so a
+  // large grid is handed out as blocks retire (heavy tiles first, see below) instead of all at once
+  __shared__ double As[2][DK][LD];
+  __shared__ double Bs[2][DK][LD];
   const int z = blockIdx.z;
   int M = p.M, K = p.K;
   if (p.lim_step) {
@@ -45,7 +49,9 @@ __global__ __launch_bounds__(256) void dgemm_kernel(const DgemmP p) {
     if (p.clamp_k) K = K < lim ? K : lim;
   }
   const int N = p.N;
-  const int m0 = blockIdx.y * TS, n0 = blockIdx.x * TS;
+  // blockIdx.x walks the rows of C; blockIdx.y walks column tiles in order of decreasing K range
+  const int ntile = (p.tri == 1) ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y;
+  const int m0 = blockIdx.x * TS, n0 = ntile * TS;
   if (M <= 0 || m0 >= M) return;
   if (p.lower && n0 >= m0 + TS) return;
   const double* A = p.A + (long long)z * p.sa;
@@ -53,7 +59,9 @@ __global__ __launch_bounds__(256) void dgemm_kernel(const DgemmP p) {
   double* C = p.C + (long long)z * p.sc;
   int kbeg = 0, kend = K;
   if (p.tri == 1) kend = (n0 + TS < K) ? n0 + TS : K;
-  if (p.tri == 2) kbeg = (n0 / DK) * DK;
+  if (p.tri == 2) kbeg = n0;            // multiples of TS, hence of DK
+  if (p.tri == 3) kbeg = m0;
+  if (p.tri == 4) kend = (m0 + TS < K) ? m0 + TS : K;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -77,37 +85,43 @@ __global__ __launch_bounds__(256) void dgemm_kernel(const DgemmP p) {
       rb[i] = (n0 + n < N && k0 + kb < kend) ? B[(long long)(k0 + kb) * p.rsb + (long long)(n0 + n) * p.csb] : 0.0;
     }
   };
-  auto sstore = [&]() {
+  auto sstore = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < EPT; ++i) {
       const int e = tid + 256 * i;
       int m, k;
       if (p.csa == 1) { m = e / DK; k = e % DK; } else { k = e / TS; m = e % TS; }
-      As[k][m] = ra[i];
+      As[buf][k][m] = ra[i];
       int n, kb;
       if (p.csb == 1) { kb = e / TS; n = e % TS; } else { n = e / DK; kb = e % DK; }
-      Bs[kb][n] = rb[i];
+      Bs[buf][kb][n] = rb[i];
     }
   };
-  if (kbeg < kend) gload(kbeg);
+  if (kbeg < kend) {
+    gload(kbeg);
+    sstore(0);
+  }
+  __syncthreads();
+  int buf = 0;
   for (int k0 = kbeg; k0 < kend; k0 += DK) {
-    sstore();
-    __syncthreads();
-    if (k0 + DK < kend) gload(k0 + DK);
+    const bool more = k0 + DK < kend;
+    if (more) gload(k0 + DK);
 #pragma unroll
     for (int ks = 0; ks < DK / 4; ++ks) {
       double af[WT], bf[WT];
       const int kk = ks * 4 + (lane >> 4);
 #pragma unroll
-      for (int i = 0; i < WT; ++i) af[i] = As[kk][wm * 16 * WT + i * 16 + (lane & 15)];
+      for (int i = 0; i < WT; ++i) af[i] = As[buf][kk][wm * 16 * WT + i * 16 + (lane & 15)];
 #pragma unroll
-      for (int j = 0; j < WT; ++j) bf[j] = Bs[kk][wn * 16 * WT + j * 16 + (lane & 15)];
+      for (int j = 0; j < WT; ++j) bf[j] = Bs[buf][kk][wn * 16 * WT + j * 16 + (lane & 15)];
 #pragma unroll
       for (int i = 0; i < WT; ++i)
 #pragma unroll
         for (int j = 0; j < WT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(af[i], bf[j], acc[i][j], 0, 0, 0);
     }
+    if (more) sstore(buf ^ 1);   // the other buffer: its readers finished before the previous barrier
     __syncthreads();
+    buf ^= 1;
   }
 #pragma unroll
   for (int i = 0; i < WT; ++i)
@@ -130,7 +144,7 @@ static strp_status dgemm_launch(strp_ctx* ctx, const DgemmP& p, int batch) {
   if (p.M <= 0 || p.N <= 0 || batch <= 0) return STRP_OK;
   const bool big = p.M > 64 && p.N > 64;
   const int ts = big ? 128 : 64;
-  dim3 grid((p.N + ts - 1) / ts, (p.M + ts - 1) / ts, batch);
+  dim3 grid((p.M + ts - 1) / ts, (p.N + ts - 1) / ts, batch);
   if (big)
     hipLaunchKernelGGL((dgemm_kernel<4>), grid, dim3(256), 0, ctx->stream, p);
   else
@@ -149,8 +163,7 @@ strp_status dgemm(strp_ctx* ctx, int M, int N, int K, double alpha, const double
 }
 
 // ---------------------------------------------------------------------------------------------
-// Diagonal block: Cholesky of a jb x jb block (jb <= 64) in LDS and the inverse of its factor
-// (inverse by recursive doubling: V21 = -V22 (L21 V11) for blocks of 1, 2, 4, ... 32)
+// Diagonal block: Cholesky of a jb x jb block (jb <= 64) and the inverse of its factor
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ double rsqrt_f64(double d) {
   double y = __builtin_amdgcn_rsq(d);
@@ -159,29 +172,30 @@ __device__ __forceinline__ double rsqrt_f64(double d) {
   return y;
 }
 
-// Thread (ty, tx) of the 16x16 block keeps the 16 elements (ty + 16 ii, tx + 16 kk) of the working block in
-// registers for the whole factorisation; per column only the column itself is exchanged through LDS (double
-// buffered, one barrier per column).  The trailing update uses the UNSCALED column: a_ik -= a_ij a_kj / d_j.
+// Thread (ty, tx) of the 16x16 block keeps the 16 elements (ty + 16 ii, tx + 16 kk) of the working block AND of
+// the inverse being built in registers for the whole factorisation; per column only the column itself and
+// row j of the inverse are exchanged through LDS (double buffered, one barrier per column).
+//   trailing update with the UNSCALED column:  a_ik -= (a_ij / d_j) a_kj
+//   inverse: A = Lu D Lu^T with Lu unit lower; the same multipliers m_ij = a_ij / d_j applied to the identity
+//   (V_i. -= m_ij V_j. for i > j) give Lu^-1, and L^-1 = D^-1/2 Lu^-1.
 __global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld, int jb, double* invd, int32_t* status) {
-  __shared__ double S[NB][NB + 1];    // temporary of the inversion
-  __shared__ double Lm[NB][NB + 1];   // factor (identity beyond jb)
-  __shared__ double V[NB][NB + 1];    // inverse of the factor
+  __shared__ double Lm[NB][NB + 1];   // factor, entries on and below the diagonal
   __shared__ double col[2][NB];
+  __shared__ double vrow[2][NB];
+  __shared__ double rsd[NB];          // d_j^-1/2
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
-  double a[4][4];
+  double a[4][4], v[4][4];
 #pragma unroll
   for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       const int i = ty + 16 * ii, k = tx + 16 * kk;
       a[ii][kk] = (i < jb && k <= i) ? A[(long long)i * ld + k] : ((i == k) ? 1.0 : 0.0);
+      v[ii][kk] = (i == k) ? 1.0 : 0.0;
     }
-  for (int e = tid; e < NB * NB; e += 256) {
-    Lm[e >> 6][e & 63] = 0.0;
-    V[e >> 6][e & 63] = 0.0;
-  }
   for (int j = 0; j < NB; ++j) {
     double* cj = col[j & 1];
+    double* vj = vrow[j & 1];
     if (tx == (j & 15)) {       // owners of column j publish it (rows ty + 16 ii)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
@@ -190,57 +204,52 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld
           for (int ii = 0; ii < 4; ++ii) cj[ty + 16 * ii] = a[ii][kk];
         }
     }
+    if (ty == (j & 15)) {       // owners of row j of the inverse publish it (columns tx + 16 kk)
+#pragma unroll
+      for (int ii = 0; ii < 4; ++ii)
+        if (ii == (j >> 4)) {
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) vj[tx + 16 * kk] = v[ii][kk];
+        }
+    }
     __syncthreads();
     const double dj = cj[j];
     const bool ok = dj > 0.0;
     const double rs = ok ? rsqrt_f64(dj) : 1.0;
     const double invdj = rs * rs;
-    if (tid == 0 && !ok && j < jb) atomicCAS(status, 0, (int)STRP_ENOTPD);
+    if (tid == 0) {
+      rsd[j] = rs;
+      if (!ok && j < jb) atomicCAS(status, 0, (int)STRP_ENOTPD);
+    }
     if (tid >= j && tid < NB) Lm[tid][j] = cj[tid] * rs;   // column j of the factor (diagonal: d * rs = sqrt d)
-    double ci[4], ck[4];
+    double ci[4], ck[4], cv[4], vk[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       ci[q] = cj[ty + 16 * q] * invdj;
       ck[q] = cj[tx + 16 * q];
+      cv[q] = (ty + 16 * q > j) ? ci[q] : 0.0;
+      vk[q] = vj[tx + 16 * q];
     }
+    // a: unpredicated (columns <= j were published before this point and are not read again from registers,
+    // entries above the diagonal are never used); v: only rows below j change
 #pragma unroll
     for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        const int i = ty + 16 * ii, k = tx + 16 * kk;
-        if (k > j && k <= i) a[ii][kk] -= ci[ii] * ck[kk];
+        a[ii][kk] = __builtin_fma(-ci[ii], ck[kk], a[ii][kk]);
+        v[ii][kk] = __builtin_fma(-cv[ii], vk[kk], v[ii][kk]);
       }
   }
   __syncthreads();
-  // inverse of the lower factor by doubling: V21 = -V22 (L21 V11) for diagonal blocks of 1, 2, 4, ..., 32
-  if (tid < NB) V[tid][tid] = 1.0 / Lm[tid][tid];
-  __syncthreads();
-  for (int lb = 0; (1 << lb) < NB; ++lb) {
-    const int b = 1 << lb;
-    for (int e = tid; e < (NB / 2) * b; e += 256) {
-      const int c = e & (b - 1), row = e >> lb;   // row = p * b + i over all pairs p
-      const int pr = row >> lb, i = row & (b - 1);
-      const int r1 = 2 * b * pr, r2 = r1 + b;
-      double acc = 0.0;
-      for (int k = c; k < b; ++k) acc += Lm[r2 + i][r1 + k] * V[r1 + k][r1 + c];
-      S[r2 + i][c] = acc;
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int i = ty + 16 * ii, k = tx + 16 * kk;
+      const bool in = i < jb && k < jb;
+      invd[i * NB + k] = (in && k <= i) ? v[ii][kk] * rsd[i] : 0.0;
+      if (in) A[(long long)i * ld + k] = (k <= i) ? Lm[i][k] : 0.0;
     }
-    __syncthreads();
-    for (int e = tid; e < (NB / 2) * b; e += 256) {
-      const int c = e & (b - 1), row = e >> lb;
-      const int pr = row >> lb, i = row & (b - 1);
-      const int r1 = 2 * b * pr, r2 = r1 + b;
-      double acc = 0.0;
-      for (int k = 0; k <= i; ++k) acc += V[r2 + i][r2 + k] * S[r2 + k][c];
-      V[r2 + i][r1 + c] = -acc;
-    }
-    __syncthreads();
-  }
-  for (int e = tid; e < NB * NB; e += 256) {
-    const int i = e >> 6, j = e & 63;
-    invd[e] = (i < jb && j < jb) ? V[i][j] : 0.0;
-    if (i < jb && j < jb) A[(long long)i * ld + j] = (j <= i) ? Lm[i][j] : 0.0;
-  }
 }
 
 // X[rows x jb] <- X * Mt, Mt[k][c] = trans ? Linv[c][k] : Linv[k][c]; one block per 64 rows
@@ -338,6 +347,7 @@ strp_status tri_inverse(strp_ctx* ctx, const double* L, int n, long long ldl, co
     p.C = tmp + (long long)b * n; p.ldc = n;
     p.sa = 2LL * b * ldl + 2LL * b; p.sb = 2LL * b * n + 2LL * b; p.sc = p.sb;
     p.lim_base = n - b; p.lim_step = 2 * b; p.lower = 0;
+    p.tri = 2;   // V11 is lower triangular
     STRP_TRY(dgemm_launch(ctx, p, pairs));
     // V21 = -V22 tmp21   (M and K both limited to the rows of the second block)
     p.alpha = -1.0;
@@ -345,6 +355,7 @@ strp_status tri_inverse(strp_ctx* ctx, const double* L, int n, long long ldl, co
     p.B = tmp + (long long)b * n; p.rsb = n; p.csb = 1;
     p.C = Linv + (long long)b * n; p.ldc = n;
     p.clamp_k = 1;
+    p.tri = 4;   // V22 is lower triangular
     STRP_TRY(dgemm_launch(ctx, p, pairs));
   }
   return STRP_OK;

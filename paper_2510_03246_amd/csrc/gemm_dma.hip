@@ -53,26 +53,8 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma_kernel(const GemmP p) {
   __shared__ double sred[NW][2];
 
   // ---- which tile, which K range ---------------------------------------------------------
-  int bid = blockIdx.x;
-  const int split = bid / p.ntiles;
-  int t = bid - split * p.ntiles;
-  if ((p.ntiles & 7) == 0) t = (t & 7) * (p.ntiles >> 3) + (t >> 3);  // one XCD owns a contiguous tile range
-  int tm, tn;
-  if (p.triangle) {
-    tm = (int)((__builtin_sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
-    while ((tm + 1) * (tm + 2) / 2 <= t) ++tm;
-    while (tm * (tm + 1) / 2 > t) --tm;
-    tn = t - tm * (tm + 1) / 2;
-  } else {
-    const int G = 4;
-    const int per_group = G * p.tilesN;
-    const int grp = t / per_group;
-    const int first_m = grp * G;
-    const int gsz = (p.tilesM - first_m) < G ? (p.tilesM - first_m) : G;
-    const int w = t - grp * per_group;
-    tm = first_m + w % gsz;
-    tn = w / gsz;
-  }
+  int tm, tn, split;
+  if (!decode_tile(p, (int)blockIdx.x, (int)gridDim.x, tm, tn, split)) return;
   const int m0 = tm * ROWS, n0 = tn * ROWS;
   const long long k0 = (long long)split * p.kchunk;
   const long long k1 = (k0 + p.kchunk < p.K) ? (k0 + p.kchunk) : p.K;

@@ -98,26 +98,8 @@ __global__ __launch_bounds__(256, WT == 4 ? 1 : 2) void gemm_kernel(const GemmP 
   __shared__ double sred[4][2];
 
   // ---- which tile, which K range ---------------------------------------------------------
-  int bid = blockIdx.x;
-  const int split = bid / p.ntiles;
-  int t = bid - split * p.ntiles;
-  if ((p.ntiles & 7) == 0) t = (t & 7) * (p.ntiles >> 3) + (t >> 3);  // one XCD owns a contiguous tile range
-  int tm, tn;
-  if (p.triangle) {
-    tm = (int)((__builtin_sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
-    while ((tm + 1) * (tm + 2) / 2 <= t) ++tm;
-    while (tm * (tm + 1) / 2 > t) --tm;
-    tn = t - tm * (tm + 1) / 2;
-  } else {
-    const int G = WT == 4 ? 4 : 8;
-    const int per_group = G * p.tilesN;
-    const int grp = t / per_group;
-    const int first_m = grp * G;
-    const int gsz = (p.tilesM - first_m) < G ? (p.tilesM - first_m) : G;
-    const int w = t - grp * per_group;
-    tm = first_m + w % gsz;
-    tn = w / gsz;
-  }
+  int tm, tn, split;
+  if (!decode_tile(p, (int)blockIdx.x, (int)gridDim.x, tm, tn, split)) return;
   const int m0 = tm * ROWS, n0 = tn * ROWS;
   const long long k0 = (long long)split * p.kchunk;
   const long long k1 = (k0 + p.kchunk < p.K) ? (k0 + p.kchunk) : p.K;
@@ -248,6 +230,24 @@ void gemm_plan_tiles(GemmP& p, int want_splits) {
   p.tilesM = (p.M + ROWS - 1) / ROWS;
   p.tilesN = (p.N + ROWS - 1) / ROWS;
   p.ntiles = p.triangle ? p.tilesM * (p.tilesM + 1) / 2 : p.tilesM * p.tilesN;
+  if (p.triangle) {
+    p.gridM = (p.tilesM + 1) / 2;
+    p.gridN = 2 * p.gridM + 1;
+  } else {
+    p.gridM = p.tilesM;
+    p.gridN = p.tilesN;
+  }
+  {
+    // tile group: 32 tiles, shaped to the grid (STRP_GROUP=<gm> overrides the row count, for experiments)
+    static const int env_gm = getenv("STRP_GROUP") ? atoi(getenv("STRP_GROUP")) : 0;
+    int gm = env_gm > 0 ? env_gm : 4;
+    if (gm > 32) gm = 32;
+    while (gm > 1 && gm > p.gridM) gm >>= 1;
+    int gn = 32 / gm;
+    while (gn > 1 && gn / 2 >= p.gridN) { gn >>= 1; if (gm * 2 <= p.gridM) gm <<= 1; }
+    p.gm = gm;
+    p.gn = gn;
+  }
   if (want_splits <= 1) {
     p.splits = 1;
     p.kchunk = ((p.K + BK - 1) / BK) * BK;
@@ -259,7 +259,7 @@ void gemm_plan_tiles(GemmP& p, int want_splits) {
   }
 }
 
-int gemm_grid_blocks(const GemmP& p) { return p.ntiles * p.splits; }
+int gemm_grid_blocks(const GemmP& p) { return p.gridM * p.gridN * p.splits; }
 
 // zero the pad k-group (index kg - 1) of a plane written by an epilogue whose row count is an odd number of groups
 __global__ __launch_bounds__(256) void zero_pad_group_kernel(unsigned short* hi, unsigned short* lo, long long kg, int npan) {

@@ -789,7 +789,7 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     // M is well conditioned (its spectrum lies in [beta/alpha, beta/alpha + |W|^2]): form M^-1 = Linv^T Linv
     // (lower half, fp64) and B = W^T M^-1 on the fp16-split matrix cores instead of a third fp64 solve
     STRP_TRY(fill_zero(ctx, Md, sizeof(double) * (size_t)d * d));
-    STRP_TRY(dgemm(ctx, d, d, d, 1.0, Linv, 1, d, Linv, d, 1, 0.0, Md, d, 1, 2));
+    STRP_TRY(dgemm(ctx, d, d, d, 1.0, Linv, 1, d, Linv, d, 1, 0.0, Md, d, 1, 3));
     PlaneOp Bp, Zk8;
     {
       Arena a3 = a2;

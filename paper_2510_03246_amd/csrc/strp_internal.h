@@ -98,6 +98,8 @@ struct GemmP {
   int force_wt;        // 2 forces the 128x128 register-staged kernel
   int wt;              // 32x32 MFMA tiles per wavefront per dimension: 2 (128x128 blocks) or 4 (256x256), set by gemm_plan_tiles
   int tilesM, tilesN, ntiles;
+  int gridM, gridN;    // tile grid the blocks are laid over: tilesM x tilesN, or the folded triangle (see decode_tile)
+  int gm, gn;          // tile group (gm x gn = tiles that are resident on one XCD together)
   int triangle;        // P == Q, only tiles with tn <= tm are computed
   int splits;
   long long kchunk;    // K range per split (multiple of the K tile)
@@ -154,7 +156,8 @@ strp_status tri_inverse(strp_ctx* ctx, const double* L, int n, long long ldl, co
 // In place X <- X (L L^T)^-1 = (X Linv^T) Linv for X [m x n] (ld n); tmp: m x n scratch.
 strp_status apply_inverse_right(strp_ctx* ctx, const double* Linv, int n, double* X, int m, double* tmp);
 // C[M x N] = alpha * A * B + beta * C with arbitrary element strides; lower != 0 skips tiles above
-// the diagonal; tri = 1: only k < n0 + tile contributes, tri = 2: only k >= n0 (triangular B).
+// the diagonal; tri limits a tile's K range to the non-zero part of a triangular operand: 1: k < n0 + tile,
+// 2: k >= n0 (B), 3: k >= m0, 4: k < m0 + tile (A).
 strp_status dgemm(strp_ctx* ctx, int M, int N, int K, double alpha, const double* A, long long rsa,
                   long long csa, const double* B, long long rsb, long long csb, double beta, double* C,
                   long long ldc, int lower, int tri = 0);
