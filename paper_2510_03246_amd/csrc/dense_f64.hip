@@ -301,20 +301,35 @@ static strp_status panel_mul(strp_ctx* ctx, double* X, long long ldx, int rows, 
   return STRP_OK;
 }
 
+// Two-level right-looking blocking: 64-column steps (diagonal block + panel) update only the rest of their
+// 256-column outer panel; the trailing matrix is updated once per outer panel with K = 256, which quarters the
+// read-modify-write traffic of the trailing matrix (a rank-64 update of a 4915 x 4915 matrix is memory bound).
 strp_status chol_factor(strp_ctx* ctx, double* A, int n, long long ld, double* invd, int32_t* status) {
   ProfScope ps(ctx, "chol_factor_f64", (double)n * n * n / 3.0, 8.0 * (double)n * n);
-  for (int j0 = 0; j0 < n; j0 += NB) {
-    const int jb = (n - j0 < NB) ? (n - j0) : NB;
-    double* Ajj = A + (long long)j0 * ld + j0;
-    double* inv = invd + (long long)(j0 / NB) * NB * NB;
-    hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(256), 0, ctx->stream, Ajj, ld, jb, inv, status);
-    STRP_HIP(ctx, hipGetLastError());
-    const int rest = n - j0 - jb;
-    if (rest > 0) {
+  constexpr int NB2 = 4 * NB;
+  for (int J0 = 0; J0 < n; J0 += NB2) {
+    const int Jend = (n - J0 < NB2) ? n : J0 + NB2;
+    for (int j0 = J0; j0 < Jend; j0 += NB) {
+      const int jb = (n - j0 < NB) ? (n - j0) : NB;
+      double* Ajj = A + (long long)j0 * ld + j0;
+      double* inv = invd + (long long)(j0 / NB) * NB * NB;
+      hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(256), 0, ctx->stream, Ajj, ld, jb, inv, status);
+      STRP_HIP(ctx, hipGetLastError());
+      const int rest = n - j0 - jb;
+      if (rest <= 0) continue;
       double* A21 = A + (long long)(j0 + jb) * ld + j0;
       STRP_TRY(panel_mul(ctx, A21, ld, rest, jb, inv, 1));
-      double* A22 = A + (long long)(j0 + jb) * ld + (j0 + jb);
-      STRP_TRY(dgemm(ctx, rest, rest, jb, -1.0, A21, ld, 1, A21, 1, ld, 1.0, A22, ld, 1));
+      const int pc = Jend - (j0 + jb);   // columns of the outer panel still to be factored
+      if (pc > 0) {
+        double* A22 = A + (long long)(j0 + jb) * ld + (j0 + jb);
+        STRP_TRY(dgemm(ctx, rest, pc, jb, -1.0, A21, ld, 1, A21, 1, ld, 1.0, A22, ld, 1));
+      }
+    }
+    const int rest2 = n - Jend;
+    if (rest2 > 0) {
+      const double* P = A + (long long)Jend * ld + J0;
+      double* C = A + (long long)Jend * ld + Jend;
+      STRP_TRY(dgemm(ctx, rest2, rest2, Jend - J0, -1.0, P, ld, 1, P, 1, ld, 1.0, C, ld, 1));
     }
   }
   return STRP_OK;

@@ -315,30 +315,52 @@ strp_status launch_gemm(strp_ctx* ctx, GemmP& p) {
 }
 
 // ---- split-K reduction -----------------------------------------------------------------------
+// One block reduces a 32 x 32 output tile (thread = column tx, rows ty + 8 i).  Symmetric products: only tiles on
+// or below the diagonal are reduced; the strict lower part is also written transposed through LDS, so the upper
+// half is a bit-exact mirror and the partials are read once, row-contiguously.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* part, int splits, int M, int N, int triangle,
                                                            float* outf, long long ldof, double* outd, long long ldod,
                                                            double* diag, int accumulate) {
-  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (e >= (long long)M * N) return;
-  const int m = (int)(e / N), n = (int)(e % N);
-  long long src = e;
-  if (triangle && n > m) src = (long long)n * N + m;  // upper half mirrors the computed lower half (exact symmetry)
-  double s = 0.0;
-  for (int sp = 0; sp < splits; ++sp) s += (double)part[(long long)sp * M * N + src];
-  if (outf) {
-    float* o = outf + (long long)m * ldof + n;
-    *o = accumulate ? (float)((double)*o + s) : (float)s;
+  __shared__ double tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int n0 = blockIdx.x * 32, m0 = blockIdx.y * 32;
+  if (triangle && n0 > m0) return;
+  const long long MN = (long long)M * N;
+  auto put = [&](int m, int n, double s) {
+    if (outf) {
+      float* o = outf + (long long)m * ldof + n;
+      *o = accumulate ? (float)((double)*o + s) : (float)s;
+    }
+    if (outd) outd[(long long)m * ldod + n] = s;
+    if (diag && m == n) diag[m] = s;
+  };
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + ty + 8 * i, n = n0 + tx;
+    double s = 0.0;
+    if (m < M && n < N) {
+      const float* src = part + (long long)m * N + n;
+      for (int sp = 0; sp < splits; ++sp) s += (double)src[(long long)sp * MN];
+      if (!triangle || n <= m) put(m, n, s);
+    }
+    tile[ty + 8 * i][tx] = s;
   }
-  if (outd) outd[(long long)m * ldod + n] = s;
-  if (diag && m == n) diag[m] = s;
+  if (!triangle) return;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int lo_m = m0 + tx, lo_n = n0 + ty + 8 * i;     // element (lo_m, lo_n) of the lower half, mirrored to (lo_n, lo_m)
+    if (lo_n < lo_m && lo_m < M && lo_n < N) put(lo_n, lo_m, tile[tx][ty + 8 * i]);
+  }
 }
 
 strp_status launch_splitk_reduce(strp_ctx* ctx, const float* part, int splits, int M, int N, int triangle,
                                  float* outf, long long ldof, double* outd, long long ldod, double* diag,
                                  int accumulate) {
   const long long tot = (long long)M * N;
-  ProfScope ps(ctx, "splitk_reduce", 0.0, 4.0 * (double)tot * (double)splits + (outf ? 4.0 : 0.0) * tot + (outd ? 8.0 : 0.0) * tot);
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, ctx->stream, part,
+  if (triangle && M != N) return fail(ctx, STRP_EINVAL, "split-K reduce: a symmetric product must be square");
+  ProfScope ps(ctx, "splitk_reduce", 0.0, 4.0 * (double)tot * (double)splits * (triangle ? 0.5 : 1.0) + (outf ? 4.0 : 0.0) * tot + (outd ? 8.0 : 0.0) * tot);
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((N + 31) / 32, (M + 31) / 32), dim3(256), 0, ctx->stream, part,
                      splits, M, N, triangle, outf, ldof, outd, ldod, diag, accumulate);
   STRP_HIP(ctx, hipGetLastError());
   return STRP_OK;

@@ -19,73 +19,106 @@ __device__ __forceinline__ unsigned int sp_pack2(unsigned short a, unsigned shor
   return (unsigned int)a | ((unsigned int)b << 16);
 }
 
-// Activations [rows x T] (optionally gathered by idx): one thread converts 8 rows x 8 tokens.
-//   T-planes (contraction over tokens,   k = token,   r = channel row): [ceil(rows/128)][ceil(T/8)][128][8]
-//   C-planes (contraction over channels, k = channel, r = token):       [ceil(T/128)][ceil(rows/8)][128][8]
-// grid.x walks token groups of 8 (256 per block), grid.y row groups of 8 (covering the padded panel rows).
+// Activations [rows x T] (optionally gathered by idx) -> planes.  Both kernels read the source row-contiguously
+// and write whole contiguous kilobytes per wavefront store (a 16-byte chunk per lane, consecutive lanes =
+// consecutive chunks): partial-line stores cost twice the HBM write traffic.
+//   T-planes (contraction over tokens,   k = token,   r = channel row): [ceil(rows/128)][KG(T)][128][8]
+//   C-planes (contraction over channels, k = channel, r = token):       [ceil(T/128)][KG(rows)][128][8]
 template <bool SRC_BF16>
-__global__ __launch_bounds__(256) void split_act_kernel(const void* src, long long lds, const int* idx, int rows, long long T,
-                                                        int relu_t, int relu_c, unsigned short* t_hi, unsigned short* t_lo,
-                                                        unsigned short* c_hi, unsigned short* c_lo) {
-  const int rg = blockIdx.y;                                        // row group
-  const long long tg = (long long)blockIdx.x * 256 + threadIdx.x;  // token group
-  const long long TG = (T + 7) >> 3;
-  const long long TGa = (TG + 1) & ~1LL;                            // allocated token groups (even)
-  const long long TGpad = ((T + 127) >> 7) << 4;                    // token groups covered by whole token panels
-  const int KGc = (rows + 7) >> 3;
-  const int KGa = (KGc + 1) & ~1;                                   // allocated channel groups (even)
-  if (tg >= TGpad) return;
-  float v[8][8];
+__device__ __forceinline__ void load4(const void* src, long long off, float (&v)[4]) {
+  if (SRC_BF16) {
+    const uint2 w = *(const uint2*)((const unsigned short*)src + off);
+    v[0] = __builtin_bit_cast(float, w.x << 16);
+    v[1] = __builtin_bit_cast(float, w.x & 0xffff0000u);
+    v[2] = __builtin_bit_cast(float, w.y << 16);
+    v[3] = __builtin_bit_cast(float, w.y & 0xffff0000u);
+  } else {
+    const float4 a = *(const float4*)((const float*)src + off);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+  }
+}
+
+// T-planes: one block = one 128-row panel x 64 tokens (8 k-groups).  Phase 1 reads 4-token pieces (16 lanes cover
+// the 64 tokens of a row, a wavefront 4 rows) and drops the fp16 halves into an LDS image of the output
+// ([k-group][row][8], k-groups padded by one chunk against bank conflicts); phase 2 copies the image out linearly:
+// the block's output is one contiguous 16 KB run per plane.
+template <bool SRC_BF16>
+__global__ __launch_bounds__(256) void split_t_kernel(const void* src, long long lds, const int* idx, int rows, long long T,
+                                                      int relu, unsigned short* t_hi, unsigned short* t_lo, long long TGa) {
+  constexpr int GP = 128 * 16 + 16;   // bytes per k-group in LDS
+  __shared__ __attribute__((aligned(16))) unsigned char sh[8 * GP];
+  __shared__ __attribute__((aligned(16))) unsigned char sl[8 * GP];
+  const int t = threadIdx.x, piece = t & 15, rsub = t >> 4;
+  const int pan = blockIdx.y;
+  const long long tg0 = (long long)blockIdx.x * 8;
+  const long long tok = tg0 * 8 + piece * 4;
+  float v[8][4];
 #pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    const int row = rg * 8 + r;
+  for (int i = 0; i < 8; ++i) {
+    const int row = pan * 128 + rsub + 16 * i;
 #pragma unroll
-    for (int c = 0; c < 8; ++c) v[r][c] = 0.0f;
-    if (row < rows && tg < TG) {
+    for (int c = 0; c < 4; ++c) v[i][c] = 0.0f;
+    if (row < rows && tok < T) {
       const long long srow = idx ? (long long)idx[row] : (long long)row;
-      const long long t0 = tg * 8;
-      if (SRC_BF16) {
-        const uint4 w = *(const uint4*)((const unsigned short*)src + srow * lds + t0);
-        const unsigned int ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          v[r][2 * c] = __builtin_bit_cast(float, ww[c] << 16);
-          v[r][2 * c + 1] = __builtin_bit_cast(float, ww[c] & 0xffff0000u);
-        }
-      } else {
-        const float4 a = *(const float4*)((const float*)src + srow * lds + t0);
-        const float4 b = *(const float4*)((const float*)src + srow * lds + t0 + 4);
-        v[r][0] = a.x; v[r][1] = a.y; v[r][2] = a.z; v[r][3] = a.w;
-        v[r][4] = b.x; v[r][5] = b.y; v[r][6] = b.z; v[r][7] = b.w;
-      }
-#pragma unroll
-      for (int c = 0; c < 8; ++c)
-        if (t0 + c >= T) v[r][c] = 0.0f;
+      load4<SRC_BF16>(src, srow * lds + tok, v[i]);
     }
   }
-  if (t_hi && tg < TGa) {  // chunk (k-group = tg, row): the 8 rows of this thread are 8 consecutive chunks
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int rr = rsub + 16 * i;
+    unsigned short h[4], l[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float x = (tok + c < T) ? v[i][c] : 0.0f;
+      if (relu) x = __builtin_fmaxf(x, 0.0f);
+      sp_split_half(x, h[c], l[c]);
+    }
+    const int o = (piece >> 1) * GP + rr * 16 + (piece & 1) * 8;
+    *(uint2*)(sh + o) = make_uint2(sp_pack2(h[0], h[1]), sp_pack2(h[2], h[3]));
+    if (t_lo) *(uint2*)(sl + o) = make_uint2(sp_pack2(l[0], l[1]), sp_pack2(l[2], l[3]));
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int c = t + 256 * j, g = c >> 7, rr = c & 127;
+    if (tg0 + g >= TGa) continue;
+    const long long o = (((long long)pan * TGa + tg0 + g) * 128 + rr) * 8;
+    *(uint4*)(t_hi + o) = *(const uint4*)(sh + g * GP + rr * 16);
+    if (t_lo) *(uint4*)(t_lo + o) = *(const uint4*)(sl + g * GP + rr * 16);
+  }
+}
+
+// C-planes: thread = token, a chunk is that token's 8 consecutive channels; one block covers 256 tokens x 32
+// channels (4 k-groups).  Every load of a row is 1 KB contiguous per wavefront, every store 1 KB contiguous.
+template <bool SRC_BF16>
+__global__ __launch_bounds__(256) void split_c_kernel(const void* src, long long lds, const int* idx, int rows, long long T,
+                                                      int relu, unsigned short* c_hi, unsigned short* c_lo, int KGa) {
+  const long long tok = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int rg0 = blockIdx.y * 4;
+  if (tok >= (((T + 127) >> 7) << 7)) return;   // past the last token panel
+  float v[4][8];
+#pragma unroll
+  for (int g = 0; g < 4; ++g)
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
-      const int row = rg * 8 + r;
-      unsigned short h[8], l[8];
-#pragma unroll
-      for (int c = 0; c < 8; ++c) sp_split_half(relu_t ? __builtin_fmaxf(v[r][c], 0.0f) : v[r][c], h[c], l[c]);
-      const long long o = ((((long long)(row >> 7)) * TGa + tg) * 128 + (row & 127)) * 8;
-      *(uint4*)(t_hi + o) = make_uint4(sp_pack2(h[0], h[1]), sp_pack2(h[2], h[3]), sp_pack2(h[4], h[5]), sp_pack2(h[6], h[7]));
-      if (t_lo) *(uint4*)(t_lo + o) = make_uint4(sp_pack2(l[0], l[1]), sp_pack2(l[2], l[3]), sp_pack2(l[4], l[5]), sp_pack2(l[6], l[7]));
+      const int row = (rg0 + g) * 8 + r;
+      float x = 0.0f;
+      if (row < rows && tok < T) {
+        const long long srow = idx ? (long long)idx[row] : (long long)row;
+        if (SRC_BF16) x = __builtin_bit_cast(float, (unsigned int)((const unsigned short*)src)[srow * lds + tok] << 16);
+        else x = ((const float*)src)[srow * lds + tok];
+      }
+      v[g][r] = relu ? __builtin_fmaxf(x, 0.0f) : x;
     }
-  }
-  if (c_hi && rg < KGa) {  // chunk (k-group = rg, token): the 8 tokens of this thread are 8 consecutive chunks
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      const long long tok = tg * 8 + c;
-      unsigned short h[8], l[8];
+  for (int g = 0; g < 4; ++g) {
+    if (rg0 + g >= KGa) continue;
+    unsigned short h[8], l[8];
 #pragma unroll
-      for (int r = 0; r < 8; ++r) sp_split_half(relu_c ? __builtin_fmaxf(v[r][c], 0.0f) : v[r][c], h[r], l[r]);
-      const long long o = (((tok >> 7) * KGa + rg) * 128 + (tok & 127)) * 8;
-      *(uint4*)(c_hi + o) = make_uint4(sp_pack2(h[0], h[1]), sp_pack2(h[2], h[3]), sp_pack2(h[4], h[5]), sp_pack2(h[6], h[7]));
-      if (c_lo) *(uint4*)(c_lo + o) = make_uint4(sp_pack2(l[0], l[1]), sp_pack2(l[2], l[3]), sp_pack2(l[4], l[5]), sp_pack2(l[6], l[7]));
-    }
+    for (int r = 0; r < 8; ++r) sp_split_half(v[g][r], h[r], l[r]);
+    const long long o = (((tok >> 7) * KGa + rg0 + g) * 128 + (tok & 127)) * 8;
+    *(uint4*)(c_hi + o) = make_uint4(sp_pack2(h[0], h[1]), sp_pack2(h[2], h[3]), sp_pack2(h[4], h[5]), sp_pack2(h[6], h[7]));
+    if (c_lo) *(uint4*)(c_lo + o) = make_uint4(sp_pack2(l[0], l[1]), sp_pack2(l[2], l[3]), sp_pack2(l[4], l[5]), sp_pack2(l[6], l[7]));
   }
 }
 
@@ -93,18 +126,28 @@ strp_status split_act(strp_ctx* ctx, const void* src, int src_dtype, long long l
                       int relu_t, int relu_c, unsigned short* t_hi, unsigned short* t_lo, unsigned short* c_hi,
                       unsigned short* c_lo) {
   if (rows <= 0 || T <= 0) return fail(ctx, STRP_EINVAL, "split_act: empty");
-  if (lds % 8) return fail(ctx, STRP_EINVAL, "split_act: source pitch must be a multiple of 8");
-  const long long TGpad = ((T + 127) >> 7) << 4;
-  const int rgroups = t_hi ? (int)(((rows + 127) / 128) * 16) : (int)plane_kg(rows);
-  dim3 grid((unsigned)((TGpad + 255) / 256), (unsigned)rgroups);
+  if (lds % 8 || lds < T) return fail(ctx, STRP_EINVAL, "split_act: source pitch must be a multiple of 8 and at least T");
   const double es = src_dtype == STRP_BF16 ? 2.0 : 4.0;
   const double wb = (t_hi ? 2.0 : 0.0) + (t_lo ? 2.0 : 0.0) + (c_hi ? 2.0 : 0.0) + (c_lo ? 2.0 : 0.0);
-  ProfScope ps(ctx, "split_act", 0.0, (es + wb) * (double)rows * (double)T);
-  if (src_dtype == STRP_BF16)
-    hipLaunchKernelGGL((split_act_kernel<true>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, relu_c, t_hi, t_lo, c_hi, c_lo);
-  else
-    hipLaunchKernelGGL((split_act_kernel<false>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, relu_c, t_hi, t_lo, c_hi, c_lo);
-  STRP_HIP(ctx, hipGetLastError());
+  ProfScope ps(ctx, "split_act", 0.0, (es * ((t_hi ? 1.0 : 0.0) + (c_hi ? 1.0 : 0.0)) + wb) * (double)rows * (double)T);
+  if (t_hi) {
+    const long long TGa = plane_kg(T);
+    dim3 grid((unsigned)((TGa + 7) / 8), (unsigned)((rows + 127) / 128));
+    if (src_dtype == STRP_BF16)
+      hipLaunchKernelGGL((split_t_kernel<true>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, t_hi, t_lo, TGa);
+    else
+      hipLaunchKernelGGL((split_t_kernel<false>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, t_hi, t_lo, TGa);
+    STRP_HIP(ctx, hipGetLastError());
+  }
+  if (c_hi) {
+    const int KGa = (int)plane_kg(rows);
+    dim3 grid((unsigned)(((T + 127) / 128 * 128 + 255) / 256), (unsigned)((KGa + 3) / 4));
+    if (src_dtype == STRP_BF16)
+      hipLaunchKernelGGL((split_c_kernel<true>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_c, c_hi, c_lo, KGa);
+    else
+      hipLaunchKernelGGL((split_c_kernel<false>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_c, c_hi, c_lo, KGa);
+    STRP_HIP(ctx, hipGetLastError());
+  }
   return STRP_OK;
 }
 
