@@ -1,0 +1,181 @@
+"""Full-size check: the OPT-6.7B-shaped module (d=4096, f=16384, T=262144, keep k=4915), run exactly as
+bench.py runs it (module init, then one call of strp_admm_step with every stage, WANDA, re-select).
+
+The oracle cannot run this size whole, so every stage is checked on sampled outputs that the oracle's
+own functions (or its definitions) can produce one by one, teacher-forced from the state the GPU holds:
+token columns for the token-parallel products, weight rows for the refits.  Token sums of length T that a
+sampled output needs (a Gram matrix, a right-hand-side row) are accumulated in fp64 by torch on the
+device - harness arithmetic, not the library - and the small dense solve is the oracle's (numpy).
+Tolerances are those of the medium-size parity tests.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import strp_oracle as orc
+from paper_2510_03246_amd import inputs, strp
+
+pytestmark = pytest.mark.gpu
+
+TOL_F = 2e-3
+TOL_J = 1e-3
+ALPHA = BETA = 1.0
+DELTA = 0.01
+
+
+def rel_fro(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def f64_nt(P, Q, T, chunk=16384):
+    """sum_t P[:, t] Q[:, t]^T over the first T columns, accumulated in fp64 on the device."""
+    out = torch.zeros((P.shape[0], Q.shape[0]), dtype=torch.float64, device=P.device)
+    for t0 in range(0, T, chunk):
+        t1 = min(T, t0 + chunk)
+        out += P[:, t0:t1].double() @ Q[:, t0:t1].double().T
+    return out
+
+
+@pytest.fixture(scope="module")
+def run():
+    free, _ = torch.cuda.mem_get_info()
+    if free < 140e9:
+        pytest.skip("needs about 140 GB of free device memory")
+    cfg = inputs.CONFIGS["opt6.7b"]
+    k = cfg.f - int(round(cfg.rbar * cfg.f))
+    m = inputs.make_ffn_module(cfg, 0, 0, "cuda")
+    ctx = strp.Context(0)
+    mod = strp.FFNModule(ctx, m["W1hat"], m["W2hat"], m["X"], cfg.T, k_max=k)
+    params = strp.Params(ALPHA, BETA, DELTA, strp.WANDA, 1, k, 0)
+    mod.init(params)
+    torch.cuda.synchronize()
+    assert ctx.poll() == strp.OK
+    rng = np.random.default_rng(0)
+    cols = np.sort(rng.choice(cfg.T, size=4, replace=False))
+    cols[-1] = cfg.T - 1                                   # the ragged end of the last tile
+    init = {n: getattr(mod, n)[:, cols].double().cpu().numpy() for n in ("Z0", "Z", "A", "Y")}
+    lam = (float(mod.scalars[0].item()), float(mod.scalars[1].item()))
+    rep = mod.step(params)
+    torch.cuda.synchronize()
+    assert rep.status == strp.OK
+    yield dict(cfg=cfg, k=k, m=m, mod=mod, cols=cols, init=init, lam=lam, rep=rep)
+    ctx.close()
+
+
+def test_init_columns(run):
+    """Z0 = W1hat X, A0 = ReLU(Z0), Y = W2hat A0 on sampled token columns; the ridge constants."""
+    m, cols, init, cfg = run["m"], run["cols"], run["init"], run["cfg"]
+    W1 = m["W1hat"].double().cpu().numpy()
+    W2 = m["W2hat"].double().cpu().numpy()
+    Xc = m["X"][:, cols].double().cpu().numpy()
+    st = orc.module_init(W1, W2, Xc)                        # per-column quantities do not depend on the other tokens
+    assert rel_fro(init["Z0"], st.Z0) < 1e-5
+    assert rel_fro(init["Z"], st.Z0) < 1e-5
+    assert rel_fro(init["A"], st.A0) < 1e-5
+    assert rel_fro(init["Y"], st.Y) < 1e-5
+    mod = run["mod"]
+    sumsq = 0.0
+    for r0 in range(0, cfg.f, 1024):
+        sumsq += float((torch.relu(mod.Z0[r0:r0 + 1024, :cfg.T]).double() ** 2).sum().item())
+    assert abs(run["lam"][1] - DELTA * sumsq / cfg.f) <= 1e-6 * run["lam"][1]
+    trH = float((m["X"][:, :cfg.T].double() ** 2).sum().item())
+    assert abs(run["lam"][0] - DELTA * trH / cfg.d) <= 1e-6 * run["lam"][0]
+
+
+def test_scores_and_mask(run):
+    """WANDA scores of sampled units from their activation rows; the mask is the oracle's top-k of the scores."""
+    mod, cfg, k, m = run["mod"], run["cfg"], run["k"], run["m"]
+    rng = np.random.default_rng(1)
+    units = rng.choice(cfg.f, size=16, replace=False)
+    A0 = np.maximum(mod.Z0[units, :cfg.T].double().cpu().numpy(), 0.0)
+    n2 = (m["W2hat"][:, units].double().cpu().numpy() ** 2).sum(axis=0)
+    ref = orc.unit_scores(np.einsum("jt,jt->j", A0, A0), n2, 0, 0, 0, orc.WANDA)
+    score = mod.score.cpu().numpy()
+    assert np.allclose(score[units], ref, rtol=1e-6, atol=0)
+    mask_o, idx_o, tau_o = orc.select_topk(score, k)
+    assert np.array_equal(mod.mask.cpu().numpy(), mask_o)
+    assert np.array_equal(mod.idx[:k].cpu().numpy().astype(np.int64), idx_o)
+    assert run["rep"].s == k and float(run["rep"].tau) == np.float32(tau_o)
+
+
+def test_refits_sampled_rows(run):
+    """Rows of the refitted weights against the ridge normal equations solved by the oracle's solver."""
+    mod, cfg, k, m, (lam1, lam2) = run["mod"], run["cfg"], run["k"], run["m"], run["lam"]
+    T = cfg.T
+    idx = mod.idx[:k].long()
+    keep = mod.mask.bool()
+    assert not bool(mod.W2[:, ~keep].any()) and not bool(mod.W1[~keep, :].any())   # pruned units are exactly zero
+    # the refits of the first iteration see A = ReLU(Z0), Z = Z0
+    AS = torch.relu(mod.Z0[idx, :T])
+    G = f64_nt(AS, AS, T).cpu().numpy()
+    rows = torch.tensor([0, 1357, 4095], device="cuda")
+    R2 = f64_nt(mod.Y[rows, :T], AS, T).cpu().numpy()
+    ref2 = np.linalg.solve(G + lam2 * np.eye(k), R2.T).T
+    got2 = mod.W2[rows][:, idx].cpu().numpy()
+    assert rel_fro(got2, ref2) < TOL_F / 4
+    del AS
+    X = m["X"]
+    H = f64_nt(X, X, T).cpu().numpy()
+    units = idx[torch.tensor([0, k // 2, k - 1], device="cuda")]
+    R1 = f64_nt(mod.Z0[units, :T], X, T).cpu().numpy()
+    ref1 = np.linalg.solve(H + lam1 * np.eye(cfg.d), R1.T).T
+    got1 = mod.W1[units].cpu().numpy()
+    assert rel_fro(got1, ref1) < TOL_F / 4
+
+
+def test_a_and_z_updates_sampled_columns(run):
+    """The a-update and z-update on sampled token columns, teacher-forced with the weights the GPU refitted."""
+    mod, cfg, k, m, cols, init = run["mod"], run["cfg"], run["k"], run["m"], run["cols"], run["init"]
+    idx = mod.idx[:k].long().cpu().numpy()
+    W2S = mod.W2[:, idx].double().cpu().numpy()
+    # pruned columns of W2 are zero (checked above), so the f x f system of the a-update decouples: the oracle's
+    # function on the kept block, and ReLU(Z) on the other rows
+    A_ref = orc.a_update(W2S, init["Y"], init["Z0"][idx], ALPHA, BETA)
+    A_gpu = mod.A[:, cols].double().cpu().numpy()
+    assert rel_fro(A_gpu[idx], A_ref) < TOL_F
+    pruned = np.setdiff1d(np.arange(cfg.f), idx)
+    assert np.array_equal(A_gpu[pruned], np.maximum(init["Z0"][pruned], 0.0))
+    W1S = mod.W1[idx].double().cpu().numpy()
+    Xc = m["X"][:, cols].double().cpu().numpy()
+    Z_ref = orc.z_update(W1S, Xc, A_gpu[idx], ALPHA, BETA)
+    Z_gpu = mod.Z[:, cols].double().cpu().numpy()
+    assert rel_fro(Z_gpu[idx], Z_ref) < TOL_F
+    Zp_ref = orc.z_update(np.zeros((len(pruned), 1)), np.zeros((1, len(cols))), A_gpu[pruned], ALPHA, BETA)
+    assert np.allclose(Z_gpu[pruned], Zp_ref, rtol=1e-6, atol=0)
+    # whole pruned rows: ReLU of the previous z, and its half
+    rows = torch.from_numpy(pruned[[0, len(pruned) // 2, -1]]).cuda()
+    a_rows = torch.relu(mod.Z0[rows, :cfg.T])
+    assert torch.equal(mod.A[rows, :cfg.T], a_rows)
+    assert torch.allclose(mod.Z[rows, :cfg.T], a_rows * (BETA / (ALPHA + BETA)), rtol=1e-6, atol=0)
+
+
+def test_objective(run):
+    """The reported objective against its definition evaluated in fp64 on the state the GPU holds."""
+    mod, cfg, k, m, rep, (lam1, lam2) = run["mod"], run["cfg"], run["k"], run["m"], run["rep"], run["lam"]
+    T = cfg.T
+    idx = mod.idx[:k].long()
+    W2S = mod.W2[:, idx].double()
+    W1S = mod.W1[idx].double()
+    keep = mod.mask.bool()
+    t1 = t2 = t3 = 0.0
+    chunk = 8192
+    for t0 in range(0, T, chunk):
+        t1_ = min(T, t0 + chunk)
+        A = mod.A[:, t0:t1_].double()
+        Z = mod.Z[:, t0:t1_].double()
+        t1 += float(((mod.Y[:, t0:t1_].double() - W2S @ A[idx]) ** 2).sum().item())
+        t2 += float(((A - torch.relu(Z)) ** 2).sum().item())
+        Z1 = torch.zeros_like(Z)
+        Z1[idx] = W1S @ m["X"][:, t0:t1_].double()
+        t3 += float(((Z - Z1) ** 2).sum().item())
+        del A, Z, Z1
+    terms = np.array([ALPHA * t1, BETA * t2, ALPHA * t3,
+                      ALPHA * lam2 * float((mod.W2.double() ** 2).sum().item()),
+                      ALPHA * lam1 * float((mod.W1.double() ** 2).sum().item())]) / T
+    got = np.array(list(rep.terms))
+    assert np.all(np.abs(got - terms) <= 2 * TOL_J * np.maximum(terms, 1e-12)), (got, terms)
+    assert abs(rep.J_ridge - terms.sum()) <= TOL_J * terms.sum()
+    assert abs(rep.J - terms[:3].sum()) <= TOL_J * terms[:3].sum()
+    assert keep.sum().item() == k
