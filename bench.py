@@ -19,6 +19,11 @@ if ROOT not in sys.path:
 PEAK_F16_TFLOPS = 2500.0   # MI355X dense fp16/bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
+# HBM-side bytes per launch (GB, averaged over the launches of the class in one iteration) from the two
+# rocprofv3 --pmc runs summarised under profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 after the copy-kernel
+# calibration).  Hardware counters cannot be read inside this process; None for classes not measured.
+TRAFFIC_GB = {}
+
 
 def cpu_baseline(cfg_name: str, sample_tokens: int):
     """The oracle as it stands, timed on the host cores on a bounded token sample of the same module."""
@@ -103,13 +108,22 @@ def main():
     is_gemm = dom_name.startswith("gemm")
     avg_ms = dom["ms"] / dom["launches"]
     if is_gemm:
+        # class name gemm_h<p>x<q>_<epilogue>: p, q = fp16 planes per operand; a p x q product issues
+        # p*q - (1 if p == q == 2) MFMA passes per algorithmic multiply-add (hi*hi + hi*lo + lo*hi)
+        npp, npq = int(dom_name[6]), int(dom_name[8])
+        passes = npp * npq - (1 if npp * npq == 4 else 0)
         achieved = dom["flops"] / dom["launches"] / (avg_ms * 1e-3) / 1e12
         roof = dict(bound="mfma", kernel=dom_name, achieved=achieved, peak=PEAK_F16_TFLOPS, unit="TFLOP/s",
-                    frac=achieved / PEAK_F16_TFLOPS, traffic=None, avg_ms=avg_ms, launches_per_step=dom["launches"] / args.steps)
+                    frac=achieved / PEAK_F16_TFLOPS, traffic=TRAFFIC_GB.get((args.workload, dom_name)),
+                    traffic_unit="GB per launch (FETCH_SIZE + WRITE_SIZE, copy-calibrated; profiles/)",
+                    algorithmic_gb=dom["bytes"] / dom["launches"] / 1e9, avg_ms=avg_ms,
+                    launches_per_step=dom["launches"] / args.steps, mfma_passes=passes,
+                    executed=achieved * passes, executed_frac=achieved * passes / PEAK_F16_TFLOPS)
     else:
         achieved = dom["bytes"] / dom["launches"] / (avg_ms * 1e-3) / 1e9
         roof = dict(bound="hbm", kernel=dom_name, achieved=achieved, peak=PEAK_HBM_GBS, unit="GB/s",
-                    frac=achieved / PEAK_HBM_GBS, traffic=None, avg_ms=avg_ms, launches_per_step=dom["launches"] / args.steps)
+                    frac=achieved / PEAK_HBM_GBS, traffic=TRAFFIC_GB.get((args.workload, dom_name)),
+                    avg_ms=avg_ms, launches_per_step=dom["launches"] / args.steps)
     kernels = {n: dict(ms_per_step=v["ms"] / args.steps, launches=v["launches"] // args.steps,
                        tflops=v["flops"] / max(v["ms"], 1e-9) / 1e9, gbs=v["bytes"] / max(v["ms"], 1e-9) / 1e6)
                for n, v in sorted(prof.items(), key=lambda kv: -kv[1]["ms"])}

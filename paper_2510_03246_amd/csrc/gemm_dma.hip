@@ -51,6 +51,7 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma_kernel(const GemmP p) {
   constexpr int WTM = 4, WTN = NW == 8 ? 2 : 4;        // 32x32 MFMA tiles per wavefront
   __shared__ __attribute__((aligned(1024))) unsigned char smem[NSTAGE * STAGE_BYTES];
   __shared__ double sred[NW][2];
+  __shared__ int srow[dma::ROWS];   // gathered state row of each output row (AUPD / ZUPD)
 
   // ---- which tile, which K range ---------------------------------------------------------
   int tm, tn, split;
@@ -63,6 +64,9 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma_kernel(const GemmP p) {
   const long long g_last = ((k1 + 7) >> 3) - 1;       // last k-group holding data; its pair partner is zero padding
 
   const int tid = threadIdx.x, lane = tid & 63;
+  // fetched now, parked in LDS after the main loop: the epilogue never waits for an index load
+  int my_row = 0;
+  if (p.oidx && tid < ROWS && m0 + tid < p.M) my_row = p.oidx[m0 + tid];
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = NW == 8 ? wave >> 2 : wave >> 1, wn = NW == 8 ? wave & 3 : wave & 1;
   constexpr int WROWS = 32 * WTM, WCOLS = 32 * WTN;
@@ -179,6 +183,7 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma_kernel(const GemmP p) {
     __builtin_amdgcn_sched_barrier(0);
   }
   wait_vmcnt<0>();           // nothing may still be writing LDS when the block ends or reuses it
+  if (tid < ROWS) srow[tid] = my_row;
   __syncthreads();
 
   // ---- epilogue -------------------------------------------------------------------------------
@@ -188,12 +193,12 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma_kernel(const GemmP p) {
   double red0 = 0.0, red1 = 0.0;
   const int mbase = m0 + wm * WROWS + 4 * (lane >> 5), nbase = n0 + wn * WCOLS + (lane & 31);
   switch (p.epi) {
-    case EPI_PARTIAL: epilogue<EPI_PARTIAL, WTM, WTN>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
-    case EPI_STORE: epilogue<EPI_STORE, WTM, WTN>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
-    case EPI_INITZ: epilogue<EPI_INITZ, WTM, WTN>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
-    case EPI_RESID: epilogue<EPI_RESID, WTM, WTN>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
-    case EPI_AUPD: epilogue<EPI_AUPD, WTM, WTN>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
-    default: epilogue<EPI_ZUPD, WTM, WTN>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
+    case EPI_PARTIAL: epilogue<EPI_PARTIAL, WTM, WTN>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    case EPI_STORE: epilogue<EPI_STORE, WTM, WTN>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    case EPI_INITZ: epilogue<EPI_INITZ, WTM, WTN>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    case EPI_RESID: epilogue<EPI_RESID, WTM, WTN>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    case EPI_AUPD: epilogue<EPI_AUPD, WTM, WTN>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    default: epilogue<EPI_ZUPD, WTM, WTN>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
   }
   if (p.red) {
     red0 = wave_sum(red0);

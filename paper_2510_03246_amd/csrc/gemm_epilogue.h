@@ -80,7 +80,7 @@ __device__ __forceinline__ bool decode_tile(const GemmP& p, int bid, int nblocks
 // per element: the compiler cannot prove that the state tensors do not overlap).
 template <int EPI>
 __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16, float unscale, int m_tile, int n, int split,
-                                              double& red0, double& red1) {
+                                              const int* rowmap, int m_blk, double& red0, double& red1) {
   const float ab = p.alpha + p.beta;
   const bool ncol = n < p.N;
   long long off[16];     // element offset of (row, n) in the tensor this epilogue reads / writes
@@ -92,7 +92,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
     const int m = m_tile + 8 * (e >> 2) + (e & 3);
     const bool ok = ncol && m < p.M;
     long long row = m;
-    if (GATHER) row = ok ? (long long)p.oidx[m] : 0;
+    if (GATHER) row = ok ? (long long)rowmap[m - m_blk] : 0;   // the block's slice of oidx, staged in LDS by the kernel
     if (EPI == EPI_PARTIAL) off[e] = ((long long)split * p.M + m) * p.N + n;
     else if (EPI == EPI_STORE) off[e] = (long long)m * p.ldo + n;
     else if (EPI == EPI_RESID) off[e] = (long long)m * p.ldy + n;
@@ -177,19 +177,20 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
 template <int EPI, int WTM, int WTN, int IJ>
 struct EpilogueWalk {
   static __device__ __forceinline__ void run(const GemmP& p, floatx16 (&acc)[WTM][WTN], float unscale, int mbase, int nbase, int split,
-                                             double& red0, double& red1) {
-    epilogue_tile<EPI>(p, acc[IJ / WTN][IJ % WTN], unscale, mbase + (IJ / WTN) * 32, nbase + (IJ % WTN) * 32, split, red0, red1);
-    EpilogueWalk<EPI, WTM, WTN, IJ + 1>::run(p, acc, unscale, mbase, nbase, split, red0, red1);
+                                             const int* rowmap, int m_blk, double& red0, double& red1) {
+    epilogue_tile<EPI>(p, acc[IJ / WTN][IJ % WTN], unscale, mbase + (IJ / WTN) * 32, nbase + (IJ % WTN) * 32, split, rowmap, m_blk,
+                       red0, red1);
+    EpilogueWalk<EPI, WTM, WTN, IJ + 1>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1);
   }
 };
 template <int EPI, int WTM, int WTN>
 struct EpilogueWalk<EPI, WTM, WTN, WTM * WTN> {
-  static __device__ __forceinline__ void run(const GemmP&, floatx16 (&)[WTM][WTN], float, int, int, int, double&, double&) {}
+  static __device__ __forceinline__ void run(const GemmP&, floatx16 (&)[WTM][WTN], float, int, int, int, const int*, int, double&, double&) {}
 };
 template <int EPI, int WTM, int WTN>
 __device__ __forceinline__ void epilogue(const GemmP& p, floatx16 (&acc)[WTM][WTN], float unscale, int mbase, int nbase, int split,
-                                         double& red0, double& red1) {
-  EpilogueWalk<EPI, WTM, WTN, 0>::run(p, acc, unscale, mbase, nbase, split, red0, red1);
+                                         const int* rowmap, int m_blk, double& red0, double& red1) {
+  EpilogueWalk<EPI, WTM, WTN, 0>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1);
 }
 
 }  // namespace strp

@@ -96,6 +96,7 @@ __global__ __launch_bounds__(256, WT == 4 ? 1 : 2) void gemm_kernel(const GemmP 
   __shared__ __attribute__((aligned(16))) unsigned short sP[NPP][ROWS * BK];
   __shared__ __attribute__((aligned(16))) unsigned short sQ[NPQ][ROWS * BK];
   __shared__ double sred[4][2];
+  __shared__ int srow[ROWS];   // gathered state row of each output row (AUPD / ZUPD)
 
   // ---- which tile, which K range ---------------------------------------------------------
   int tm, tn, split;
@@ -106,6 +107,7 @@ __global__ __launch_bounds__(256, WT == 4 ? 1 : 2) void gemm_kernel(const GemmP 
   const long long g_end = (k1 + 7) >> 3;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid < ROWS) srow[tid] = (p.oidx && m0 + tid < p.M) ? p.oidx[m0 + tid] : 0;   // visible after the loop's barriers
   const int wm = wave >> 1, wn = wave & 1;
   constexpr int WROWS = 32 * WT;   // rows (and columns) of the output owned by one wavefront
 
@@ -192,12 +194,12 @@ __global__ __launch_bounds__(256, WT == 4 ? 1 : 2) void gemm_kernel(const GemmP 
   double red0 = 0.0, red1 = 0.0;
   const int mbase = m0 + wm * WROWS + 4 * (lane >> 5), nbase = n0 + wn * WROWS + (lane & 31);
   switch (p.epi) {
-    case EPI_PARTIAL: epilogue<EPI_PARTIAL, WT, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
-    case EPI_STORE: epilogue<EPI_STORE, WT, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
-    case EPI_INITZ: epilogue<EPI_INITZ, WT, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
-    case EPI_RESID: epilogue<EPI_RESID, WT, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
-    case EPI_AUPD: epilogue<EPI_AUPD, WT, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
-    default: epilogue<EPI_ZUPD, WT, WT>(p, acc, unscale, mbase, nbase, split, red0, red1); break;
+    case EPI_PARTIAL: epilogue<EPI_PARTIAL, WT, WT>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    case EPI_STORE: epilogue<EPI_STORE, WT, WT>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    case EPI_INITZ: epilogue<EPI_INITZ, WT, WT>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    case EPI_RESID: epilogue<EPI_RESID, WT, WT>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    case EPI_AUPD: epilogue<EPI_AUPD, WT, WT>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    default: epilogue<EPI_ZUPD, WT, WT>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
   }
   if (p.red) {
     red0 = wave_sum(red0);
