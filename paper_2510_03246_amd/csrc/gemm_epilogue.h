@@ -75,39 +75,49 @@ __device__ __forceinline__ bool decode_tile(const GemmP& p, int bid, int nblocks
 
 // Epilogue of one 32x32 accumulator tile (passed by value so the accumulators never need an address).
 // Register e of lane l is output row m_tile + 8 (e / 4) + (e % 4), column n  (m_tile, n include the lane's share).
-// Three phases per tile - row offsets, then every load the tile needs, then arithmetic and stores - so that the
-// loads of a tile are in flight together (interleaving them with the stores would serialise one memory round trip
-// per element: the compiler cannot prove that the state tensors do not overlap).
-template <int EPI>
+//
+// Loads are branch-free and come first: rows and the column are clamped into range so that every address is
+// valid, and the 16 loads of the tile are issued back to back.  (A predicated load costs a wait per element, and
+// loads interleaved with the stores would serialise one memory round trip per element, since the compiler cannot
+// prove that the state tensors do not overlap.)  Only the stores are predicated.  Offsets are recomputed where
+// they are used rather than kept: 16 64-bit offsets next to 128 accumulators would spill.
+// ZWRITE (EPI_ZUPD only): true = apply the z rule and store Z, false = only accumulate the objective sums.
+template <int EPI, bool ZWRITE, bool EDGE>
 __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16, float unscale, int m_tile, int n, int split,
                                               const int* rowmap, int m_blk, double& red0, double& red1) {
-  const float ab = p.alpha + p.beta;
-  const bool ncol = n < p.N;
-  long long off[16];     // element offset of (row, n) in the tensor this epilogue reads / writes
-  float in0[16];         // RESID: Y, AUPD: Z, ZUPD: A
-  float in1[16];         // ZUPD without write-back: Z
   constexpr bool GATHER = (EPI == EPI_AUPD || EPI == EPI_ZUPD);
+  const bool ncol = !EDGE || n < p.N;
+  const int nc = ncol ? n : p.N - 1;
+  int rowid[16];         // GATHER: state row of each element's output row (0 for rows past M)
+  if (GATHER) {
 #pragma unroll
-  for (int e = 0; e < 16; ++e) {
-    const int m = m_tile + 8 * (e >> 2) + (e & 3);
-    const bool ok = ncol && m < p.M;
-    long long row = m;
-    if (GATHER) row = ok ? (long long)rowmap[m - m_blk] : 0;   // the block's slice of oidx, staged in LDS by the kernel
-    if (EPI == EPI_PARTIAL) off[e] = ((long long)split * p.M + m) * p.N + n;
-    else if (EPI == EPI_STORE) off[e] = (long long)m * p.ldo + n;
-    else if (EPI == EPI_RESID) off[e] = (long long)m * p.ldy + n;
-    else off[e] = row * p.lda + n;
+    for (int e = 0; e < 16; ++e) rowid[e] = rowmap[m_tile + 8 * (e >> 2) + (e & 3) - m_blk];   // slice of oidx staged in LDS
   }
+  // 32 x 32 -> 64-bit products (one instruction each): rows, leading dimensions and columns all fit 32 bits
+  auto offset = [&](int e) -> long long {
+    const int m = m_tile + 8 * (e >> 2) + (e & 3);
+    const unsigned mc = (unsigned)((!EDGE || m < p.M) ? m : p.M - 1);
+    unsigned long long o;
+    if (EPI == EPI_PARTIAL) o = (unsigned long long)((unsigned)split * (unsigned)p.M + mc) * (unsigned)p.N + (unsigned)nc;
+    else if (EPI == EPI_STORE) o = (unsigned long long)mc * (unsigned)p.ldo + (unsigned)nc;
+    else if (EPI == EPI_RESID) o = (unsigned long long)mc * (unsigned)p.ldy + (unsigned)nc;
+    else if (GATHER) o = (unsigned long long)(unsigned)rowid[e] * (unsigned)p.lda + (unsigned)nc;
+    else o = (unsigned long long)mc * (unsigned)p.lda + (unsigned)nc;
+    return (long long)o;
+  };
+  float in0[16];         // RESID: Y, AUPD: Z, ZUPD: A (ZWRITE) or A and, in in1, Z (!ZWRITE)
+  float in1[16];
   if (EPI == EPI_RESID || EPI == EPI_AUPD || EPI == EPI_ZUPD) {
     const float* src = EPI == EPI_RESID ? p.Yin : (EPI == EPI_AUPD ? p.Zs : p.As);
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      const int m = m_tile + 8 * (e >> 2) + (e & 3);
-      const bool ok = ncol && m < p.M;
-      in0[e] = ok ? src[off[e]] : 0.0f;
-      if (EPI == EPI_ZUPD) in1[e] = (ok && !p.write_out) ? p.Zs[off[e]] : 0.0f;
+      const long long o = offset(e);
+      in0[e] = src[o];
+      if (EPI == EPI_ZUPD && !ZWRITE) in1[e] = p.Zs[o];
     }
   }
+  const float inv_ab = 1.0f / (p.alpha + p.beta);
+  float s0 = 0.0f, s1 = 0.0f;   // this tile's share of the reduction sums (16 terms in fp32, then fp64)
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int mq = m_tile + 8 * q;  // rows mq .. mq+3
@@ -115,54 +125,56 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int e = 4 * q + r;
-      const int m = mq + r;
+      const bool ok = !EDGE || (ncol && (mq + r) < p.M);
       const float v = a16[e] * unscale;
       outv[r] = 0.0f;
-      if (m >= p.M || !ncol) continue;
       if (EPI == EPI_PARTIAL) {
-        p.out[off[e]] = v;
+        if (ok) p.out[offset(e)] = v;
       } else if (EPI == EPI_STORE) {
-        p.out[off[e]] = v;
-        outv[r] = v;
+        if (ok) p.out[offset(e)] = v;
+        outv[r] = ok ? v : 0.0f;
       } else if (EPI == EPI_INITZ) {
         const float a = __builtin_fmaxf(v, 0.0f);
-        p.Z0s[off[e]] = v;
-        p.Zs[off[e]] = v;
-        p.As[off[e]] = a;
-        outv[r] = a;
-        red0 += (double)a * (double)a;
+        if (ok) {
+          const long long o = offset(e);
+          p.Z0s[o] = v;
+          p.Zs[o] = v;
+          p.As[o] = a;
+        }
+        outv[r] = ok ? a : 0.0f;
+        s0 += ok ? a * a : 0.0f;
       } else if (EPI == EPI_RESID) {
-        const float rr = in0[e] - v;
+        const float rr = ok ? in0[e] - v : 0.0f;
         outv[r] = rr;
-        red0 += (double)rr * (double)rr;
+        s0 += rr * rr;
       } else if (EPI == EPI_AUPD) {
         const float a = __builtin_fmaxf(in0[e], 0.0f) + v;
-        p.As[off[e]] = a;
-        outv[r] = a;
+        if (ok) p.As[offset(e)] = a;
+        outv[r] = ok ? a : 0.0f;
       } else {  // EPI_ZUPD
         const float a = in0[e];
         const float z1 = v;
         float z;
-        if (p.write_out) {
-          const float z2 = (p.beta * a + p.alpha * z1) / ab;
+        if (ZWRITE) {
+          const float z2 = (p.beta * a + p.alpha * z1) * inv_ab;
           const float cm = __builtin_fminf(z1, 0.0f);
           const float costm = p.beta * a * a + p.alpha * (cm - z1) * (cm - z1);
           const float cp = __builtin_fmaxf(z2, 0.0f);
           const float costp = p.beta * (a - cp) * (a - cp) + p.alpha * (cp - z1) * (cp - z1);
           z = costm < costp ? cm : cp;
-          p.Zs[off[e]] = z;
+          if (ok) p.Zs[offset(e)] = z;
         } else {
           z = in1[e];
         }
-        const float ra = a - __builtin_fmaxf(z, 0.0f);
-        const float rz = z - z1;
-        red0 += (double)ra * (double)ra;
-        red1 += (double)rz * (double)rz;
+        const float ra = ok ? a - __builtin_fmaxf(z, 0.0f) : 0.0f;
+        const float rz = ok ? z - z1 : 0.0f;
+        s0 += ra * ra;
+        s1 += rz * rz;
       }
     }
     // optional operand-plane copy of the produced tile (its rows are the contraction axis of the consumer):
     // this lane's four rows are half of one 16-byte chunk; rows past M inside the last chunk are written as zeros
-    if ((EPI == EPI_STORE || EPI == EPI_INITZ || EPI == EPI_RESID || EPI == EPI_AUPD) && p.k8_hi && ncol && (mq & ~7) < p.M) {
+    if ((EPI == EPI_STORE || EPI == EPI_INITZ || EPI == EPI_RESID || EPI == EPI_AUPD) && p.k8_hi && ncol && (!EDGE || (mq & ~7) < p.M)) {
       unsigned short h[4], l[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) split_half(outv[r], h[r], l[r]);
@@ -170,27 +182,39 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
       *(uint2*)(p.k8_hi + o) = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
       if (p.k8_lo) *(uint2*)(p.k8_lo + o) = make_uint2(pack2(l[0], l[1]), pack2(l[2], l[3]));
     }
+    __builtin_amdgcn_sched_barrier(0);   // bounds the live temporaries to one group of four rows
   }
+  red0 += (double)s0;
+  red1 += (double)s1;
 }
 
 // Compile-time walk over the WTM x WTN tiles of a wavefront (constant indices keep the accumulators in registers).
-template <int EPI, int WTM, int WTN, int IJ>
+// The scheduling barrier keeps the compiler from hoisting the next tile's loads and offsets over this tile.
+template <int EPI, bool ZWRITE, int WTM, int WTN, int IJ>
 struct EpilogueWalk {
   static __device__ __forceinline__ void run(const GemmP& p, floatx16 (&acc)[WTM][WTN], float unscale, int mbase, int nbase, int split,
                                              const int* rowmap, int m_blk, double& red0, double& red1) {
-    epilogue_tile<EPI>(p, acc[IJ / WTN][IJ % WTN], unscale, mbase + (IJ / WTN) * 32, nbase + (IJ % WTN) * 32, split, rowmap, m_blk,
-                       red0, red1);
-    EpilogueWalk<EPI, WTM, WTN, IJ + 1>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1);
+    // interior tiles (the common case, decided per wavefront) skip every bounds predicate
+    const int mt = mbase + (IJ / WTN) * 32, nt = nbase + (IJ % WTN) * 32;
+    const bool edge = __builtin_amdgcn_readfirstlane(mt) + 32 > p.M || __builtin_amdgcn_readfirstlane(nt) + 32 > p.N;
+    if (edge) epilogue_tile<EPI, ZWRITE, true>(p, acc[IJ / WTN][IJ % WTN], unscale, mt, nt, split, rowmap, m_blk, red0, red1);
+    else epilogue_tile<EPI, ZWRITE, false>(p, acc[IJ / WTN][IJ % WTN], unscale, mt, nt, split, rowmap, m_blk, red0, red1);
+    __builtin_amdgcn_sched_barrier(0);
+    EpilogueWalk<EPI, ZWRITE, WTM, WTN, IJ + 1>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1);
   }
 };
-template <int EPI, int WTM, int WTN>
-struct EpilogueWalk<EPI, WTM, WTN, WTM * WTN> {
-  static __device__ __forceinline__ void run(const GemmP&, floatx16 (&)[WTM][WTN], float, int, int, int, const int*, int, double&, double&) {}
+template <int EPI, bool ZWRITE, int WTM, int WTN>
+struct EpilogueWalk<EPI, ZWRITE, WTM, WTN, WTM * WTN> {
+  static __device__ __forceinline__ void run(const GemmP&, floatx16 (&)[WTM][WTN], float, int, int, int, const int*, int, double&,
+                                             double&) {}
 };
 template <int EPI, int WTM, int WTN>
 __device__ __forceinline__ void epilogue(const GemmP& p, floatx16 (&acc)[WTM][WTN], float unscale, int mbase, int nbase, int split,
                                          const int* rowmap, int m_blk, double& red0, double& red1) {
-  EpilogueWalk<EPI, WTM, WTN, 0>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1);
+  if (EPI == EPI_ZUPD && !p.write_out)
+    EpilogueWalk<EPI, false, WTM, WTN, 0>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1);
+  else
+    EpilogueWalk<EPI, true, WTM, WTN, 0>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1);
 }
 
 }  // namespace strp
