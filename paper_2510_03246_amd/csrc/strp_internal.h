@@ -18,6 +18,8 @@ struct strp_ctx {
   void* pinned;        // small pinned host buffer for report read-back
   char err[512];
   struct Profiler* prof;  // optional per-kernel event timing (host object)
+  hipStream_t aux;        // second stream (default priority) for work that is independent of what `stream` runs
+  hipEvent_t ev_fork, ev_join;
 };
 
 struct Profiler;
@@ -33,6 +35,19 @@ struct ProfScope {
   int rec;
   ProfScope(strp_ctx* c, const char* name, double flops, double bytes) : ctx(c), rec(prof_begin(c, name, flops, bytes)) {}
   ~ProfScope() { prof_end(ctx, rec); }
+};
+
+// ---- fork / join between the context's two streams -----------------------------------------------
+// fork: everything enqueued on ctx->stream so far happens before what follows on ctx->aux.
+// AuxScope: while alive, ctx->stream IS the aux stream, so every helper enqueues there.
+// join: everything enqueued on ctx->aux so far happens before what follows on ctx->stream.
+strp_status stream_fork(strp_ctx* ctx);
+strp_status stream_join(strp_ctx* ctx);
+struct AuxScope {
+  strp_ctx* ctx;
+  hipStream_t saved;
+  explicit AuxScope(strp_ctx* c) : ctx(c), saved(c->stream) { c->stream = c->aux; }
+  ~AuxScope() { ctx->stream = saved; }
 };
 
 // ---- error helpers -------------------------------------------------------------------
@@ -55,6 +70,7 @@ struct Arena {
   size_t off, cap;
   Arena() : base(nullptr), off(0), cap(0) {}
   explicit Arena(strp_ctx* ctx) : base(ctx->ws), off(256), cap(ctx->ws_bytes) {}
+  Arena(void* block, size_t bytes) : base((char*)block), off(0), cap(bytes) {}   // sub-arena over a block taken elsewhere
   void* take(size_t bytes) {
     size_t b = (bytes + 255) & ~size_t(255);
     if (!base || off + b > cap) return nullptr;
