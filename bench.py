@@ -45,6 +45,29 @@ def cpu_baseline(cfg_name: str, sample_tokens: int):
                        f"{sample_tokens} of the {inputs.CONFIGS[cfg_name].T} tokens: {dt:.1f} s")
 
 
+def select_stress(ctx, torch):
+    """Multi-block top-k (one threshold over a long score vector): algorithmic bytes 4n (scores) + n (mask) + 4k (indices)."""
+    res = {}
+    for name, n in (("2^26 scores", 1 << 26), ("48 x 28672 scores", 48 * 28672)):
+        g = torch.Generator(device="cuda").manual_seed(n)
+        score = torch.randn(n, generator=g, device="cuda") ** 2
+        k = int(0.3 * n)
+        ctx.strp_mask_topk(score, k)                      # warm-up (also sizes the workspace)
+        torch.cuda.synchronize()
+        ctx.profile_enable(True)
+        reps = 5
+        for _ in range(reps):
+            ctx.strp_mask_topk(score, k)
+        torch.cuda.synchronize()
+        prof = ctx.profile_read()
+        ctx.profile_enable(False)
+        ms = prof["topk"]["ms"] / reps
+        gb = (5.0 * n + 4.0 * k) / 1e9
+        res[name] = dict(n=n, k=k, ms=ms, achieved_gbs=gb / (ms * 1e-3), frac_hbm=gb / (ms * 1e-3) / PEAK_HBM_GBS)
+        del score
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -54,6 +77,9 @@ def main():
     ap.add_argument("--tokens", type=int, default=0, help="override T (0: the configuration's 128 x 2048)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--select-stress", action="store_true",
+                    help="also time the multi-block top-k on 2^26 synthetic scores and on the 48 x 28672 scores of the "
+                         "largest configuration (one global threshold); reported under \"select_stress\" in the same line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="before the timed region run one elementwise copy kernel that reads 1 GiB and writes 1 GiB, "
                          "as the known-size reference for scaling hardware byte counters")
@@ -138,6 +164,8 @@ def main():
         "roofline": roof,
         "kernels": kernels,
     }
+    if args.select_stress:
+        out["select_stress"] = select_stress(ctx, torch)
     if not args.no_cpu_baseline:
         del mod, m
         torch.cuda.empty_cache()

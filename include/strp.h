@@ -149,10 +149,16 @@ strp_status strp_score_alloc(strp_ctx* ctx, const strp_score_in* in, float* unit
  * Keeps exactly the k highest of the n unit scores; equal scores keep the lower index.
  *   mask[n] uint8 in {0,1};  idx[k*group] int32 ascending kept CHANNEL indices (unit*group + c);
  *   tau (optional) = lowest kept score.
- * Errors: STRP_EINVAL (k < 0, k > n, n <= 0, group <= 0, null pointers).
+ * One module's scores (n up to 65536) are selected by one block; a longer vector -- the scores of every layer
+ * at once for the single global threshold of Alg. 4 (K = floor(r n L) kept over all L n units) -- is selected
+ * by a multi-block path that needs strp_topk_workspace_bytes(n) bytes of the context's workspace (group must
+ * be 1 there).
+ * Errors: STRP_EINVAL (k < 0, k > n, n <= 0, group <= 0, null pointers), STRP_ENOMEM (workspace).
  */
 strp_status strp_mask_topk(strp_ctx* ctx, const float* score, int32_t n, int32_t k, int32_t group,
                            uint8_t* mask, int32_t* idx, float* tau);
+/* Workspace (bytes, device) that strp_mask_topk needs for n scores; 0 when one block handles them. */
+size_t strp_topk_workspace_bytes(int32_t n);
 
 /*
  * strp_refit -- closed-form ridge least-squares recovery of the surviving weights

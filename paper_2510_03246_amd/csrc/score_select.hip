@@ -435,14 +435,441 @@ __global__ __launch_bounds__(1024) void topk_kernel(const float* score, int n, i
   }
 }
 
-size_t topk_scratch_bytes(int n) { (void)n; return 0; }
+// ---------------------------------------------------------------------------------------------
+// top-k select over a long score vector (all layers' scores at once for a global threshold, or a stress
+// input): several blocks, two reads of the scores and one of the mask.
+//   level 0 (top 11 key bits: sign, exponent, 2 mantissa bits), over the scores
+//     hist    every block histograms its contiguous chunk (kept per block and summed)
+//     pick    one block picks the bucket that holds the k-th largest key; keys above it are kept, below dropped
+//     gather  every block re-reads its chunk, writes the mask of the decided keys and appends the keys of the
+//             bucket (a few per cent of n: the bucket is a 2^(1/4)-wide value range) to a candidate list, in
+//             index order (the per-block histograms give the offsets)
+//   level 1 (next 11 bits), over the candidates: the same three steps; what survives is ~n / 10^5 keys
+//   resolve   one block selects among those on the last 10 bits, ties to the lower index, completes the mask and
+//             scans the per-block kept counts
+//   compact   every block turns its part of the mask into ascending indices
+// A vector of equal scores degenerates to candidate lists of length n and a single-block resolve: correct, slow.
+// ---------------------------------------------------------------------------------------------
+namespace big {
+constexpr int BINS = 2048;          // 11 bits
+constexpr int THREADS = 512;
+constexpr int MAXBLOCKS = 1024;
+constexpr int L1BLOCKS = 256;
+struct State {
+  unsigned int bucket;      // chosen digit at this level
+  unsigned int krem;        // keys still to keep inside the bucket
+  unsigned int ncand;       // keys in the bucket
+  unsigned int pad;
+};
+}  // namespace big
+
+struct BigLevel {
+  unsigned int* bhist;      // [blocks][BINS]
+  unsigned int* ghist;      // [BINS]
+  big::State* state;        // this level's choice
+  unsigned int* coff;       // [blocks] offset of the block's candidates in the output list
+  unsigned int* cand_key;   // output list
+  int* cand_idx;
+  int blocks;
+};
+
+struct BigTopkPlan {
+  int blocks0;
+  long long chunk0;         // elements per block at level 0 (multiple of big::THREADS)
+  BigLevel lv[2];
+  unsigned int* gtcnt;      // [blocks0] keys above the level-0 bucket in the block's chunk
+  unsigned int* kept_cand;  // [blocks0] kept candidates per level-0 chunk (levels 1 and 2)
+  unsigned int* kpre;       // [blocks0] kept entries before the block's chunk
+  int vec;                  // scores 16-byte aligned and mask 8-byte aligned: vector accesses allowed
+};
+
+static void big_plan(long long n, int* blocks, long long* chunk) {
+  long long b = (n + 8 * big::THREADS - 1) / (8 * big::THREADS);
+  if (b > big::MAXBLOCKS) b = big::MAXBLOCKS;
+  if (b < 1) b = 1;
+  long long c = (n + b - 1) / b;
+  c = (c + big::THREADS - 1) / big::THREADS * big::THREADS;
+  *blocks = (int)((n + c - 1) / c);
+  *chunk = c;
+}
+
+size_t topk_scratch_bytes(int n) {
+  if (n <= 65536) return 0;
+  int blocks;
+  long long chunk;
+  big_plan(n, &blocks, &chunk);
+  auto al = [](size_t b) { return (b + 255) & ~size_t(255); };
+  return al((size_t)blocks * big::BINS * 4) + al((size_t)big::L1BLOCKS * big::BINS * 4) + 2 * al(big::BINS * 4) + 2 * al(sizeof(big::State)) +
+         al((size_t)blocks * 4) + al((size_t)big::L1BLOCKS * 4) + 3 * al((size_t)blocks * 4) + 4 * al((size_t)n * 4) + 256;
+}
+
+// chunk of block blk at level LEVEL: level 0 splits [0, n) by plan.chunk0; level 1 splits the candidate list, whose
+// length is a device value
+template <int LEVEL>
+__device__ __forceinline__ void level_range(const BigTopkPlan& pl, long long n, long long* beg, long long* end) {
+  if (LEVEL == 0) {
+    *beg = (long long)blockIdx.x * pl.chunk0;
+    *end = *beg + pl.chunk0 < n ? *beg + pl.chunk0 : n;
+  } else {
+    const long long m = pl.lv[0].state->ncand;
+    long long c = (m + gridDim.x - 1) / gridDim.x;
+    c = (c + big::THREADS - 1) / big::THREADS * big::THREADS;
+    *beg = (long long)blockIdx.x * c < m ? (long long)blockIdx.x * c : m;
+    *end = *beg + c < m ? *beg + c : m;
+  }
+}
+template <int LEVEL>
+__device__ __forceinline__ unsigned int level_key(const BigTopkPlan& pl, const float* score, long long i) {
+  return LEVEL == 0 ? score_key(score[i]) : pl.lv[0].cand_key[i];
+}
+template <int LEVEL>
+__device__ __forceinline__ unsigned int level_digit(unsigned int key) {
+  return LEVEL == 0 ? key >> 21 : (key >> 10) & 0x7ffu;
+}
+
+template <int LEVEL>
+__global__ __launch_bounds__(big::THREADS) void topk_hist_kernel(const float* score, long long n, BigTopkPlan pl) {
+  __shared__ unsigned int hist[big::BINS];
+  for (int i = threadIdx.x; i < big::BINS; i += big::THREADS) hist[i] = 0;
+  __syncthreads();
+  long long beg, end;
+  level_range<LEVEL>(pl, n, &beg, &end);
+  if (LEVEL == 0 && pl.vec) {   // beg is a multiple of 512: float4 loads stay aligned
+    const long long nv = (end - beg) >> 2;
+    const float4* s4 = (const float4*)(score + beg);
+    for (long long v = threadIdx.x; v < nv; v += big::THREADS) {
+      const float4 x = s4[v];
+      atomicAdd(&hist[score_key(x.x) >> 21], 1u);
+      atomicAdd(&hist[score_key(x.y) >> 21], 1u);
+      atomicAdd(&hist[score_key(x.z) >> 21], 1u);
+      atomicAdd(&hist[score_key(x.w) >> 21], 1u);
+    }
+    for (long long i = beg + (nv << 2) + threadIdx.x; i < end; i += big::THREADS) atomicAdd(&hist[score_key(score[i]) >> 21], 1u);
+  } else {
+    for (long long i = beg + threadIdx.x; i < end; i += big::THREADS) atomicAdd(&hist[level_digit<LEVEL>(level_key<LEVEL>(pl, score, i))], 1u);
+  }
+  __syncthreads();
+  const BigLevel& lv = pl.lv[LEVEL];
+  for (int i = threadIdx.x; i < big::BINS; i += big::THREADS) {
+    const unsigned int h = hist[i];
+    lv.bhist[(long long)blockIdx.x * big::BINS + i] = h;
+    if (h) atomicAdd(&lv.ghist[i], h);
+  }
+}
+
+// One block: bucket choice at this level and the per-block candidate offsets.  The number to keep is k at level 0
+// and what level 0 left to its bucket at level 1.
+template <int LEVEL>
+__global__ __launch_bounds__(1024) void topk_pick_kernel(long long k0, BigTopkPlan pl) {
+  __shared__ unsigned long long suf[big::BINS];   // suf[d] = number of keys with digit >= d
+  __shared__ unsigned int sb;
+  __shared__ unsigned int scan[1024];
+  const int tid = threadIdx.x;
+  const BigLevel& lv = pl.lv[LEVEL];
+  const unsigned long long k = LEVEL == 0 ? (unsigned long long)k0 : (unsigned long long)pl.lv[0].state->krem;
+  suf[tid] = lv.ghist[tid];
+  suf[tid + 1024] = lv.ghist[tid + 1024];
+  if (tid == 0) sb = 0;
+  __syncthreads();
+  for (int o = 1; o < big::BINS; o <<= 1) {   // inclusive suffix scan, two bins per thread
+    const unsigned long long v0 = tid + o < big::BINS ? suf[tid + o] : 0ull;
+    const unsigned long long v1 = tid + 1024 + o < big::BINS ? suf[tid + 1024 + o] : 0ull;
+    __syncthreads();
+    suf[tid] += v0;
+    suf[tid + 1024] += v1;
+    __syncthreads();
+  }
+  // the bucket is the largest digit whose suffix count reaches k (digit 0 always does: k <= n)
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int d = tid + 1024 * h;
+    const unsigned long long above = d + 1 < big::BINS ? suf[d + 1] : 0ull;
+    if (suf[d] >= k && above < k) {
+      sb = (unsigned int)d;
+      lv.state->bucket = (unsigned int)d;
+      lv.state->krem = (unsigned int)(k - above);
+      lv.state->ncand = (unsigned int)(suf[d] - above);
+    }
+  }
+  __syncthreads();
+  const unsigned int b = sb;
+  const unsigned int mine = tid < lv.blocks ? lv.bhist[(long long)tid * big::BINS + b] : 0u;
+  scan[tid] = mine;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {   // inclusive scan
+    const unsigned int v = tid >= o ? scan[tid - o] : 0;
+    __syncthreads();
+    scan[tid] += v;
+    __syncthreads();
+  }
+  if (tid < lv.blocks) lv.coff[tid] = scan[tid] - mine;
+}
+
+// position of a flagged thread among the flagged threads of the block, in thread order; *total = their number
+__device__ __forceinline__ int block_rank(bool flag, int* wave_tot, int* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const unsigned long long bal = __ballot(flag);
+  const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  if (lane == 0) wave_tot[wave] = __popcll(bal);
+  __syncthreads();
+  int off = 0, tot = 0;
+  const int nw = blockDim.x >> 6;
+  for (int w = 0; w < nw; ++w) {
+    const int c = wave_tot[w];
+    if (w < wave) off += c;
+    tot += c;
+  }
+  __syncthreads();
+  *total = tot;
+  return off + __popcll(bal & lt);
+}
+
+// exclusive prefix, in thread order, of a per-thread count over the block; *total = the block's sum
+__device__ __forceinline__ int block_scan(int cnt, int* wave_tot, int* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = cnt;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int v = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += v;
+  }
+  if (lane == 63) wave_tot[wave] = inc;
+  __syncthreads();
+  int off = 0, tot = 0;
+  const int nw = blockDim.x >> 6;
+  for (int w = 0; w < nw; ++w) {
+    const int c = wave_tot[w];
+    if (w < wave) off += c;
+    tot += c;
+  }
+  __syncthreads();
+  *total = tot;
+  return off + inc - cnt;
+}
+
+// kept candidates are counted per level-0 chunk (for the final compaction): LDS counters, flushed at the end
+__device__ __forceinline__ void kept_flush(unsigned int* lds_cnt, unsigned int* global_cnt, int blocks0) {
+  __syncthreads();
+  for (int i = threadIdx.x; i < blocks0; i += blockDim.x) {
+    const unsigned int c = lds_cnt[i];
+    if (c) atomicAdd(&global_cnt[i], c);
+  }
+}
+
+// Each thread takes EPT consecutive entries per round (index order is thread order), so a round costs one block
+// scan for EPT * THREADS entries.
+template <int LEVEL>
+__global__ __launch_bounds__(big::THREADS) void topk_gather_kernel(const float* score, long long n, uint8_t* mask, BigTopkPlan pl) {
+  constexpr int EPT = 8;
+  __shared__ int wave_tot[16];
+  __shared__ unsigned int kept_blk[big::MAXBLOCKS];
+  const BigLevel& lv = pl.lv[LEVEL];
+  const unsigned int b = lv.state->bucket;
+  if (LEVEL == 1) {
+    for (int i = threadIdx.x; i < big::MAXBLOCKS; i += big::THREADS) kept_blk[i] = 0;
+    __syncthreads();
+  }
+  long long beg, end;
+  level_range<LEVEL>(pl, n, &beg, &end);
+  unsigned int run = lv.coff[blockIdx.x];
+  unsigned int n_above = 0;   // level 0: this thread's keys above the bucket
+  for (long long base = beg; base < end; base += (long long)EPT * big::THREADS) {
+    const long long i0 = base + (long long)threadIdx.x * EPT;
+    unsigned int key[EPT];
+    int id[EPT];
+    int cnt = 0;
+    unsigned int isc = 0, above = 0;
+    const bool whole = LEVEL == 0 && pl.vec && i0 + EPT <= end;   // i0 is a multiple of 8
+    float xv[EPT];
+    if (whole) {
+      const float4 x0 = *(const float4*)(score + i0), x1 = *(const float4*)(score + i0 + 4);
+      xv[0] = x0.x; xv[1] = x0.y; xv[2] = x0.z; xv[3] = x0.w;
+      xv[4] = x1.x; xv[5] = x1.y; xv[6] = x1.z; xv[7] = x1.w;
+    }
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const long long i = i0 + e;
+      const bool in = i < end;
+      key[e] = whole ? score_key(xv[e]) : (in ? level_key<LEVEL>(pl, score, i) : 0u);
+      id[e] = LEVEL == 0 ? (int)i : (in ? pl.lv[0].cand_idx[i] : 0);
+      const unsigned int dgt = level_digit<LEVEL>(key[e]);
+      if (in && dgt == b) { isc |= 1u << e; ++cnt; }
+      if (in && dgt > b) above |= 1u << e;
+    }
+    int tot;
+    unsigned int pos = run + (unsigned int)block_scan(cnt, wave_tot, &tot);
+    if (LEVEL == 0) {
+      n_above += (unsigned int)__popc(above);
+      if (whole) {   // eight mask bytes in one store
+        unsigned long long m8 = 0;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) m8 |= (unsigned long long)((above >> e) & 1u) << (8 * e);
+        *(unsigned long long*)(mask + i0) = m8;
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const long long i = i0 + e;
+      if (LEVEL == 0) {
+        if (!whole && i < end) mask[i] = (uint8_t)((above >> e) & 1u);
+      } else if ((above >> e) & 1u) {
+        mask[id[e]] = 1;
+        atomicAdd(&kept_blk[(long long)id[e] / pl.chunk0], 1u);
+      }
+      if ((isc >> e) & 1u) {
+        lv.cand_key[pos] = key[e];
+        lv.cand_idx[pos] = id[e];
+        ++pos;
+      }
+    }
+    run += (unsigned int)tot;
+  }
+  if (LEVEL == 1) kept_flush(kept_blk, pl.kept_cand, pl.blocks0);
+  if (LEVEL == 0) {
+    int tot;
+    (void)block_scan((int)n_above, wave_tot, &tot);
+    if (threadIdx.x == 0) pl.gtcnt[blockIdx.x] = (unsigned int)tot;
+  }
+}
+
+// One block: the krem largest of the level-1 candidates on their last 10 key bits, ties to the lower index (the
+// list is in index order), then the exclusive scan of the per-chunk kept counts.
+__global__ __launch_bounds__(1024) void topk_resolve_kernel(uint8_t* mask, float* tau, BigTopkPlan pl) {
+  __shared__ unsigned int hist[1024];
+  __shared__ unsigned int sel_low, sel_krem;
+  __shared__ int wave_tot[16];
+  __shared__ unsigned int kept_blk[big::MAXBLOCKS];
+  const int tid = threadIdx.x;
+  const BigLevel& lv = pl.lv[1];
+  const unsigned int ncand = lv.state->ncand;
+  hist[tid] = 0;
+  kept_blk[tid] = 0;
+  __syncthreads();
+  for (unsigned int i = tid; i < ncand; i += 1024) atomicAdd(&hist[lv.cand_key[i] & 0x3ffu], 1u);
+  __syncthreads();
+  if (tid == 0) {
+    const unsigned int krem = lv.state->krem;
+    unsigned int cum = 0;
+    int d = 1023;
+    for (; d > 0; --d) {
+      if (cum + hist[d] >= krem) break;
+      cum += hist[d];
+    }
+    sel_low = (unsigned int)d;
+    sel_krem = krem - cum;
+    if (tau) *tau = key_score((pl.lv[0].state->bucket << 21) | (lv.state->bucket << 10) | (unsigned int)d);
+  }
+  __syncthreads();
+  const unsigned int low = sel_low, krem = sel_krem;   // krem of the candidates equal to the threshold are kept
+  unsigned int run_eq = 0;
+  for (unsigned int base = 0; base < ncand; base += 1024) {
+    const unsigned int i = base + tid;
+    const bool in = i < ncand;
+    unsigned int key = 0;
+    int id = 0;
+    if (in) {
+      key = lv.cand_key[i] & 0x3ffu;
+      id = lv.cand_idx[i];
+    }
+    const bool eq = in && key == low;
+    int tot;
+    const int r = block_rank(eq, wave_tot, &tot);
+    const bool keep = in && (key > low || (eq && run_eq + (unsigned int)r < krem));
+    if (keep) {
+      mask[id] = 1;
+      atomicAdd(&kept_blk[(long long)id / pl.chunk0], 1u);
+    }
+    run_eq += (unsigned int)tot;
+  }
+  __syncthreads();
+  // exclusive scan of kept = above the level-0 bucket + kept candidates, per level-0 chunk (<= 1024 = one per thread)
+  const unsigned int mine = tid < pl.blocks0 ? pl.gtcnt[tid] + pl.kept_cand[tid] + kept_blk[tid] : 0;
+  __syncthreads();
+  kept_blk[tid] = mine;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    const unsigned int v = tid >= o ? kept_blk[tid - o] : 0;
+    __syncthreads();
+    kept_blk[tid] += v;
+    __syncthreads();
+  }
+  if (tid < pl.blocks0) pl.kpre[tid] = kept_blk[tid] - mine;
+}
+
+__global__ __launch_bounds__(big::THREADS) void topk_compact_kernel(const uint8_t* mask, long long n, int32_t* idx, BigTopkPlan pl) {
+  constexpr int EPT = 8;   // eight consecutive mask bytes per thread: chunk0 and every round start are multiples of 8
+  __shared__ int wave_tot[16];
+  const long long beg = (long long)blockIdx.x * pl.chunk0;
+  const long long end = beg + pl.chunk0 < n ? beg + pl.chunk0 : n;
+  unsigned int run = pl.kpre[blockIdx.x];
+  for (long long base = beg; base < end; base += (long long)EPT * big::THREADS) {
+    const long long i0 = base + (long long)threadIdx.x * EPT;
+    unsigned int bits = 0;
+    if (pl.vec && i0 + EPT <= end) {
+      const unsigned long long m8 = *(const unsigned long long*)(mask + i0);
+#pragma unroll
+      for (int e = 0; e < EPT; ++e)
+        if ((m8 >> (8 * e)) & 0xffull) bits |= 1u << e;
+    } else {
+#pragma unroll
+      for (int e = 0; e < EPT; ++e)
+        if (i0 + e < end && mask[i0 + e]) bits |= 1u << e;
+    }
+    int tot;
+    unsigned int pos = run + (unsigned int)block_scan(__popc(bits), wave_tot, &tot);
+#pragma unroll
+    for (int e = 0; e < EPT; ++e)
+      if ((bits >> e) & 1u) idx[pos++] = (int)(i0 + e);
+    run += (unsigned int)tot;
+  }
+}
 
 strp_status launch_topk(strp_ctx* ctx, const float* score, int n, int k, int group, uint8_t* mask, int32_t* idx, float* tau,
                         void* scratch, size_t scratch_bytes) {
-  (void)scratch;
-  (void)scratch_bytes;
   ProfScope ps(ctx, "topk", 0.0, 5.0 * (double)n + 4.0 * (double)k * group);
-  hipLaunchKernelGGL(topk_kernel, dim3(1), dim3(1024), 0, ctx->stream, score, n, k, group, mask, idx, tau);
+  const bool big_path = n > 65536 && group == 1 && k > 0 && k < n;
+  if (!big_path) {
+    hipLaunchKernelGGL(topk_kernel, dim3(1), dim3(1024), 0, ctx->stream, score, n, k, group, mask, idx, tau);
+    STRP_HIP(ctx, hipGetLastError());
+    return STRP_OK;
+  }
+  if (!scratch || scratch_bytes < topk_scratch_bytes(n))
+    return fail(ctx, STRP_ENOMEM, "top-k over %d scores needs %zu bytes of workspace", n, topk_scratch_bytes(n));
+  BigTopkPlan pl;
+  big_plan(n, &pl.blocks0, &pl.chunk0);
+  pl.vec = (((uintptr_t)score & 15) == 0 && ((uintptr_t)mask & 7) == 0) ? 1 : 0;
+  char* p = (char*)scratch;
+  auto take = [&](size_t bytes) { char* q = p; p += (bytes + 255) & ~size_t(255); return q; };
+  pl.lv[0].blocks = pl.blocks0;
+  pl.lv[1].blocks = big::L1BLOCKS;
+  pl.lv[0].bhist = (unsigned int*)take((size_t)pl.blocks0 * big::BINS * 4);
+  pl.lv[1].bhist = (unsigned int*)take((size_t)big::L1BLOCKS * big::BINS * 4);
+  // contiguous from here to kept_cand: cleared by one fill
+  char* z0 = p;
+  pl.lv[0].ghist = (unsigned int*)take(big::BINS * 4);
+  pl.lv[1].ghist = (unsigned int*)take(big::BINS * 4);
+  pl.lv[0].state = (big::State*)take(sizeof(big::State));
+  pl.lv[1].state = (big::State*)take(sizeof(big::State));
+  pl.kept_cand = (unsigned int*)take((size_t)pl.blocks0 * 4);
+  const size_t zbytes = (size_t)(p - z0);
+  pl.lv[0].coff = (unsigned int*)take((size_t)pl.blocks0 * 4);
+  pl.lv[1].coff = (unsigned int*)take((size_t)big::L1BLOCKS * 4);
+  pl.gtcnt = (unsigned int*)take((size_t)pl.blocks0 * 4);
+  pl.kpre = (unsigned int*)take((size_t)pl.blocks0 * 4);
+  for (int l = 0; l < 2; ++l) {
+    pl.lv[l].cand_key = (unsigned int*)take((size_t)n * 4);
+    pl.lv[l].cand_idx = (int*)take((size_t)n * 4);
+  }
+  STRP_TRY(fill_zero(ctx, z0, zbytes));
+  const dim3 b0(pl.blocks0), b1(big::L1BLOCKS), th(big::THREADS);
+  hipLaunchKernelGGL((topk_hist_kernel<0>), b0, th, 0, ctx->stream, score, (long long)n, pl);
+  hipLaunchKernelGGL((topk_pick_kernel<0>), dim3(1), dim3(1024), 0, ctx->stream, (long long)k, pl);
+  hipLaunchKernelGGL((topk_gather_kernel<0>), b0, th, 0, ctx->stream, score, (long long)n, mask, pl);
+  hipLaunchKernelGGL((topk_hist_kernel<1>), b1, th, 0, ctx->stream, score, (long long)n, pl);
+  hipLaunchKernelGGL((topk_pick_kernel<1>), dim3(1), dim3(1024), 0, ctx->stream, (long long)k, pl);
+  hipLaunchKernelGGL((topk_gather_kernel<1>), b1, th, 0, ctx->stream, score, (long long)n, mask, pl);
+  hipLaunchKernelGGL(topk_resolve_kernel, dim3(1), dim3(1024), 0, ctx->stream, mask, tau, pl);
+  hipLaunchKernelGGL(topk_compact_kernel, b0, th, 0, ctx->stream, (const uint8_t*)mask, (long long)n, idx, pl);
   STRP_HIP(ctx, hipGetLastError());
   return STRP_OK;
 }

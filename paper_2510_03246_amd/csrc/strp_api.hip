@@ -359,8 +359,17 @@ strp_status strp_mask_topk(strp_ctx* ctx, const float* score, int32_t n, int32_t
   if (!ctx) return STRP_EINVAL;
   if (!score || !mask || !idx) return fail(ctx, STRP_EINVAL, "mask_topk: null argument");
   if (n <= 0 || k < 0 || k > n || group <= 0) return fail(ctx, STRP_EINVAL, "mask_topk: need n > 0, 0 <= k <= n, group > 0");
-  return launch_topk(ctx, score, n, k, group, mask, idx, tau, nullptr, 0);
+  const size_t need = (group == 1 && k > 0 && k < n) ? topk_scratch_bytes(n) : 0;
+  void* scratch = nullptr;
+  if (need) {
+    Arena arena(ctx);
+    scratch = arena.take(need);
+    if (!scratch) return fail(ctx, STRP_ENOMEM, "mask_topk: %d scores need %zu bytes of workspace (strp_topk_workspace_bytes)", n, need + 256);
+  }
+  return launch_topk(ctx, score, n, k, group, mask, idx, tau, scratch, need);
 }
+
+size_t strp_topk_workspace_bytes(int32_t n) { return n > 0 ? topk_scratch_bytes(n) + 512 : 0; }
 
 }  // extern "C"
 

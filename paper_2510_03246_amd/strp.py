@@ -24,7 +24,7 @@ STAGE_ALL = 63
 
 EXPORTS = [
     "strp_create", "strp_destroy", "strp_last_error", "strp_set_precision", "strp_set_workspace",
-    "strp_poll", "strp_workspace_bytes", "strp_module_cache_bytes", "strp_profile_enable", "strp_profile_read", "strp_gram", "strp_score_alloc", "strp_mask_topk",
+    "strp_poll", "strp_workspace_bytes", "strp_module_cache_bytes", "strp_profile_enable", "strp_profile_read", "strp_gram", "strp_score_alloc", "strp_mask_topk", "strp_topk_workspace_bytes",
     "strp_refit", "strp_module_init", "strp_admm_step",
 ]
 
@@ -95,6 +95,8 @@ def load_library():
     lib.strp_workspace_bytes.restype = C.c_size_t
     lib.strp_module_cache_bytes.argtypes = [C.POINTER(ModuleDesc)]
     lib.strp_module_cache_bytes.restype = C.c_size_t
+    lib.strp_topk_workspace_bytes.restype = C.c_size_t
+    lib.strp_topk_workspace_bytes.argtypes = [C.c_int32]
     lib.strp_gram.argtypes = [vp, vp, C.c_int, i32, i64, i64, vp, i32, vp, i32, vp, C.c_int]
     lib.strp_score_alloc.argtypes = [vp, C.POINTER(ScoreIn), vp, vp, i32, i32, vp, vp, dbl, dbl, dbl, vp, vp]
     lib.strp_mask_topk.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
@@ -104,7 +106,7 @@ def load_library():
     lib.strp_admm_step.argtypes = [vp, C.POINTER(ModuleDesc), C.POINTER(ModuleState), C.POINTER(Params),
                                    C.POINTER(Report)]
     for name in EXPORTS:
-        if name not in ("strp_last_error", "strp_workspace_bytes", "strp_module_cache_bytes"):
+        if name not in ("strp_last_error", "strp_workspace_bytes", "strp_module_cache_bytes", "strp_topk_workspace_bytes"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -213,6 +215,9 @@ class Context:
         mask = torch.empty(n, dtype=torch.uint8, device=score.device)
         idx = torch.empty(max(k * group, 1), dtype=torch.int32, device=score.device)
         tau = torch.empty(1, dtype=torch.float32, device=score.device)
+        need = int(self.lib.strp_topk_workspace_bytes(n))
+        if need:
+            self.ensure_workspace(need)
         self.check(self.lib.strp_mask_topk(self.h, _ptr(score), n, k, group, _ptr(mask), _ptr(idx), _ptr(tau)))
         return mask, idx[: k * group], tau
 

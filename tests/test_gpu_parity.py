@@ -108,6 +108,31 @@ def test_mask_topk_exact(ctx, n, k, group):
         assert float(tau.item()) == np.float32(to)
 
 
+@pytest.mark.parametrize("n,frac,kind", [(48 * 28672, 0.3, "chi2"), ((1 << 22) + 3, 0.5, "normal"), (70001, 0.9, "ties"),
+                                         (200000, 0.37, "equal"), (65537, 1.0 / 65537, "normal")])
+def test_mask_topk_global_threshold(ctx, n, frac, kind):
+    """One threshold over a long score vector (all layers' scores at once, Alg. 4): the multi-block path."""
+    rng = np.random.default_rng(n)
+    if kind == "chi2":
+        score = rng.normal(size=n).astype(np.float32) ** 2
+    elif kind == "normal":
+        score = rng.normal(size=n).astype(np.float32)          # negative keys too
+    elif kind == "ties":
+        score = rng.integers(0, 50, size=n).astype(np.float32)   # ~2 % of the entries share every value
+    else:
+        score = np.full(n, 3.25, dtype=np.float32)
+    k = max(1, int(frac * n))
+    if kind in ("chi2", "normal"):
+        kth = np.sort(score)[::-1][k - 1]
+        score[rng.integers(0, n, size=64)] = kth                 # ties exactly at the threshold, spread over the blocks
+    mask, idx, tau = ctx.strp_mask_topk(torch.from_numpy(score).cuda(), k)
+    assert ctx.poll() == strp.OK
+    mo, io, to = orc.select_topk(score, k)
+    assert np.array_equal(mask.cpu().numpy(), mo)
+    assert np.array_equal(idx.cpu().numpy().astype(np.int64), io)
+    assert float(tau.item()) == np.float32(to)
+
+
 # ---------------------------------------------------------------------------------------------
 # strp_score_alloc
 # ---------------------------------------------------------------------------------------------
