@@ -183,6 +183,79 @@ def softmax_allocation(I, n_units, rbar, temperature, rmax=0.95, group_id=None):
 
 
 # --------------------------------------------------------------------------------------
+# Alg. 2: weight-only layer importances and temperature-guided inverse weighting
+# --------------------------------------------------------------------------------------
+def weight_importance(mats, var_coef, l2_coef=0.0, scale=1.0):
+    """scale * (|W|_1 + var_coef * Var(W) + l2_coef * |W|_2) of ONE parameter group (Alg. 2 step 1).
+
+    `mats` is a list of arrays that together form the group (a head's slices of the four
+    attention matrices, or a single fc matrix): the 1-norm is the sum of absolute values,
+    Var the population variance over every entry of the group, |.|_2 the Euclidean
+    (Frobenius) norm of the entries.
+    """
+    v = np.concatenate([np.asarray(m, dtype=np.float64).ravel() for m in mats])
+    l1 = np.sum(np.abs(v))
+    var = np.mean(v * v) - np.mean(v) ** 2
+    l2 = np.sqrt(np.sum(v * v))
+    return float(scale * (l1 + var_coef * var + l2_coef * l2))
+
+
+def layer_importance_alg2(kind, layer, groups, gamma, rho=1.0):
+    """I_l of Alg. 2: depth decay gamma^l (l counted from 1) times, for an attention layer,
+    rho * sum over heads of (|W_h|_1 + 0.1 Var(W_h) + 0.01 |W_h|_2); for an MLP layer,
+    sum over fc1, fc2 of (|W_m|_1 + 0.05 Var(W_m)).  `groups` = list of parameter groups
+    (each a list of arrays): the heads, or [[fc1], [fc2]]."""
+    d = gamma ** layer
+    if kind == "attn":
+        return sum(weight_importance(g, 0.1, 0.01, d * rho) for g in groups)
+    if kind == "mlp":
+        return sum(weight_importance(g, 0.05, 0.0, d) for g in groups)
+    raise ValueError(kind)
+
+
+def inverse_allocation(I, n_units, rbar, temperature, rmax=0.95, group_id=None):
+    """Alg. 2 step 2: per group w = softmax(-I/T) (energies scaled by the group's mean |I|, as in
+    softmax_allocation), r = clip(rbar * L * (1 - w) / sum(1 - w), 0, rmax).  No rescale step.
+    A group with a single layer gets r = rbar (1 - w = 0 there).  Integer counts as in
+    softmax_allocation."""
+    I = np.asarray(I, dtype=np.float64)
+    n_units = np.asarray(n_units, dtype=np.int64)
+    L = I.shape[0]
+    if group_id is None:
+        group_id = np.zeros(L, dtype=np.int64)
+    group_id = np.asarray(group_id)
+    r = np.zeros(L)
+    nprune = np.zeros(L, dtype=np.int64)
+    for gid in np.unique(group_id):
+        sel = np.nonzero(group_id == gid)[0]
+        Lg = sel.shape[0]
+        Ig = I[sel]
+        scale = np.mean(np.abs(Ig))
+        In = Ig / scale if scale > 0 else np.zeros(Lg)
+        a = -In / temperature
+        a = a - np.max(a)
+        w = np.exp(a)
+        w = w / np.sum(w)
+        if Lg > 1:
+            rg = rbar * Lg * (1.0 - w) / np.sum(1.0 - w)
+        else:
+            rg = np.full(1, rbar)
+        rg = np.minimum(np.maximum(rg, 0.0), rmax)
+        r[sel] = rg
+        x = rg * n_units[sel]
+        base = np.floor(x).astype(np.int64)
+        extra = int(np.rint(np.sum(x))) - int(np.sum(base))
+        frac = x - base
+        order = np.argsort(-frac, kind="stable")
+        for t in range(max(extra, 0)):
+            base[order[t % Lg]] += 1
+        base = np.minimum(base, n_units[sel] - 1)
+        base = np.maximum(base, 0)
+        nprune[sel] = base
+    return r, nprune
+
+
+# --------------------------------------------------------------------------------------
 # O4  top-k structured mask (threshold rule below Lemma 1; Alg. 4 threshold step)
 # --------------------------------------------------------------------------------------
 def select_topk(score, k, group=1):

@@ -375,3 +375,47 @@ def test_config_shapes_match_tables():
         c = inputs.CONFIGS[name]
         assert 2 * c.d * c.f == p == 8 * c.d * c.d
         assert c.L == layers[name]
+
+
+# ---------------------------------------------------------------------------------------------
+# Alg. 2: weight-only importances and inverse weighting
+# ---------------------------------------------------------------------------------------------
+def test_weight_importance_hand_values():
+    """A 2 x 2 matrix worked by hand: |W|_1 = 10, mean = -0.5, Var = 30/4 - 0.25 = 7.25, |W|_2 = sqrt(30)."""
+    W = np.array([[1.0, -2.0], [3.0, -4.0]])
+    assert orc.weight_importance([W], 0.0) == 10.0
+    assert np.isclose(orc.weight_importance([W], 1.0) - 10.0, 7.25, rtol=1e-14)
+    assert np.isclose(orc.weight_importance([W], 0.0, 1.0) - 10.0, np.sqrt(30.0), rtol=1e-14)
+    # a group of two slices pools its entries: same numbers from the two rows given separately
+    assert np.isclose(orc.weight_importance([W[0], W[1]], 0.1, 0.01, 2.0), 2.0 * (10.0 + 0.725 + 0.01 * np.sqrt(30.0)), rtol=1e-14)
+    # the layer formula: MLP = fc1 and fc2 scored separately, depth decay gamma^l
+    I = orc.layer_importance_alg2("mlp", 3, [[W], [2 * W]], gamma=0.5)
+    assert np.isclose(I, 0.125 * ((10.0 + 0.05 * 7.25) + (20.0 + 0.05 * 29.0)), rtol=1e-14)
+    Ia = orc.layer_importance_alg2("attn", 1, [[W], [W]], gamma=0.9, rho=2.0)
+    assert np.isclose(Ia, 0.9 * 2.0 * 2 * (10.0 + 0.725 + 0.01 * np.sqrt(30.0)), rtol=1e-14)
+
+
+def test_inverse_allocation_identities():
+    rng = np.random.default_rng(3)
+    L = 12
+    I = rng.uniform(1.0, 3.0, size=L)
+    n = np.full(L, 1000)
+    r, npr = orc.inverse_allocation(I, n, 0.5, 1.0)
+    assert np.isclose(np.sum(r), 0.5 * L, rtol=1e-12)            # nothing clipped: the mean is rbar
+    assert np.sum(npr) == int(np.rint(np.sum(r * n)))
+    # as printed: w = softmax(-I/T) falls with I, so 1 - w and the sparsity RISE with the importance
+    order = np.argsort(I)
+    assert np.all(np.diff(r[order]) >= 0)
+    # T -> infinity: uniform
+    r_inf, _ = orc.inverse_allocation(I, n, 0.5, 1e9)
+    assert np.allclose(r_inf, 0.5, rtol=1e-6)
+    # two layers, closed form: scaled energies a, b with mean 1; w1 = 1 / (1 + exp((a - b)/T)); r1 = 2 rbar (1 - w1)
+    a, b = 0.8, 1.2
+    r2, _ = orc.inverse_allocation(np.array([a, b]) * 7.0, np.array([10, 10]), 0.4, 0.5)
+    w1 = 1.0 / (1.0 + np.exp((a - b) / 0.5))
+    assert np.allclose(r2, [0.8 * (1 - w1), 0.8 * w1], rtol=1e-12)
+    # one layer per group: r = rbar; the clip binds at rmax
+    r1, _ = orc.inverse_allocation(np.array([5.0, 1.0, 2.0]), np.array([8, 8, 8]), 0.3, 1.0, group_id=np.array([0, 1, 1]))
+    assert r1[0] == 0.3
+    rc, _ = orc.inverse_allocation(np.array([1.0, 50.0]), np.array([100, 100]), 0.9, 0.05)
+    assert np.max(rc) == 0.95 and np.min(rc) >= 0.0
