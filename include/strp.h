@@ -145,6 +145,38 @@ strp_status strp_score_alloc(strp_ctx* ctx, const strp_score_in* in, float* unit
                              int32_t* nprune_out);
 
 /*
+ * strp_weight_energy -- weight-only layer importance (Alg. 2, step 1), one parameter group per call:
+ *   *energy += scale * ( |W|_1 + var_coef * Var(W) + l2_coef * |W|_2 )
+ * over every entry of the n_mats matrices listed (a head's slices of the attention matrices, or one fc
+ * matrix): |W|_1 = sum of absolute values, Var = population variance, |W|_2 = Euclidean norm of the entries.
+ * The listing's attention term is (var_coef, l2_coef) = (0.1, 0.01) per head with scale = gamma^l * rho, its
+ * MLP term (0.05, 0) per fc matrix with scale = gamma^l; a layer's importance is the sum of its groups' calls.
+ *   mats: HOST array of descriptors; each W is a DEVICE pointer, row-major [rows x ld], ld >= cols.
+ *   energy: DEVICE double, accumulated (zero it first).  Needs 6 KiB of the context's workspace.
+ * Errors: STRP_EINVAL, STRP_ENOMEM (no workspace).
+ */
+typedef struct strp_weight_ref {
+  const void* W;
+  int32_t dtype;     /* strp_dtype */
+  int32_t rows, cols;
+  int64_t ld;
+} strp_weight_ref;
+strp_status strp_weight_energy(strp_ctx* ctx, const strp_weight_ref* mats, int32_t n_mats, double var_coef,
+                               double l2_coef, double scale, double* energy);
+
+/*
+ * strp_alloc_inverse -- temperature-guided inverse weighting (Alg. 2, step 2) over energies[L] (device):
+ * per softmax group (group_id, NULL = one group) w = softmax(-I / T) with the energies divided by the group's
+ * mean |I| (the same scale-free temperature as strp_score_alloc), r_l = clip(rbar * L_g * (1 - w_l) /
+ * sum_j (1 - w_j), 0, rmax); a group of one layer gets rbar.  nprune_out: largest-remainder integer counts of
+ * r_l * n_units[l] per group, every layer keeping at least one unit.  All arrays are device arrays of length L.
+ * Errors: STRP_EINVAL.
+ */
+strp_status strp_alloc_inverse(strp_ctx* ctx, const double* energies, int32_t L, const int32_t* n_units,
+                               const int32_t* group_id, double rbar, double temperature, double rmax,
+                               double* r_out, int32_t* nprune_out);
+
+/*
  * strp_mask_topk -- structured mask by score threshold (rule below Lemma 1; Alg. 4 threshold step).
  * Keeps exactly the k highest of the n unit scores; equal scores keep the lower index.
  *   mask[n] uint8 in {0,1};  idx[k*group] int32 ascending kept CHANNEL indices (unit*group + c);

@@ -220,10 +220,76 @@ strp_status launch_unit_scores(strp_ctx* ctx, const double* sums, const double* 
 // ---------------------------------------------------------------------------------------------
 // softmax allocation: one wavefront, fp64, layers strided over lanes
 // ---------------------------------------------------------------------------------------------
+// ---------------------------------------------------------------------------------------------
+// weight statistics of a parameter group (Alg. 2 step 1): sum |w|, sum w, sum w^2 over every entry of a list of
+// matrices.  Block b keeps its own partial [3] (launches on one stream add to it in order: deterministic);
+// weight_energy_kernel folds the partials into  scale (|W|_1 + cv Var(W) + c2 |W|_2)  and adds it to the energy.
+// ---------------------------------------------------------------------------------------------
+constexpr int WSTAT_BLOCKS = 256;
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void weight_stats_kernel(const void* W, int rows, int cols, long long ld, double* partial) {
+  double s1 = 0.0, s = 0.0, s2 = 0.0;
+  const long long n = (long long)rows * cols;
+  for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long long)WSTAT_BLOCKS * 256) {
+    const long long r = e / cols, c = e - r * cols;
+    float x;
+    if (BF16) x = __builtin_bit_cast(float, (unsigned int)((const unsigned short*)W)[r * ld + c] << 16);
+    else x = ((const float*)W)[r * ld + c];
+    const double v = (double)x;
+    s1 += fabs(v);
+    s += v;
+    s2 += v * v;
+  }
+  __shared__ double red[4][3];
+  s1 = wave_allsum_d(s1);
+  s = wave_allsum_d(s);
+  s2 = wave_allsum_d(s2);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) { red[wave][0] = s1; red[wave][1] = s; red[wave][2] = s2; }
+  __syncthreads();
+  if (threadIdx.x < 3) {
+    const int q = threadIdx.x;
+    partial[3 * blockIdx.x + q] += red[0][q] + red[1][q] + red[2][q] + red[3][q];
+  }
+}
+
+__global__ __launch_bounds__(64) void weight_energy_kernel(const double* partial, double count, double var_coef, double l2_coef,
+                                                           double scale, double* energy) {
+  double a[3] = {0.0, 0.0, 0.0};
+  for (int b = threadIdx.x; b < WSTAT_BLOCKS; b += 64)
+    for (int q = 0; q < 3; ++q) a[q] += partial[3 * b + q];
+  for (int q = 0; q < 3; ++q) a[q] = wave_allsum_d(a[q]);
+  if (threadIdx.x == 0) {
+    const double mean = a[1] / count;
+    const double var = a[2] / count - mean * mean;
+    *energy += scale * (a[0] + var_coef * var + l2_coef * sqrt(a[2]));
+  }
+}
+
+strp_status launch_weight_energy(strp_ctx* ctx, const strp_weight_ref* mats, int n_mats, double var_coef, double l2_coef, double scale,
+                                 double* energy, double* partial /* [3 * WSTAT_BLOCKS] scratch */) {
+  STRP_TRY(fill_zero(ctx, partial, sizeof(double) * 3 * WSTAT_BLOCKS));
+  double count = 0.0;
+  for (int i = 0; i < n_mats; ++i) {
+    const strp_weight_ref& m = mats[i];
+    if (m.dtype == STRP_BF16)
+      hipLaunchKernelGGL((weight_stats_kernel<true>), dim3(WSTAT_BLOCKS), dim3(256), 0, ctx->stream, m.W, m.rows, m.cols, (long long)m.ld, partial);
+    else
+      hipLaunchKernelGGL((weight_stats_kernel<false>), dim3(WSTAT_BLOCKS), dim3(256), 0, ctx->stream, m.W, m.rows, m.cols, (long long)m.ld, partial);
+    count += (double)m.rows * (double)m.cols;
+  }
+  hipLaunchKernelGGL(weight_energy_kernel, dim3(1), dim3(64), 0, ctx->stream, (const double*)partial, count, var_coef, l2_coef, scale, energy);
+  STRP_HIP(ctx, hipGetLastError());
+  return STRP_OK;
+}
+size_t weight_energy_scratch_bytes() { return sizeof(double) * 3 * WSTAT_BLOCKS; }
+
 constexpr int ALLOC_MAXL = 1024;
 
+// rule 0: r = rbar L w, clip, conditional rescale (Alg. 1);  rule 1: r = rbar L (1 - w) / sum(1 - w), clip (Alg. 2)
 __global__ __launch_bounds__(64) void alloc_kernel(const double* I, int L, const int32_t* n_units, const int32_t* group_id,
-                                                   double rbar, double temperature, double rmax, double* r_out,
+                                                   double rbar, double temperature, double rmax, int rule, double* r_out,
                                                    int32_t* nprune_out) {
   __shared__ double r[ALLOC_MAXL];
   __shared__ double frac[ALLOC_MAXL];
@@ -269,7 +335,9 @@ __global__ __launch_bounds__(64) void alloc_kernel(const double* I, int L, const
     int at_max = 0;
     double rsum = 0.0;
     for (int q = lane; q < Lg; q += 64) {
-      double rv = rbar * (double)Lg * (r[q] / wsum);
+      const double w = r[q] / wsum;
+      double rv = rbar * (double)Lg * w;
+      if (rule == 1) rv = Lg > 1 ? rbar * (double)Lg * (1.0 - w) / (double)(Lg - 1) : rbar;   // sum(1 - w) = L - 1
       rv = fmin(fmax(rv, 0.0), rmax);
       r[q] = rv;
       at_max |= (rv == rmax);
@@ -277,7 +345,7 @@ __global__ __launch_bounds__(64) void alloc_kernel(const double* I, int L, const
     }
     at_max = __any(at_max);
     rsum = wave_allsum_d(rsum);
-    if (!at_max) {
+    if (!at_max && rule == 0) {
       const double mu = rsum / (double)Lg;
       for (int q = lane; q < Lg; q += 64) r[q] = fmin(fmax(r[q] * (rbar / mu), 0.0), rmax);
     }
@@ -312,10 +380,10 @@ __global__ __launch_bounds__(64) void alloc_kernel(const double* I, int L, const
 }
 
 strp_status launch_alloc(strp_ctx* ctx, const double* energies, int L, const int32_t* n_units, const int32_t* group_id,
-                         double rbar, double temperature, double rmax, double* r_out, int32_t* nprune_out) {
+                         double rbar, double temperature, double rmax, int rule, double* r_out, int32_t* nprune_out) {
   if (L <= 0 || L > ALLOC_MAXL) return fail(ctx, STRP_EINVAL, "alloc: L=%d outside [1, %d]", L, ALLOC_MAXL);
   hipLaunchKernelGGL(alloc_kernel, dim3(1), dim3(64), 0, ctx->stream, energies, L, n_units, group_id, rbar, temperature,
-                     rmax, r_out, nprune_out);
+                     rmax, rule, r_out, nprune_out);
   STRP_HIP(ctx, hipGetLastError());
   return STRP_OK;
 }

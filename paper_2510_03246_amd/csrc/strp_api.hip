@@ -350,7 +350,7 @@ strp_status strp_score_alloc(strp_ctx* ctx, const strp_score_in* in, float* unit
   }
   STRP_TRY(launch_row_sums(ctx, in->A, in->a_dtype, in->Z, in->Z0, in->ld, in->T, in->n_channels, in->mode, sums));
   STRP_TRY(launch_unit_scores(ctx, sums, n2, in->n_channels, in->group, in->mode, unit_score, energies + layer_idx));
-  if (r_out) STRP_TRY(launch_alloc(ctx, energies, L, n_units, group_id, rbar, temperature, rmax, r_out, nprune_out));
+  if (r_out) STRP_TRY(launch_alloc(ctx, energies, L, n_units, group_id, rbar, temperature, rmax, 0, r_out, nprune_out));
   return STRP_OK;
 }
 
@@ -367,6 +367,30 @@ strp_status strp_mask_topk(strp_ctx* ctx, const float* score, int32_t n, int32_t
     if (!scratch) return fail(ctx, STRP_ENOMEM, "mask_topk: %d scores need %zu bytes of workspace (strp_topk_workspace_bytes)", n, need + 256);
   }
   return launch_topk(ctx, score, n, k, group, mask, idx, tau, scratch, need);
+}
+
+strp_status strp_weight_energy(strp_ctx* ctx, const strp_weight_ref* mats, int32_t n_mats, double var_coef, double l2_coef,
+                               double scale, double* energy) {
+  if (!ctx) return STRP_EINVAL;
+  if (!mats || n_mats <= 0 || !energy) return fail(ctx, STRP_EINVAL, "weight_energy: null or empty matrix list");
+  for (int i = 0; i < n_mats; ++i) {
+    const strp_weight_ref& m = mats[i];
+    if (!m.W || m.rows <= 0 || m.cols <= 0 || m.ld < m.cols) return fail(ctx, STRP_EINVAL, "weight_energy: bad matrix %d", i);
+    if (m.dtype != STRP_BF16 && m.dtype != STRP_F32) return fail(ctx, STRP_EINVAL, "weight_energy: unknown dtype");
+  }
+  Arena arena(ctx);
+  STRP_TAKE(ctx, arena, partial, double, weight_energy_scratch_bytes() / sizeof(double));
+  return launch_weight_energy(ctx, mats, n_mats, var_coef, l2_coef, scale, energy, partial);
+}
+
+strp_status strp_alloc_inverse(strp_ctx* ctx, const double* energies, int32_t L, const int32_t* n_units, const int32_t* group_id,
+                               double rbar, double temperature, double rmax, double* r_out, int32_t* nprune_out) {
+  if (!ctx) return STRP_EINVAL;
+  if (!energies || !n_units || !r_out || !nprune_out) return fail(ctx, STRP_EINVAL, "alloc_inverse: null argument");
+  if (L <= 0) return fail(ctx, STRP_EINVAL, "alloc_inverse: L must be positive");
+  if (!(temperature > 0.0) || !(rbar >= 0.0 && rbar <= 1.0) || !(rmax > 0.0 && rmax <= 1.0))
+    return fail(ctx, STRP_EINVAL, "alloc_inverse: need temperature > 0, 0 <= rbar <= 1, 0 < rmax <= 1");
+  return launch_alloc(ctx, energies, L, n_units, group_id, rbar, temperature, rmax, 1, r_out, nprune_out);
 }
 
 size_t strp_topk_workspace_bytes(int32_t n) { return n > 0 ? topk_scratch_bytes(n) + 512 : 0; }

@@ -189,8 +189,11 @@ strp_status launch_colnorm2(strp_ctx* ctx, const void* W, int w_dtype, int rows,
 strp_status launch_unit_scores(strp_ctx* ctx, const double* sums, const double* n2, int n_channels, int group,
                                int mode, float* score, double* energy_out);
 strp_status launch_alloc(strp_ctx* ctx, const double* energies, int L, const int32_t* n_units,
-                         const int32_t* group_id, double rbar, double temperature, double rmax, double* r_out,
+                         const int32_t* group_id, double rbar, double temperature, double rmax, int rule, double* r_out,
                          int32_t* nprune_out);
+strp_status launch_weight_energy(strp_ctx* ctx, const strp_weight_ref* mats, int n_mats, double var_coef, double l2_coef,
+                                 double scale, double* energy, double* partial);
+size_t weight_energy_scratch_bytes();
 strp_status launch_topk(strp_ctx* ctx, const float* score, int n, int k, int group, uint8_t* mask, int32_t* idx,
                         float* tau, void* scratch, size_t scratch_bytes);
 size_t topk_scratch_bytes(int n);

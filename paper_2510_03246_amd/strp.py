@@ -24,7 +24,7 @@ STAGE_ALL = 63
 
 EXPORTS = [
     "strp_create", "strp_destroy", "strp_last_error", "strp_set_precision", "strp_set_workspace",
-    "strp_poll", "strp_workspace_bytes", "strp_module_cache_bytes", "strp_profile_enable", "strp_profile_read", "strp_gram", "strp_score_alloc", "strp_mask_topk", "strp_topk_workspace_bytes",
+    "strp_poll", "strp_workspace_bytes", "strp_module_cache_bytes", "strp_profile_enable", "strp_profile_read", "strp_gram", "strp_score_alloc", "strp_mask_topk", "strp_topk_workspace_bytes", "strp_weight_energy", "strp_alloc_inverse",
     "strp_refit", "strp_module_init", "strp_admm_step",
 ]
 
@@ -64,6 +64,10 @@ class Report(C.Structure):
                 ("lam2", C.c_double), ("tau", C.c_float), ("s", C.c_int32), ("status", C.c_int32)]
 
 
+class WeightRef(C.Structure):
+    _fields_ = [("W", C.c_void_p), ("dtype", C.c_int32), ("rows", C.c_int32), ("cols", C.c_int32), ("ld", C.c_int64)]
+
+
 class ProfileEntry(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("launches", C.c_int32), ("ms", C.c_double), ("flops", C.c_double),
                 ("bytes", C.c_double)]
@@ -97,6 +101,8 @@ def load_library():
     lib.strp_module_cache_bytes.restype = C.c_size_t
     lib.strp_topk_workspace_bytes.restype = C.c_size_t
     lib.strp_topk_workspace_bytes.argtypes = [C.c_int32]
+    lib.strp_weight_energy.argtypes = [vp, C.POINTER(WeightRef), i32, C.c_double, C.c_double, C.c_double, vp]
+    lib.strp_alloc_inverse.argtypes = [vp, vp, i32, vp, vp, C.c_double, C.c_double, C.c_double, vp, vp]
     lib.strp_gram.argtypes = [vp, vp, C.c_int, i32, i64, i64, vp, i32, vp, i32, vp, C.c_int]
     lib.strp_score_alloc.argtypes = [vp, C.POINTER(ScoreIn), vp, vp, i32, i32, vp, vp, dbl, dbl, dbl, vp, vp]
     lib.strp_mask_topk.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
@@ -220,6 +226,22 @@ class Context:
             self.ensure_workspace(need)
         self.check(self.lib.strp_mask_topk(self.h, _ptr(score), n, k, group, _ptr(mask), _ptr(idx), _ptr(tau)))
         return mask, idx[: k * group], tau
+
+    def strp_weight_energy(self, mats, var_coef, l2_coef, scale, energy):
+        """energy (device double, 1 element) += scale (|W|_1 + var_coef Var(W) + l2_coef |W|_2) over the 2-D tensors in mats."""
+        self.ensure_workspace(1 << 16)
+        refs = (WeightRef * len(mats))()
+        for r, m in zip(refs, mats):
+            r.W, r.dtype, r.rows, r.cols, r.ld = m.data_ptr(), dtype_code(m), m.shape[0], m.shape[1], m.stride(0)
+        self.check(self.lib.strp_weight_energy(self.h, refs, len(mats), float(var_coef), float(l2_coef), float(scale), _ptr(energy)))
+
+    def strp_alloc_inverse(self, energies, n_units, rbar, temperature, rmax=0.95, group_id=None):
+        L = energies.numel()
+        r = torch.empty(L, dtype=torch.float64, device=energies.device)
+        npr = torch.empty(L, dtype=torch.int32, device=energies.device)
+        self.check(self.lib.strp_alloc_inverse(self.h, _ptr(energies), L, _ptr(n_units), _ptr(group_id), float(rbar),
+                                               float(temperature), float(rmax), _ptr(r), _ptr(npr)))
+        return r, npr
 
     def strp_refit(self, side, Gram, lam, Lhs, Rhs, T, idx, W, chol=None, chol_valid=False):
         out, inn = W.shape

@@ -189,6 +189,44 @@ def test_allocation_parity(ctx, temperature, rbar):
     assert np.array_equal(npr.cpu().numpy(), n_ref)
 
 
+def test_weight_only_importance_and_inverse_allocation(ctx):
+    """Alg. 2: layer importances from the weights alone, then the inverse-weighted sparsities."""
+    d, f, heads, Lm = 192, 768, 6, 4
+    g = d // heads
+    gen = torch.Generator(device="cuda").manual_seed(21)
+    gamma, rho = 0.95, 1.5
+    I_ref, kinds = [], []
+    energies = torch.zeros(2 * Lm, dtype=torch.float64, device="cuda")
+    for l in range(Lm):
+        for kind in ("attn", "mlp"):
+            li = len(kinds)
+            depth = l + 1
+            if kind == "attn":
+                Wq, Wk, Wv, Wo = (((0.02 + 0.005 * l) * torch.randn((d, d), generator=gen, device="cuda")).to(torch.bfloat16) for _ in range(4))
+                groups_gpu = [[Wq[h * g:(h + 1) * g], Wk[h * g:(h + 1) * g], Wv[h * g:(h + 1) * g], Wo[:, h * g:(h + 1) * g]] for h in range(heads)]
+                for grp in groups_gpu:
+                    ctx.strp_weight_energy(grp, 0.1, 0.01, gamma ** depth * rho, energies[li:li + 1])
+            else:
+                W1 = (0.02 * torch.randn((f, d), generator=gen, device="cuda") + 0.001 * l)          # fp32, non-zero mean
+                W2 = (0.03 * torch.randn((d, f), generator=gen, device="cuda")).to(torch.bfloat16)
+                groups_gpu = [[W1], [W2]]
+                for grp in groups_gpu:
+                    ctx.strp_weight_energy(grp, 0.05, 0.0, gamma ** depth, energies[li:li + 1])
+            groups = [[m.double().cpu().numpy() for m in grp] for grp in groups_gpu]
+            I_ref.append(orc.layer_importance_alg2(kind, depth, groups, gamma, rho))
+            kinds.append(kind)
+    assert ctx.poll() == strp.OK
+    I_ref = np.array(I_ref)
+    assert np.allclose(energies.cpu().numpy(), I_ref, rtol=1e-12)
+    gid = np.array([0 if k == "attn" else 1 for k in kinds], dtype=np.int32)
+    n_units = np.array([heads if k == "attn" else f for k in kinds], dtype=np.int32)
+    for temperature, rbar in ((0.5, 0.5), (2.0, 0.7), (0.02, 0.9)):
+        r, npr = ctx.strp_alloc_inverse(energies, torch.from_numpy(n_units).cuda(), rbar, temperature, 0.95, torch.from_numpy(gid).cuda())
+        r_ref, n_ref = orc.inverse_allocation(I_ref, n_units, rbar, temperature, 0.95, gid)
+        assert np.allclose(r.cpu().numpy(), r_ref, rtol=1e-10, atol=1e-14)
+        assert np.array_equal(npr.cpu().numpy().astype(np.int64), n_ref)
+
+
 # ---------------------------------------------------------------------------------------------
 # strp_refit
 # ---------------------------------------------------------------------------------------------
