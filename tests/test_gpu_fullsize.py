@@ -179,3 +179,23 @@ def test_objective(run):
     assert abs(rep.J_ridge - terms.sum()) <= TOL_J * terms.sum()
     assert abs(rep.J - terms[:3].sum()) <= TOL_J * terms[:3].sum()
     assert keep.sum().item() == k
+
+
+def test_gain_and_lemma_scores_on_moved_state(run):
+    """After one iteration Z != Z0 and A != A0: the three-tensor token sums (GAIN, LEMMA) at full size."""
+    mod, cfg, m = run["mod"], run["cfg"], run["m"]
+    ctx = mod.ctx
+    rng = np.random.default_rng(2)
+    units = rng.choice(cfg.f, size=12, replace=False)
+    rows = torch.from_numpy(units).cuda()
+    A, Z, Z0 = (getattr(mod, n)[rows, :cfg.T].double().cpu().numpy() for n in ("A", "Z", "Z0"))
+    W2u = m["W2hat"][:, rows].double().cpu().numpy()
+    sums = orc.unit_sums(A, np.maximum(Z0, 0.0), Z, Z0, W2u)
+    score = torch.empty(cfg.f, dtype=torch.float32, device="cuda")
+    energies = torch.zeros(1, dtype=torch.float64, device="cuda")
+    for mode_gpu, mode_ref in ((strp.GAIN, orc.GAIN), (strp.LEMMA, orc.LEMMA)):
+        ctx.strp_score_alloc(mod.A, cfg.T, mode_gpu, score, energies, 0, 1, Z=mod.Z, Z0=mod.Z0, n2=mod.n2)
+        assert ctx.poll() == strp.OK
+        ref = orc.unit_scores(*sums, mode_ref)
+        assert np.allclose(score.cpu().numpy()[units], ref, rtol=2e-6, atol=0)
+        assert np.isclose(energies.item(), float(score.double().mean().item()), rtol=1e-6)

@@ -344,6 +344,51 @@ def test_free_running_config1(ctx):
         assert max(err.values()) < TOL_F, err
 
 
+def test_model_driver_temperature_sweep(ctx):
+    """Alg. 1 end to end on three small modules: energies -> softmax allocation -> per-module ADMM -> summed loss,
+    for each temperature of the grid; the best temperature is the argmin of the totals."""
+    cfg = inputs.CONFIGS["tiny"]
+    L, K, rbar = 3, 3, 0.5
+    temps = (0.5, 1.0, 2.0)
+    mods_in = []
+    for layer in range(L):
+        m = inputs.make_ffn_module(cfg, layer, 3, "cuda")
+        m["X"] = (m["X"] * (1.0 + 0.6 * layer)).contiguous()       # different activation scales -> different energies
+        mods_in.append(m)
+    ref, best_ref = orc.prune_model([tuple(m[n].double().cpu().numpy() for n in ("W1hat", "W2hat", "X")) for m in mods_in],
+                                    rbar, temps, K)
+    totals = {}
+    n_units = torch.full((L,), cfg.f, dtype=torch.int32, device="cuda")
+    for temp in temps:
+        mods = []
+        energies = torch.zeros(L, dtype=torch.float64, device="cuda")
+        r_out = torch.empty(L, dtype=torch.float64, device="cuda")
+        npr = torch.empty(L, dtype=torch.int32, device="cuda")
+        for layer, m in enumerate(mods_in):
+            mod = strp.FFNModule(ctx, m["W1hat"], m["W2hat"], m["X"], cfg.T)
+            mod.init(_params(1))
+            last = layer == L - 1
+            ctx.strp_score_alloc(mod.A, cfg.T, strp.WANDA, mod.score, energies, layer, L, n2=mod.n2,
+                                 **(dict(n_units=n_units, rbar=rbar, temperature=temp, rmax=0.95, r_out=r_out, nprune_out=npr)
+                                    if last else {}))
+            mods.append(mod)
+        assert ctx.poll() == strp.OK
+        assert np.allclose(energies.cpu().numpy(), ref[temp]["energies"], rtol=1e-6)
+        assert np.allclose(r_out.cpu().numpy(), ref[temp]["r"], rtol=1e-6)
+        assert np.array_equal(npr.cpu().numpy().astype(np.int64), ref[temp]["nprune"])
+        losses = []
+        for layer, mod in enumerate(mods):
+            k = cfg.f - int(npr[layer].item())
+            p = _params(k)
+            for it in range(K):
+                rep = mod.step(p)
+            assert rep.status == strp.OK
+            losses.append(rep.J_ridge)
+        assert np.allclose(losses, ref[temp]["losses"], rtol=TOL_J)
+        totals[temp] = float(np.sum(losses))
+    assert min(totals, key=totals.get) == best_ref
+
+
 @pytest.mark.parametrize("mode", [strp.WANDA, strp.GAIN])
 def test_teacher_forced_stages_medium(ctx, mode):
     """Each stage of one iteration from oracle-supplied state (several tiles, ragged sizes)."""
