@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0
 TRAFFIC_GB = {}
 
 
-def cpu_baseline(cfg_name: str, sample_tokens: int):
+def cpu_baseline(cfg_name: str, sample_tokens: int, score_mode: str = "wanda"):
     """The oracle as it stands, timed on the host cores on a bounded token sample of the same module."""
     import numpy as np  # noqa: F401
     import torch
@@ -38,7 +38,7 @@ def cpu_baseline(cfg_name: str, sample_tokens: int):
     st = orc.module_init(*(m[n].double().numpy() for n in ("W1hat", "W2hat", "X")))
     k = cfg.f - int(round(cfg.rbar * cfg.f))
     t0 = time.perf_counter()
-    orc.admm_step(st, k, 1.0, 1.0, orc.WANDA, select=True)
+    orc.admm_step(st, k, 1.0, 1.0, {"wanda": orc.WANDA, "lemma": orc.LEMMA, "gain": orc.GAIN}[score_mode], select=True)
     dt = time.perf_counter() - t0
     return dict(value=sample_tokens / dt, unit="calib tokens/s", cores=torch.get_num_threads(), kind="oracle",
                 sample=f"one oracle ADMM iteration (fp64 numpy) on {cfg_name} d={cfg.d} f={cfg.f} k={k} with "
@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="opt6.7b")
     ap.add_argument("--tokens", type=int, default=0, help="override T (0: the configuration's 128 x 2048)")
+    ap.add_argument("--score-mode", default="wanda", choices=("wanda", "lemma", "gain"),
+                    help="unit score used by the select stage (the metric is quoted on wanda)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
     ap.add_argument("--select-stress", action="store_true",
@@ -101,7 +103,8 @@ def main():
     m = inputs.make_ffn_module(cfg, 0, 0, dev)
     ctx = strp.Context(0)
     mod = strp.FFNModule(ctx, m["W1hat"], m["W2hat"], m["X"], cfg.T, k_max=k)
-    params = strp.Params(1.0, 1.0, 0.01, strp.WANDA, 1, k, 0)
+    mode = {"wanda": strp.WANDA, "lemma": strp.LEMMA, "gain": strp.GAIN}[args.score_mode]
+    params = strp.Params(1.0, 1.0, 0.01, mode, 1, k, 0)
     mod.init(params)
     for _ in range(args.warmup):
         mod.step(params, report=False)
@@ -159,7 +162,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16x2-split MFMA, f32 accumulate, f64 solves", "data": "synthetic",
         "config": {"workload": f"{cfg.name} FFN module: d={cfg.d} f={cfg.f} T={cfg.T} keep k={k} "
-                               f"({cfg.rbar:.0%} pruned), WANDA score, re-select every iteration, alpha=beta=1",
+                               f"({cfg.rbar:.0%} pruned), {args.score_mode.upper()} score, re-select every iteration, alpha=beta=1",
                    "module_iterations_per_s": args.steps / dt, "objective_J": rep.J_ridge},
         "roofline": roof,
         "kernels": kernels,
@@ -169,7 +172,7 @@ def main():
     if not args.no_cpu_baseline:
         del mod, m
         torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(args.workload, args.cpu_sample_tokens)
+        out["cpu_baseline"] = cpu_baseline(args.workload, args.cpu_sample_tokens, args.score_mode)
     print(json.dumps(out))
 
 
