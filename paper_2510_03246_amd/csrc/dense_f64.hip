@@ -173,15 +173,17 @@ __device__ __forceinline__ double rsqrt_f64(double d) {
 }
 
 // Thread (ty, tx) of the 16x16 block keeps the 16 elements (ty + 16 ii, tx + 16 kk) of the working block AND of
-// the inverse being built in registers for the whole factorisation; per column only the column itself and
-// row j of the inverse are exchanged through LDS (double buffered, one barrier per column).
-//   trailing update with the UNSCALED column:  a_ik -= (a_ij / d_j) a_kj
-//   inverse: A = Lu D Lu^T with Lu unit lower; the same multipliers m_ij = a_ij / d_j applied to the identity
-//   (V_i. -= m_ij V_j. for i > j) give Lu^-1, and L^-1 = D^-1/2 Lu^-1.
+// the inverse being built in registers for the whole factorisation.  Four columns are eliminated per barrier:
+// the four columns of the block and rows j0..j0+3 of the inverse go through LDS (double buffered), every thread
+// factors the 4 x 4 pivot block redundantly (A = Lu D Lu^T, Lu unit lower), eliminates the four panel entries of
+// the eight row indices it needs (p_c(x) = P(x,c) - sum_{c'<c} p_c'(x) u_{c,c'}), and applies the rank-4 update
+//   a_ik -= sum_c (p_c(i) / d_c) p_c(k)            (unpredicated: entries of finished columns are never re-read)
+//   V_i. -= sum_c (p_c(i) / d_c) q_c(.)  for i > j0 + c,   q_c = row j0 + c of the inverse, eliminated likewise
+// so that V ends as Lu^-1 and L^-1 = D^-1/2 Lu^-1.  Column j0 + c of L is p_c(i) d_c^-1/2.
 __global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld, int jb, double* invd, int32_t* status) {
   __shared__ double Lm[NB][NB + 1];   // factor, entries on and below the diagonal
-  __shared__ double col[2][NB];
-  __shared__ double vrow[2][NB];
+  __shared__ double colb[2][4][NB];
+  __shared__ double rowb[2][4][NB];
   __shared__ double rsd[NB];          // d_j^-1/2
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   double a[4][4], v[4][4];
@@ -193,52 +195,109 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld
       a[ii][kk] = (i < jb && k <= i) ? A[(long long)i * ld + k] : ((i == k) ? 1.0 : 0.0);
       v[ii][kk] = (i == k) ? 1.0 : 0.0;
     }
-  for (int j = 0; j < NB; ++j) {
-    double* cj = col[j & 1];
-    double* vj = vrow[j & 1];
-    if (tx == (j & 15)) {       // owners of column j publish it (rows ty + 16 ii)
+  for (int j0 = 0; j0 < NB; j0 += 4) {
+    const int buf = (j0 >> 2) & 1, lo16 = j0 & 15, hi = j0 >> 4;
+    if (tx >= lo16 && tx < lo16 + 4) {      // owners of columns j0 .. j0+3 publish them (rows ty + 16 ii)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
-        if (kk == (j >> 4)) {
+        if (kk == hi) {
 #pragma unroll
-          for (int ii = 0; ii < 4; ++ii) cj[ty + 16 * ii] = a[ii][kk];
+          for (int ii = 0; ii < 4; ++ii) colb[buf][tx - lo16][ty + 16 * ii] = a[ii][kk];
         }
     }
-    if (ty == (j & 15)) {       // owners of row j of the inverse publish it (columns tx + 16 kk)
+    if (ty >= lo16 && ty < lo16 + 4) {      // owners of rows j0 .. j0+3 of the inverse publish them
 #pragma unroll
       for (int ii = 0; ii < 4; ++ii)
-        if (ii == (j >> 4)) {
+        if (ii == hi) {
 #pragma unroll
-          for (int kk = 0; kk < 4; ++kk) vj[tx + 16 * kk] = v[ii][kk];
+          for (int kk = 0; kk < 4; ++kk) rowb[buf][ty - lo16][tx + 16 * kk] = v[ii][kk];
         }
     }
     __syncthreads();
-    const double dj = cj[j];
-    const bool ok = dj > 0.0;
-    const double rs = ok ? rsqrt_f64(dj) : 1.0;
-    const double invdj = rs * rs;
+    // ---- 4 x 4 pivot block (every thread, redundantly) --------------------------------------------
+    const double (*cb)[NB] = colb[buf];
+    const double D00 = cb[0][j0], D10 = cb[0][j0 + 1], D20 = cb[0][j0 + 2], D30 = cb[0][j0 + 3];
+    const double D11 = cb[1][j0 + 1], D21 = cb[1][j0 + 2], D31 = cb[1][j0 + 3];
+    const double D22 = cb[2][j0 + 2], D32 = cb[2][j0 + 3], D33 = cb[3][j0 + 3];
+    bool ok = true;
+    double rs[4], id[4];
+    ok = ok && D00 > 0.0;
+    rs[0] = D00 > 0.0 ? rsqrt_f64(D00) : 1.0;
+    id[0] = rs[0] * rs[0];
+    const double u10 = D10 * id[0], u20 = D20 * id[0], u30 = D30 * id[0];
+    const double E11 = D11 - D10 * u10, E21 = D21 - D20 * u10, E31 = D31 - D30 * u10;
+    ok = ok && E11 > 0.0;
+    rs[1] = E11 > 0.0 ? rsqrt_f64(E11) : 1.0;
+    id[1] = rs[1] * rs[1];
+    const double u21 = E21 * id[1], u31 = E31 * id[1];
+    const double F22 = D22 - D20 * u20 - E21 * u21, F32 = D32 - D30 * u20 - E31 * u21;
+    ok = ok && F22 > 0.0;
+    rs[2] = F22 > 0.0 ? rsqrt_f64(F22) : 1.0;
+    id[2] = rs[2] * rs[2];
+    const double u32 = F32 * id[2];
+    const double G33 = D33 - D30 * u30 - E31 * u31 - F32 * u32;
+    ok = ok && G33 > 0.0;
+    rs[3] = G33 > 0.0 ? rsqrt_f64(G33) : 1.0;
+    id[3] = rs[3] * rs[3];
     if (tid == 0) {
-      rsd[j] = rs;
-      if (!ok && j < jb) atomicCAS(status, 0, (int)STRP_ENOTPD);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) rsd[j0 + c] = rs[c];
+      if (!ok && j0 + 3 < jb) atomicCAS(status, 0, (int)STRP_ENOTPD);
+      else if (!ok) {   // ragged block: only pivots inside jb count (the padding is the identity)
+        const bool bad = (0 < jb - j0 && !(D00 > 0.0)) || (1 < jb - j0 && !(E11 > 0.0)) || (2 < jb - j0 && !(F22 > 0.0));
+        if (bad) atomicCAS(status, 0, (int)STRP_ENOTPD);
+      }
     }
-    if (tid >= j && tid < NB) Lm[tid][j] = cj[tid] * rs;   // column j of the factor (diagonal: d * rs = sqrt d)
-    double ci[4], ck[4], cv[4], vk[4];
+    // ---- eliminated panel entries of this thread's rows (pi) and columns (pk) --------------------------
+    double pi[4][4], pk[4][4];   // [c][ii] and [c][kk]
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      ci[q] = cj[ty + 16 * q] * invdj;
-      ck[q] = cj[tx + 16 * q];
-      cv[q] = (ty + 16 * q > j) ? ci[q] : 0.0;
-      vk[q] = vj[tx + 16 * q];
+      const int xi = ty + 16 * q, xk = tx + 16 * q;
+      pi[0][q] = cb[0][xi];
+      pi[1][q] = cb[1][xi] - pi[0][q] * u10;
+      pi[2][q] = cb[2][xi] - pi[0][q] * u20 - pi[1][q] * u21;
+      pi[3][q] = cb[3][xi] - pi[0][q] * u30 - pi[1][q] * u31 - pi[2][q] * u32;
+      pk[0][q] = cb[0][xk];
+      pk[1][q] = cb[1][xk] - pk[0][q] * u10;
+      pk[2][q] = cb[2][xk] - pk[0][q] * u20 - pk[1][q] * u21;
+      pk[3][q] = cb[3][xk] - pk[0][q] * u30 - pk[1][q] * u31 - pk[2][q] * u32;
     }
-    // a: unpredicated (columns <= j were published before this point and are not read again from registers,
-    // entries above the diagonal are never used); v: only rows below j change
+    // column j0 + c of the factor: thread (ty, tx = c) holds it for rows ty + 16 ii
 #pragma unroll
-    for (int ii = 0; ii < 4; ++ii)
+    for (int c = 0; c < 4; ++c)
+      if (tx == c) {
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        a[ii][kk] = __builtin_fma(-ci[ii], ck[kk], a[ii][kk]);
-        v[ii][kk] = __builtin_fma(-cv[ii], vk[kk], v[ii][kk]);
+        for (int ii = 0; ii < 4; ++ii) {
+          const int row = ty + 16 * ii;
+          if (row >= j0 + c) Lm[row][j0 + c] = pi[c][ii] * rs[c];
+        }
       }
+    // rows j0 + c of the inverse, eliminated among themselves, at this thread's columns
+    const double (*rb)[NB] = rowb[buf];
+    double qk[4][4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int xk = tx + 16 * q;
+      qk[0][q] = rb[0][xk];
+      qk[1][q] = rb[1][xk] - u10 * qk[0][q];
+      qk[2][q] = rb[2][xk] - u20 * qk[0][q] - u21 * qk[1][q];
+      qk[3][q] = rb[3][xk] - u30 * qk[0][q] - u31 * qk[1][q] - u32 * qk[2][q];
+    }
+    // ---- rank-4 updates ------------------------------------------------------------------------
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii) {
+      const int row = ty + 16 * ii;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const double m = pi[c][ii] * id[c];
+        const double mv = row > j0 + c ? m : 0.0;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          a[ii][kk] = __builtin_fma(-m, pk[c][kk], a[ii][kk]);
+          v[ii][kk] = __builtin_fma(-mv, qk[c][kk], v[ii][kk]);
+        }
+      }
+    }
   }
   __syncthreads();
 #pragma unroll
