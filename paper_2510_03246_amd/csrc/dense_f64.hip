@@ -142,7 +142,10 @@ __global__ __launch_bounds__(256) void dgemm_kernel(const DgemmP p) {
 
 static strp_status dgemm_launch(strp_ctx* ctx, const DgemmP& p, int batch) {
   if (p.M <= 0 || p.N <= 0 || batch <= 0) return STRP_OK;
-  const bool big = p.M > 64 && p.N > 64;
+  // 128 x 128 tiles only when they still give every CU a couple of blocks: a block is a serial chain of fp64
+  // matrix-core instructions, and with triangular K ranges the heaviest block bounds a one-round launch
+  const long long blocks128 = (long long)((p.M + 127) / 128) * ((p.N + 127) / 128) * batch;
+  const bool big = p.M > 64 && p.N > 64 && blocks128 > 512;
   const int ts = big ? 128 : 64;
   dim3 grid((p.M + ts - 1) / ts, (p.N + ts - 1) / ts, batch);
   if (big)
