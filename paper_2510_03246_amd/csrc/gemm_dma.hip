@@ -1,4 +1,4 @@
-// Pipelined MFMA GEMM for large problems: 256x256 block tile, four wavefronts of 128x128, operand tiles
+// Pipelined MFMA GEMM for large problems: 256x256 block tile, eight wavefronts of 128x64, operand tiles
 // brought from HBM/L2 straight into LDS by the global-load-to-LDS path (no staging registers), four LDS
 // stages of 16 contraction steps each, three stages in flight behind the one being multiplied.
 //
@@ -232,9 +232,6 @@ static void launch_dma_nw(strp_ctx* ctx, const GemmP& p, int npp, int npq) {
   }
 }
 
-void launch_gemm_dma(strp_ctx* ctx, const GemmP& p, int npp, int npq) {
-  static const int env_nw = getenv("STRP_WAVES") ? atoi(getenv("STRP_WAVES")) : 8;   // tuning knob
-  if (env_nw == 4) launch_dma_nw<4>(ctx, p, npp, npq); else launch_dma_nw<8>(ctx, p, npp, npq);
-}
+void launch_gemm_dma(strp_ctx* ctx, const GemmP& p, int npp, int npq) { launch_dma_nw<8>(ctx, p, npp, npq); }
 
 }  // namespace strp
