@@ -282,6 +282,15 @@ strp_status strp_module_init(strp_ctx* ctx, const strp_module_desc* desc, strp_m
 strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_module_state* st,
                            const strp_params* params, strp_report* report_host);
 
+/*
+ * strp_peak_probe -- measurement aid (no part of the method): sustained rate, in TFLOP/s on *tflops_out (host),
+ * of the fp16 matrix-core instruction the GEMMs use.  kind 0: constant register operands, nothing else running
+ * (the issue limit); kind 1: the GEMM's inner loop without its memory side (fragments re-read from LDS every
+ * stage, random fp16 data).  Runs for about `milliseconds` twice and times the second run.  Needs 512 KiB of the
+ * context's workspace; synchronises the stream.  Errors: STRP_EINVAL, STRP_ENOMEM, STRP_EHIP.
+ */
+strp_status strp_peak_probe(strp_ctx* ctx, int32_t kind, double milliseconds, double* tflops_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libstrp.so")
-SOURCES = ["gemm_mfma.hip", "gemm_dma.hip", "split_planes.hip", "dense_f64.hip", "score_select.hip", "strp_api.hip"]
+SOURCES = ["gemm_mfma.hip", "gemm_dma.hip", "split_planes.hip", "dense_f64.hip", "score_select.hip", "peak_probe.hip", "strp_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
