@@ -185,6 +185,7 @@ def main():
         out["select_stress"] = select_stress(ctx, torch)
     if not args.no_mfma_ceiling:
         out["mfma_ceiling"] = {"unit": "TFLOP/s", "register_operands": ctx.strp_peak_probe(0),
+                               "register_operands_random_data": ctx.strp_peak_probe(2),
                                "lds_fed_random_data": ctx.strp_peak_probe(1)}
         if roof.get("executed"):
             roof["executed_frac_of_lds_fed_ceiling"] = roof["executed"] / out["mfma_ceiling"]["lds_fed_random_data"]

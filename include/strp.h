@@ -285,7 +285,7 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
 /*
  * strp_peak_probe -- measurement aid (no part of the method): sustained rate, in TFLOP/s on *tflops_out (host),
  * of the fp16 matrix-core instruction the GEMMs use.  kind 0: constant register operands, nothing else running
- * (the issue limit); kind 1: the GEMM's inner loop without its memory side (fragments re-read from LDS every
+ * (the issue limit); kind 2: the same with random fp16 values in the operand registers; kind 1: the GEMM's inner loop without its memory side (fragments re-read from LDS every
  * stage, random fp16 data).  Runs for about `milliseconds` twice and times the second run.  Needs 512 KiB of the
  * context's workspace; synchronises the stream.  Errors: STRP_EINVAL, STRP_ENOMEM, STRP_EHIP.
  */

@@ -1,6 +1,8 @@
 // Measurement aid: the sustained rate of v_mfma_f32_32x32x16_f16 on this chip, so that the GEMM figures can be read
 // against what the matrix cores deliver in practice and not only against the nominal 2.5 PFLOP/s.
 //   kind 0: back-to-back MFMA on constant register operands (no LDS, no memory): the instruction's issue limit
+//   kind 2: as kind 0 with random fp16 values in the operand registers (operand toggling is what the power
+//           management reacts to)
 //   kind 1: the GEMM's inner loop without its memory side: eight wavefronts per CU, each 4 x 2 tiles, three passes
 //           per 16-deep stage, operand fragments re-read from LDS every stage, LDS filled with random fp16 values
 //           (operand toggling is what the power management reacts to)
@@ -26,6 +28,39 @@ __global__ __launch_bounds__(512, 1) void probe_mfma_reg_kernel(float* out, int 
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[i], 0, 0, 0);
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s += acc[i][e];
+  out[blockIdx.x * 512 + threadIdx.x] = s;
+}
+
+__global__ __launch_bounds__(512, 1) void probe_mfma_rand_kernel(float* out, int iters, unsigned int seed) {
+  probe_floatx16 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.0f;
+  unsigned int x = seed + threadIdx.x * 2654435761u + blockIdx.x * 40503u;
+  auto rnd = [&]() {
+    x = x * 1664525u + 1013904223u;
+    const unsigned int lo = (x & 0x83ffu) | 0x3800u, hi = ((x >> 16) & 0x83ffu) | 0x3800u;
+    return lo | (hi << 16);
+  };
+  uint4 a[4], b[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a[i] = make_uint4(rnd(), rnd(), rnd(), rnd());
+#pragma unroll
+  for (int i = 0; i < 2; ++i) b[i] = make_uint4(rnd(), rnd(), rnd(), rnd());
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[i * 2 + j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(probe_half8, a[i]), __builtin_bit_cast(probe_half8, b[j]),
+                                                                acc[i * 2 + j], 0, 0, 0);
   }
   float s = 0.0f;
 #pragma unroll
@@ -98,23 +133,25 @@ using namespace strp;
 
 extern "C" strp_status strp_peak_probe(strp_ctx* ctx, int32_t kind, double milliseconds, double* tflops_out) {
   if (!ctx) return STRP_EINVAL;
-  if (!tflops_out || (kind != 0 && kind != 1) || !(milliseconds > 0.0) || milliseconds > 2000.0)
-    return fail(ctx, STRP_EINVAL, "peak_probe: kind 0 or 1, 0 < milliseconds <= 2000");
+  if (!tflops_out || (kind < 0 || kind > 2) || !(milliseconds > 0.0) || milliseconds > 2000.0)
+    return fail(ctx, STRP_EINVAL, "peak_probe: kind 0, 1 or 2, 0 < milliseconds <= 2000");
   Arena arena(ctx);
   STRP_TAKE(ctx, arena, out, float, 256 * 512);
   hipEvent_t e0, e1;
   STRP_HIP(ctx, hipEventCreate(&e0));
   STRP_HIP(ctx, hipEventCreate(&e1));
-  const double flops_per_iter = kind == 0 ? 8.0 * 32768.0 : 24.0 * 32768.0;   // per wavefront
+  const double flops_per_iter = kind == 1 ? 24.0 * 32768.0 : 8.0 * 32768.0;   // per wavefront
   // ~25 ns per MFMA pair of wavefronts at full rate: size the run to the requested duration (long enough for the
   // power management to settle), then measure
-  int iters = (int)(milliseconds * 1e-3 / ((kind == 0 ? 8.0 : 24.0) * 2.0 * 13.4e-9));
+  int iters = (int)(milliseconds * 1e-3 / ((kind == 1 ? 24.0 : 8.0) * 2.0 * 13.4e-9));
   if (iters < 1000) iters = 1000;
   float ms = 0.0f;
   for (int rep = 0; rep < 2; ++rep) {   // the first run warms the clocks
     STRP_HIP(ctx, hipEventRecord(e0, ctx->stream));
     if (kind == 0)
       hipLaunchKernelGGL(probe_mfma_reg_kernel, dim3(256), dim3(512), 0, ctx->stream, out, iters);
+    else if (kind == 2)
+      hipLaunchKernelGGL(probe_mfma_rand_kernel, dim3(256), dim3(512), 0, ctx->stream, out, iters, 5u + rep);
     else
       hipLaunchKernelGGL(probe_mfma_lds_kernel, dim3(256), dim3(512), 0, ctx->stream, out, iters, 17u + rep);
     STRP_HIP(ctx, hipEventRecord(e1, ctx->stream));
