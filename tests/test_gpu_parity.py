@@ -467,6 +467,29 @@ def test_free_running_reselect_medium(ctx):
     assert max(err.values()) < TOL_F, err
 
 
+@pytest.mark.parametrize("name,d,f,T,k,dt", [("all kept", 72, 264, 520, 264, "bf16"), ("k=8", 136, 520, 1003, 8, "bf16"),
+                                              ("tiny T", 64, 256, 96, 100, "f32"), ("f32 X", 264, 1048, 3000, 400, "f32"),
+                                              ("k=f-1", 72, 264, 777, 263, "bf16"), ("wide d", 776, 1032, 2600, 300, "bf16")])
+def test_free_running_edge_shapes(ctx, name, d, f, T, k, dt):
+    """Two free-running iterations (GAIN score, re-select) at the corners: nothing pruned, almost everything pruned,
+    fewer tokens than one tile, fp32 inputs, d larger than a tile and not a multiple of it."""
+    base = inputs.CONFIGS["opt125m"]
+    cfg = type(base)(**{**base.__dict__, "d": d, "f": f, "T": T, "n_outlier": 2, "dtype": dt})
+    m = inputs.make_ffn_module(cfg, 0, 5, "cuda", ld=(T + 7) // 8 * 8)
+    mod = strp.FFNModule(ctx, m["W1hat"], m["W2hat"], m["X"], T)
+    p = _params(k, strp.GAIN, reselect=1)
+    mod.init(p)
+    st = orc.module_init(m["W1hat"].double().cpu().numpy(), m["W2hat"].double().cpu().numpy(), m["X"][:, :T].double().cpu().numpy())
+    for it in range(2):
+        rep = mod.step(p)
+        terms = orc.admm_step(st, k, 1.0, 1.0, orc.GAIN, select=True)
+        assert rep.status == strp.OK
+    assert not mask_mismatch_outside_ties(st.score, mod.mask.cpu().numpy(), k)
+    err = _compare_state(mod, st, T)
+    assert max(err.values()) < TOL_F, err
+    assert abs(rep.J_ridge - float(np.sum(terms))) <= TOL_J * float(np.sum(terms))
+
+
 def test_large_tile_pipeline_path(ctx):
     """Sizes at which the 256x256 LDS-DMA pipelined kernel is selected (ragged in every dimension)."""
     base = inputs.CONFIGS["opt125m"]
