@@ -174,7 +174,8 @@ def main():
         "metric": "ADMM module-iterations/s (calib tokens/s) at OPT-6.7B shape; % MFMA peak",
         "value": tokens_per_s, "unit": "calib tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16x2-split MFMA, f32 accumulate, f64 solves", "data": "synthetic",
+        "dtype": "f16", "dtype_detail": "fp32 values as two fp16 planes on the fp16 matrix cores (hi*hi + hi*lo + lo*hi), "
+                                        "fp32 accumulation; fp64 for the ridge factorisations and solves", "data": "synthetic",
         "config": {"workload": f"{cfg.name} FFN module: d={cfg.d} f={cfg.f} T={cfg.T} keep k={k} "
                                f"({cfg.rbar:.0%} pruned), {args.score_mode.upper()} score, re-select every iteration, alpha=beta=1",
                    "module_iterations_per_s": args.steps / dt, "objective_J": rep.J_ridge},
