@@ -124,12 +124,6 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma_kernel(const GemmP p) {
       if (NPQ == 2) f.ql[j] = *(const uint4*)(st + (NPP + 1) * PLANE_STAGE_BYTES + offQ + j * 512);
     }
   };
-  auto zero_frags = [&](Frags& f) {
-#pragma unroll
-    for (int i = 0; i < WTM; ++i) f.ph[i] = f.pl[i] = make_uint4(0, 0, 0, 0);
-#pragma unroll
-    for (int j = 0; j < WTN; ++j) f.qh[j] = f.ql[j] = make_uint4(0, 0, 0, 0);
-  };
   auto mma1 = [&](uint4 a, uint4 b, floatx16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
   };
@@ -152,6 +146,19 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma_kernel(const GemmP p) {
       for (int j = 0; j < WTN; ++j) acc[i][j] = mma1(f.ph[i], f.qh[j], acc[i][j]);
   };
 
+  // Instruction order inside a half stage: the fragment reads of the next stage are issued in the shadow of the
+  // matrix-core instructions of this one (one LDS read after each of the first MFMAs) instead of ahead of them.
+  auto interleave = [&]() {
+    constexpr int NRD = (NPP + NPQ == 4) ? 12 : (NPP + NPQ == 3 ? (NPP == 2 ? 10 : 8) : 6);   // ds_read_b128 per half stage
+    constexpr int NMF = WTM * WTN * (NPP * NPQ == 4 ? 3 : NPP * NPQ);
+#pragma unroll
+    for (int i = 0; i < NRD; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one DS read
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD, 0);
+  };
+
   // ---- pipeline: stages 0..3 requested up front; iteration s multiplies stage s from registers while the
   // fragments of stage s+1 are read from LDS and stage s+4 is requested into the slot stage s just left.
   issue_stage(0);
@@ -162,26 +169,27 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma_kernel(const GemmP p) {
   wait_vmcnt<3 * LPW>();     // stage 0 has landed (three younger stages may still be in flight)
   __syncthreads();
   read_frags(fa, 0);
+  int s = 0;
 #pragma unroll 1
-  for (int s = 0; s < nstages; s += 2) {
+  for (; s + 1 < nstages; s += 2) {
     // -- even half: multiply stage s (fa), fetch fragments of stage s+1 into fb
     wait_vmcnt_lgkm0<2 * LPW>();   // stage s+1 has landed; this wavefront's fragment reads of stage s are complete
     __syncthreads();               // ... and so for every wavefront: the slot of stage s may be overwritten
     issue_stage(s + 4);            // into the slot of stage s
     read_frags(fb, s + 1);
-    if (s + 1 >= nstages) zero_frags(fb);   // ragged last pair: the odd half multiplies zeros
-    __builtin_amdgcn_sched_barrier(0);
     run_mfma(fa);
+    interleave();
     __builtin_amdgcn_sched_barrier(0);
     // -- odd half
     wait_vmcnt_lgkm0<2 * LPW>();
     __syncthreads();
     issue_stage(s + 5);
-    read_frags(fa, s + 2);
-    __builtin_amdgcn_sched_barrier(0);
+    read_frags(fa, s + 2);         // past the last stage this reads a slot that is never multiplied
     run_mfma(fb);
+    interleave();
     __builtin_amdgcn_sched_barrier(0);
   }
+  if (s < nstages) run_mfma(fa);   // odd stage count: the last stage is already in registers
   wait_vmcnt<0>();           // nothing may still be writing LDS when the block ends or reuses it
   if (tid < ROWS) srow[tid] = my_row;
   __syncthreads();
