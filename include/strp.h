@@ -231,9 +231,14 @@ typedef struct {
   int32_t* idx;        /* [f]         kept indices ascending (first s valid)                */
   double* scalars;     /* [32]        device scalars: lam1, lam2, objective sums, tau       */
   void* cache;         /* strp_module_cache_bytes(desc) bytes, 256-byte aligned: fp16 operand planes of
-                          X and Y written by strp_module_init and read by every later step      */
+                          X and Y written by strp_module_init and read by every later step, and the
+                          cached scoring sums (see sums_cached)                                  */
   int32_t s;           /* kept units of the current mask (host field, set by the library)   */
   int32_t iter;        /* inner iterations done (host field)                                */
+  int32_t sums_cached; /* host field, set by the library: the scoring sums of the pruned rows were accumulated
+                          while the last iteration wrote those rows (1: sum A^2, 2: all four) and sit in `cache`,
+                          so the next selection streams the kept rows only; strp_module_init clears it.  Z, A and
+                          mask must not be changed by the caller between iterations (or set this field to 0).   */
 } strp_module_state;
 
 typedef struct {

@@ -31,12 +31,24 @@ __device__ __forceinline__ float bf16hi(unsigned int w) { return __builtin_bit_c
 // ---------------------------------------------------------------------------------------------
 template <bool A_BF16, bool FULL>
 __global__ __launch_bounds__(256) void row_sums_kernel(const void* Av, const float* Z, const float* Z0, long long ld,
-                                                       long long T, int rows, double* sums, int32_t* status) {
+                                                       long long T, int rows, double* sums, int32_t* status,
+                                                       const uint8_t* kept_mask, const double* cached) {
   const int r = blockIdx.x;
   const int tid = threadIdx.x;
   double g = 0.0, e = 0.0, u = 0.0, v = 0.0;
   const long long T8 = T & ~7LL;
-  if (A_BF16 && !FULL) {
+  // a row whose sums were accumulated when it was last written is not streamed again (block-uniform branch)
+  const bool have = cached && !kept_mask[r];
+  if (have) {
+    if (tid == 0) {
+      g = cached[r];
+      if (FULL) {
+        e = cached[(long long)rows + r];
+        u = cached[2LL * rows + r];
+        v = cached[3LL * rows + r];
+      }
+    }
+  } else if (A_BF16 && !FULL) {
     const uint4* a8 = (const uint4*)((const unsigned short*)Av + (long long)r * ld);
     for (long long c = tid; c < T8 / 8; c += 256) {
       const uint4 w = a8[c];
@@ -117,19 +129,28 @@ __global__ __launch_bounds__(256) void row_sums_kernel(const void* Av, const flo
 }
 
 strp_status launch_row_sums(strp_ctx* ctx, const void* A, int a_dtype, const float* Z, const float* Z0, long long ld,
-                            long long T, int rows, int mode, double* sums) {
+                            long long T, int rows, int mode, double* sums, const uint8_t* kept_mask, const double* cached,
+                            int n_cached) {
   const bool full = mode != STRP_SCORE_WANDA;
+  if (!kept_mask || !cached) {
+    cached = nullptr;
+    n_cached = 0;
+  }
+  const int streamed = rows - n_cached;
   if (full && a_dtype != STRP_F32) return fail(ctx, STRP_EINVAL, "score: LEMMA/GAIN need fp32 auxiliaries");
   dim3 grid(rows), block(256);
   const double es = a_dtype == STRP_BF16 ? 2.0 : 4.0;
-  ProfScope ps(ctx, full ? "row_sums_full" : "row_sums_wanda", (full ? 8.0 : 2.0) * (double)rows * (double)T,
-               (full ? 12.0 : es) * (double)rows * (double)T);
+  ProfScope ps(ctx, full ? "row_sums_full" : "row_sums_wanda", (full ? 8.0 : 2.0) * (double)streamed * (double)T,
+               (full ? 12.0 : es) * (double)streamed * (double)T);
   if (full)
-    hipLaunchKernelGGL((row_sums_kernel<false, true>), grid, block, 0, ctx->stream, A, Z, Z0, ld, T, rows, sums, ctx->status_dev);
+    hipLaunchKernelGGL((row_sums_kernel<false, true>), grid, block, 0, ctx->stream, A, Z, Z0, ld, T, rows, sums, ctx->status_dev, kept_mask,
+                       cached);
   else if (a_dtype == STRP_BF16)
-    hipLaunchKernelGGL((row_sums_kernel<true, false>), grid, block, 0, ctx->stream, A, Z, Z0, ld, T, rows, sums, ctx->status_dev);
+    hipLaunchKernelGGL((row_sums_kernel<true, false>), grid, block, 0, ctx->stream, A, Z, Z0, ld, T, rows, sums, ctx->status_dev, kept_mask,
+                       (const double*)nullptr);
   else
-    hipLaunchKernelGGL((row_sums_kernel<false, false>), grid, block, 0, ctx->stream, A, Z, Z0, ld, T, rows, sums, ctx->status_dev);
+    hipLaunchKernelGGL((row_sums_kernel<false, false>), grid, block, 0, ctx->stream, A, Z, Z0, ld, T, rows, sums, ctx->status_dev, kept_mask,
+                       cached);
   STRP_HIP(ctx, hipGetLastError());
   return STRP_OK;
 }

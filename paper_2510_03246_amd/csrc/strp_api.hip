@@ -125,13 +125,20 @@ __device__ __forceinline__ void pruned_elem(float& zv, float& av, int phase, flo
   }
 }
 
+// rowsums (phase 2 only, may be null): the scoring sums of the row's NEW state, [0][j] = sum A^2 and, when Z0 is
+// given, [1][j] = sum A relu(Z0), [2][j] = sum Z0 Z, [3][j] = sum Z0^2, so that the next selection does not have
+// to stream the pruned rows again.
 __global__ __launch_bounds__(256) void pruned_rows_kernel(const uint8_t* mask, float* Z, float* A, long long lda, long long T, int phase,
-                                                          float alpha, float beta, int write, double* red) {
+                                                          float alpha, float beta, int write, double* red, const float* Z0,
+                                                          double* rowsums, int rows) {
   const int j = blockIdx.x;
   double r0 = 0.0, r1 = 0.0;
-  if (!mask[j]) {
+  double sg = 0.0, se = 0.0, su = 0.0, sv = 0.0;
+  const bool pruned = !mask[j];
+  if (pruned) {
     float* z = Z + (long long)j * lda;
     float* a = A + (long long)j * lda;
+    const float* z0 = Z0 ? Z0 + (long long)j * lda : nullptr;
     const long long T4 = T >> 2;
     for (long long c = threadIdx.x; c < T4; c += 256) {
       float4 zv = ((const float4*)z)[c];
@@ -143,28 +150,64 @@ __global__ __launch_bounds__(256) void pruned_rows_kernel(const uint8_t* mask, f
       pruned_elem(zv.w, av.w, phase, alpha, beta, write, r0, r1);
       if (phase != 1) ((float4*)a)[c] = av;
       if (phase != 0 && write) ((float4*)z)[c] = zv;
+      if (rowsums) {
+        const float aa[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) sg = __builtin_fma((double)aa[q], (double)aa[q], sg);
+        if (z0) {
+          const float4 w = ((const float4*)z0)[c];
+          const float wa[4] = {w.x, w.y, w.z, w.w}, za[4] = {zv.x, zv.y, zv.z, zv.w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const double z0d = wa[q];
+            se = __builtin_fma((double)aa[q], fmax(z0d, 0.0), se);
+            su = __builtin_fma(z0d, (double)za[q], su);
+            sv = __builtin_fma(z0d, z0d, sv);
+          }
+        }
+      }
     }
     for (long long t = T4 * 4 + threadIdx.x; t < T; t += 256) {
       float zv = z[t], av = phase == 1 ? a[t] : 0.0f;
       pruned_elem(zv, av, phase, alpha, beta, write, r0, r1);
       if (phase != 1) a[t] = av;
       if (phase != 0 && write) z[t] = zv;
+      if (rowsums) {
+        sg = __builtin_fma((double)av, (double)av, sg);
+        if (z0) {
+          const double z0d = z0[t];
+          se = __builtin_fma((double)av, fmax(z0d, 0.0), se);
+          su = __builtin_fma(z0d, (double)zv, su);
+          sv = __builtin_fma(z0d, z0d, sv);
+        }
+      }
     }
   }
-  if (red) {
-    __shared__ double sh[4][2];
+  if (red || rowsums) {
+    __shared__ double sh[4][6];
     for (int o = 32; o > 0; o >>= 1) {
       r0 += __shfl_down(r0, o, 64);
       r1 += __shfl_down(r1, o, 64);
+      if (rowsums) {
+        sg += __shfl_down(sg, o, 64);
+        se += __shfl_down(se, o, 64);
+        su += __shfl_down(su, o, 64);
+        sv += __shfl_down(sv, o, 64);
+      }
     }
     if ((threadIdx.x & 63) == 0) {
-      sh[threadIdx.x >> 6][0] = r0;
-      sh[threadIdx.x >> 6][1] = r1;
+      double* w = sh[threadIdx.x >> 6];
+      w[0] = r0; w[1] = r1; w[2] = sg; w[3] = se; w[4] = su; w[5] = sv;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-      red[2 * (long long)j] = sh[0][0] + sh[1][0] + sh[2][0] + sh[3][0];
-      red[2 * (long long)j + 1] = sh[0][1] + sh[1][1] + sh[2][1] + sh[3][1];
+    if (threadIdx.x < 6) {
+      const int q = threadIdx.x;
+      const double t = sh[0][q] + sh[1][q] + sh[2][q] + sh[3][q];
+      if (q < 2) {
+        if (red) red[2 * (long long)j + q] = t;
+      } else if (rowsums && pruned && (q == 2 || Z0)) {
+        rowsums[(long long)(q - 2) * rows + j] = t;
+      }
     }
   }
 }
@@ -348,7 +391,7 @@ strp_status strp_score_alloc(strp_ctx* ctx, const strp_score_in* in, float* unit
     STRP_TRY(launch_colnorm2(ctx, in->What, in->w_dtype, in->w_rows, in->n_channels, in->ldw, n2buf));
     n2 = n2buf;
   }
-  STRP_TRY(launch_row_sums(ctx, in->A, in->a_dtype, in->Z, in->Z0, in->ld, in->T, in->n_channels, in->mode, sums));
+  STRP_TRY(launch_row_sums(ctx, in->A, in->a_dtype, in->Z, in->Z0, in->ld, in->T, in->n_channels, in->mode, sums, nullptr, nullptr, 0));
   STRP_TRY(launch_unit_scores(ctx, sums, n2, in->n_channels, in->group, in->mode, unit_score, energies + layer_idx));
   if (r_out) STRP_TRY(launch_alloc(ctx, energies, L, n_units, group_id, rbar, temperature, rmax, 0, r_out, nprune_out));
   return STRP_OK;
@@ -547,12 +590,15 @@ static strp_status ridge_solve(strp_ctx* ctx, Arena& arena, const RefitIn& in, d
 // Y as ROW planes, X as ROW planes and as K8 planes.
 struct CacheView {
   int nx, ny;
+  double* rowsums;     // [4][f] scoring sums of the pruned rows, valid as strp_module_state::sums_cached says
   PlaneOp Yt, Xt, Xc;   // Y and X for token-contraction products; X for the channel-contraction product W1 X
 };
 static size_t cache_layout(const strp_module_desc* desc, int prec, char* base, CacheView* v) {
   const long long d = desc->d, T = desc->T;
   const int nx = planes_for(desc->x_dtype, prec), ny = planes_for(STRP_F32, prec);
   size_t off = 256;
+  double* rowsums = (double*)(base ? base + off : nullptr);
+  off += ((size_t)desc->f * 4 * sizeof(double) + 255) & ~size_t(255);
   auto take = [&](size_t elems) {
     char* p = base ? base + off : nullptr;
     off += (elems * 2 + 255) & ~size_t(255);
@@ -566,6 +612,7 @@ static size_t cache_layout(const strp_module_desc* desc, int prec, char* base, C
   unsigned short* kl = nx == 2 ? take(plane_elems(T, d)) : nullptr;
   if (v) {
     v->nx = nx; v->ny = ny;
+    v->rowsums = rowsums;
     v->Yt = PlaneOp{yh, yl, plane_kg(T), (int)((d + 127) / 128), nullptr};
     v->Xt = PlaneOp{xh, xl, plane_kg(T), (int)((d + 127) / 128), nullptr};
     v->Xc = PlaneOp{kh, kl, plane_kg(d), (int)((T + 127) / 128), nullptr};
@@ -757,6 +804,7 @@ strp_status strp_module_init(strp_ctx* ctx, const strp_module_desc* desc, strp_m
   STRP_HIP(ctx, hipGetLastError());
   st->s = 0;
   st->iter = 0;
+  st->sums_cached = 0;
   return STRP_OK;
 }
 
@@ -790,11 +838,16 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   if (do_select) {
     Arena a2 = arena;
     STRP_TAKE(ctx, a2, sums, double, 4 * (size_t)f);
-    STRP_TRY(launch_row_sums(ctx, st->A, STRP_F32, st->Z, st->Z0, lda, T, f, params->mode, sums));
+    // rows pruned by the previous iteration had their sums accumulated while that iteration wrote them
+    const bool cached = st->sums_cached >= (params->mode == STRP_SCORE_WANDA ? 1 : 2) && st->s > 0;
+    STRP_TRY(launch_row_sums(ctx, st->A, STRP_F32, st->Z, st->Z0, lda, T, f, params->mode, sums, cached ? st->mask : nullptr,
+                             cached ? cv.rowsums : nullptr, cached ? f - st->s : 0));
     STRP_TRY(launch_unit_scores(ctx, sums, st->n2, f, 1, params->mode, st->score, sc + SC_ENERGY));
     STRP_TRY(launch_topk(ctx, st->score, f, params->k, 1, st->mask, st->idx, (float*)(sc + SC_TAU), nullptr, 0));
     st->s = params->k;
   }
+  // the cached sums describe the state and the mask as the last iteration left them: void them before either changes
+  if (do_select || (stages & (STRP_STAGE_AUPD | STRP_STAGE_ZUPD))) st->sums_cached = 0;
   const int s = st->s;
   const long long sp = round_up(s, 8);
 
@@ -932,7 +985,8 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     }
     if (!fuse_pruned) {
       ProfScope ps(ctx, "pruned_rows_a", 0.0, 8.0 * (double)(f - s) * (double)T);
-      hipLaunchKernelGGL(pruned_rows_kernel, dim3(f), dim3(256), 0, ctx->stream, st->mask, st->Z, st->A, lda, T, 0, alpha, beta, 1, (double*)nullptr);
+      hipLaunchKernelGGL(pruned_rows_kernel, dim3(f), dim3(256), 0, ctx->stream, st->mask, st->Z, st->A, lda, T, 0, alpha, beta, 1, (double*)nullptr,
+                         (const float*)nullptr, (double*)nullptr, f);
     }
   }
   // ---- S8 (+ objective terms 2, 3): z-update fused on Z1 = W1 X --------------------------------
@@ -953,8 +1007,11 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     STRP_TRY(launch_block_sum(ctx, red, nb, sc + SC_TMP0, sc + SC_TMP1, 1.0, 1.0));
     {
       ProfScope ps(ctx, fuse_pruned ? "pruned_rows_az" : "pruned_rows_z", 0.0, (fuse_pruned ? 12.0 : 8.0) * (double)(f - s) * (double)T);
+      const bool keep_sums = fuse_pruned && zupd;   // the rows are in registers in their final state: sum them for the next selection
+      const float* z0_for_sums = params->mode == STRP_SCORE_WANDA ? nullptr : st->Z0;
       hipLaunchKernelGGL(pruned_rows_kernel, dim3(f), dim3(256), 0, ctx->stream, st->mask, st->Z, st->A, lda, T, fuse_pruned ? 2 : 1, alpha, beta,
-                         zupd ? 1 : 0, red);
+                         zupd ? 1 : 0, red, keep_sums ? z0_for_sums : nullptr, keep_sums ? cv.rowsums : nullptr, f);
+      if (keep_sums) st->sums_cached = z0_for_sums ? 2 : 1;
     }
     STRP_TRY(launch_block_sum(ctx, red, f, sc + SC_TMP2, sc + SC_TMP3, 1.0, 1.0));
     hipLaunchKernelGGL(axpby_scalar_kernel, dim3(1), dim3(1), 0, ctx->stream, sc, (int)SC_T2, params->beta / (double)T, (int)SC_TMP0, params->beta / (double)T, (int)SC_TMP2);

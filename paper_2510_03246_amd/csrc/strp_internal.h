@@ -182,8 +182,11 @@ strp_status f32_to_f64_ridge(strp_ctx* ctx, const float* Af, long long ldf, doub
                              double lam, const double* lam_dev);
 
 // ---- reductions, scores, allocation, select (score_select.hip) ------------------------------
+// cached (optional, fp32 A only): rows with kept_mask[r] == 0 take their sums from cached[4][rows] instead of
+// being streamed; n_cached = number of such rows (for the traffic figure of the timing record)
 strp_status launch_row_sums(strp_ctx* ctx, const void* A, int a_dtype, const float* Z, const float* Z0,
-                            long long ld, long long T, int rows, int mode, double* sums /*[4][rows]*/);
+                            long long ld, long long T, int rows, int mode, double* sums /*[4][rows]*/,
+                            const uint8_t* kept_mask, const double* cached, int n_cached);
 strp_status launch_colnorm2(strp_ctx* ctx, const void* W, int w_dtype, int rows, int cols, long long ldw,
                             double* n2);
 strp_status launch_unit_scores(strp_ctx* ctx, const double* sums, const double* n2, int n_channels, int group,

@@ -51,7 +51,8 @@ class ModuleState(C.Structure):
     _fields_ = [("X", C.c_void_p), ("W1hat", C.c_void_p), ("W2hat", C.c_void_p), ("Z", C.c_void_p), ("A", C.c_void_p),
                 ("Z0", C.c_void_p), ("Y", C.c_void_p), ("W1", C.c_void_p), ("W2", C.c_void_p), ("H", C.c_void_p),
                 ("cholH", C.c_void_p), ("n2", C.c_void_p), ("score", C.c_void_p), ("mask", C.c_void_p),
-                ("idx", C.c_void_p), ("scalars", C.c_void_p), ("cache", C.c_void_p), ("s", C.c_int32), ("iter", C.c_int32)]
+                ("idx", C.c_void_p), ("scalars", C.c_void_p), ("cache", C.c_void_p), ("s", C.c_int32), ("iter", C.c_int32),
+                ("sums_cached", C.c_int32)]
 
 
 class Params(C.Structure):

@@ -414,6 +414,7 @@ def test_teacher_forced_stages_medium(ctx, mode):
         mod.mask.copy_(torch.from_numpy(st.mask).cuda())
         mod.idx[: st.idx.shape[0]] = torch.from_numpy(st.idx.astype(np.int32)).cuda()
         mod.state.s = int(st.idx.shape[0])
+        mod.state.sums_cached = 0   # the state was changed from outside
 
     upload()
     # select
@@ -465,6 +466,44 @@ def test_free_running_reselect_medium(ctx):
         assert abs(rep.J_ridge - float(np.sum(terms))) <= TOL_J * float(np.sum(terms))
     err = _compare_state(mod, st, T)
     assert max(err.values()) < TOL_F, err
+
+
+@pytest.mark.parametrize("mode,level", [(strp.WANDA, 1), (strp.GAIN, 2), (strp.LEMMA, 2)])
+def test_cached_sums_of_pruned_rows_match_streamed_sums(ctx, mode, level):
+    """The scoring sums a full iteration keeps for the rows it pruned give the same scores and mask as streaming
+    every row again, and the oracle's scores (ragged T: vector body and scalar tail of the row loop)."""
+    base = inputs.CONFIGS["opt125m"]
+    d, f, T, k = 136, 520, 1003, 200
+    cfg = type(base)(**{**base.__dict__, "d": d, "f": f, "T": T, "n_outlier": 2})
+    m = inputs.make_ffn_module(cfg, 0, 7, "cuda", ld=(T + 7) // 8 * 8)
+    mod = strp.FFNModule(ctx, m["W1hat"], m["W2hat"], m["X"], T)
+    p = _params(k, mode, reselect=1)
+    mod.init(p)
+    assert mod.state.sums_cached == 0
+    st = orc.module_init(m["W1hat"].double().cpu().numpy(), m["W2hat"].double().cpu().numpy(), m["X"][:, :T].double().cpu().numpy())
+    omode = {strp.WANDA: orc.WANDA, strp.GAIN: orc.GAIN, strp.LEMMA: orc.LEMMA}[mode]
+    for it in range(2):
+        mod.step(p)
+        orc.admm_step(st, k, 1.0, 1.0, omode, select=True)
+    assert mod.state.sums_cached == level
+    old_mask = mod.mask.clone()
+    sel = _params(k, mode, reselect=1, stages=strp.STAGE_SELECT)
+    mod.step(sel)                       # pruned rows from the cache
+    assert mod.state.sums_cached == 0   # a selection voids it
+    score_cached, mask_cached = mod.score.clone(), mod.mask.clone()
+    mod.mask.copy_(old_mask)
+    mod.step(sel)                       # every row streamed
+    assert torch.allclose(score_cached, mod.score, rtol=1e-6, atol=0)
+    assert torch.equal(mask_cached, mod.mask)
+    score = orc.module_scores(st, omode)
+    assert np.allclose(mod.score.cpu().numpy(), score, rtol=5e-3, atol=5e-3 * float(np.abs(score).max()))
+    # a selection in another mode must not use sums the cache does not hold
+    mod.step(p)
+    if level == 1:
+        mod.step(_params(k, strp.GAIN, reselect=1, stages=strp.STAGE_SELECT))
+        orc.admm_step(st, k, 1.0, 1.0, omode, select=True)
+        score = orc.module_scores(st, orc.GAIN)
+        assert np.allclose(mod.score.cpu().numpy(), score, rtol=5e-3, atol=5e-3 * float(np.abs(score).max()))
 
 
 @pytest.mark.parametrize("name,d,f,T,k,dt", [("all kept", 72, 264, 520, 264, "bf16"), ("k=8", 136, 520, 1003, 8, "bf16"),
