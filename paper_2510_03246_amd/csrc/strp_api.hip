@@ -140,10 +140,8 @@ __global__ __launch_bounds__(256) void pruned_rows_kernel(const uint8_t* mask, f
     float* a = A + (long long)j * lda;
     const float* z0 = Z0 ? Z0 + (long long)j * lda : nullptr;
     const long long T4 = T >> 2;
-    for (long long c = threadIdx.x; c < T4; c += 256) {
-      float4 zv = ((const float4*)z)[c];
-      float4 av = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (phase == 1) av = ((const float4*)a)[c];
+    // two independent 16-byte groups per thread and trip: all loads of a trip are issued before its first store
+    auto body = [&](long long c, float4 zv, float4 av, float4 w) {
       pruned_elem(zv.x, av.x, phase, alpha, beta, write, r0, r1);
       pruned_elem(zv.y, av.y, phase, alpha, beta, write, r0, r1);
       pruned_elem(zv.z, av.z, phase, alpha, beta, write, r0, r1);
@@ -155,7 +153,6 @@ __global__ __launch_bounds__(256) void pruned_rows_kernel(const uint8_t* mask, f
 #pragma unroll
         for (int q = 0; q < 4; ++q) sg = __builtin_fma((double)aa[q], (double)aa[q], sg);
         if (z0) {
-          const float4 w = ((const float4*)z0)[c];
           const float wa[4] = {w.x, w.y, w.z, w.w}, za[4] = {zv.x, zv.y, zv.z, zv.w};
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
@@ -166,7 +163,17 @@ __global__ __launch_bounds__(256) void pruned_rows_kernel(const uint8_t* mask, f
           }
         }
       }
+    };
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    long long c = threadIdx.x;
+    for (; c + 256 < T4; c += 512) {
+      const float4 zv0 = ((const float4*)z)[c], zv1 = ((const float4*)z)[c + 256];
+      const float4 av0 = phase == 1 ? ((const float4*)a)[c] : zero4, av1 = phase == 1 ? ((const float4*)a)[c + 256] : zero4;
+      const float4 w0 = z0 ? ((const float4*)z0)[c] : zero4, w1 = z0 ? ((const float4*)z0)[c + 256] : zero4;
+      body(c, zv0, av0, w0);
+      body(c + 256, zv1, av1, w1);
     }
+    if (c < T4) body(c, ((const float4*)z)[c], phase == 1 ? ((const float4*)a)[c] : zero4, z0 ? ((const float4*)z0)[c] : zero4);
     for (long long t = T4 * 4 + threadIdx.x; t < T; t += 256) {
       float zv = z[t], av = phase == 1 ? a[t] : 0.0f;
       pruned_elem(zv, av, phase, alpha, beta, write, r0, r1);
