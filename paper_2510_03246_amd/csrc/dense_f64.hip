@@ -178,13 +178,23 @@ __device__ __forceinline__ double rsqrt_f64(double d) {
 //   a_ik -= sum_c (p_c(i) / d_c) p_c(k)            (unpredicated: entries of finished columns are never re-read)
 //   V_i. -= sum_c (p_c(i) / d_c) q_c(.)  for i > j0 + c,   q_c = row j0 + c of the inverse, eliminated likewise
 // so that V ends as Lu^-1 and L^-1 = D^-1/2 Lu^-1.  Column j0 + c of L is p_c(i) d_c^-1/2.
-__global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld, int jb, double* invd, int32_t* status) {
-  __shared__ double Lm[NB][NB + 1];   // factor, entries on and below the diagonal
-  __shared__ double colb[2][4][NB];
-  __shared__ double rowb[2][4][NB];
-  __shared__ double rsd[NB];          // d_j^-1/2
+struct PotrfShared {
+  double Lm[NB][NB + 1];   // factor, entries on and below the diagonal
+  double colb[2][4][NB];
+  double rowb[2][4][NB];
+  double rsd[NB];          // d_j^-1/2
+};
+
+// On return (after its closing barrier): sh.Lm holds the factor, sh.rsd the inverse square roots of the pivots and
+// v the unit-lower inverse (L^-1 = diag(rsd) v) at this thread's 16 positions.  report: this block raises ENOTPD.
+__device__ __forceinline__ void potrf_block(const double* A, long long ld, int jb, PotrfShared& sh, double (&v)[4][4], int32_t* status,
+                                            bool report) {
+  auto& Lm = sh.Lm;
+  auto& colb = sh.colb;
+  auto& rowb = sh.rowb;
+  auto& rsd = sh.rsd;
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
-  double a[4][4], v[4][4];
+  double a[4][4];
 #pragma unroll
   for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
@@ -193,8 +203,13 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld
       a[ii][kk] = (i < jb && k <= i) ? A[(long long)i * ld + k] : ((i == k) ? 1.0 : 0.0);
       v[ii][kk] = (i == k) ? 1.0 : 0.0;
     }
-  for (int j0 = 0; j0 < NB; j0 += 4) {
-    const int buf = (j0 >> 2) & 1, lo16 = j0 & 15, hi = j0 >> 4;
+  // rounds j0 = 16 hi + lo16: the outer loop is unrolled so that the register rows and columns a round publishes
+  // (index hi) are compile-time choices
+#pragma unroll
+  for (int hi = 0; hi < 4; ++hi)
+#pragma unroll 1
+  for (int lo16 = 0; lo16 < 16; lo16 += 4) {
+    const int j0 = 16 * hi + lo16, buf = (j0 >> 2) & 1;
     if (tx >= lo16 && tx < lo16 + 4) {      // owners of columns j0 .. j0+3 publish them (rows ty + 16 ii)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
@@ -220,29 +235,28 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld
     bool ok = true;
     double rs[4], id[4];
     ok = ok && D00 > 0.0;
-    rs[0] = D00 > 0.0 ? rsqrt_f64(D00) : 1.0;
+    rs[0] = rsqrt_f64(D00 > 0.0 ? D00 : 1.0);
     id[0] = rs[0] * rs[0];
     const double u10 = D10 * id[0], u20 = D20 * id[0], u30 = D30 * id[0];
     const double E11 = D11 - D10 * u10, E21 = D21 - D20 * u10, E31 = D31 - D30 * u10;
     ok = ok && E11 > 0.0;
-    rs[1] = E11 > 0.0 ? rsqrt_f64(E11) : 1.0;
+    rs[1] = rsqrt_f64(E11 > 0.0 ? E11 : 1.0);
     id[1] = rs[1] * rs[1];
     const double u21 = E21 * id[1], u31 = E31 * id[1];
     const double F22 = D22 - D20 * u20 - E21 * u21, F32 = D32 - D30 * u20 - E31 * u21;
     ok = ok && F22 > 0.0;
-    rs[2] = F22 > 0.0 ? rsqrt_f64(F22) : 1.0;
+    rs[2] = rsqrt_f64(F22 > 0.0 ? F22 : 1.0);
     id[2] = rs[2] * rs[2];
     const double u32 = F32 * id[2];
     const double G33 = D33 - D30 * u30 - E31 * u31 - F32 * u32;
     ok = ok && G33 > 0.0;
-    rs[3] = G33 > 0.0 ? rsqrt_f64(G33) : 1.0;
+    rs[3] = rsqrt_f64(G33 > 0.0 ? G33 : 1.0);
     id[3] = rs[3] * rs[3];
     if (tid == 0) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) rsd[j0 + c] = rs[c];
-      if (!ok && j0 + 3 < jb) atomicCAS(status, 0, (int)STRP_ENOTPD);
-      else if (!ok) {   // ragged block: only pivots inside jb count (the padding is the identity)
-        const bool bad = (0 < jb - j0 && !(D00 > 0.0)) || (1 < jb - j0 && !(E11 > 0.0)) || (2 < jb - j0 && !(F22 > 0.0));
+      if (report && !ok) {   // in a ragged block only the pivots inside jb count (the padding is the identity)
+        const bool bad = j0 + 3 < jb || (0 < jb - j0 && !(D00 > 0.0)) || (1 < jb - j0 && !(E11 > 0.0)) || (2 < jb - j0 && !(F22 > 0.0));
         if (bad) atomicCAS(status, 0, (int)STRP_ENOTPD);
       }
     }
@@ -260,16 +274,16 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld
       pk[2][q] = cb[2][xk] - pk[0][q] * u20 - pk[1][q] * u21;
       pk[3][q] = cb[3][xk] - pk[0][q] * u30 - pk[1][q] * u31 - pk[2][q] * u32;
     }
-    // column j0 + c of the factor: thread (ty, tx = c) holds it for rows ty + 16 ii
+    // column j0 + c of the factor: thread (ty, tx = c) writes it for rows ty + 16 ii (entries above the diagonal are
+    // written too and never read)
+    if (report && tx < 4) {   // only the block that stores the factor needs it
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
-      if (tx == c) {
-#pragma unroll
-        for (int ii = 0; ii < 4; ++ii) {
-          const int row = ty + 16 * ii;
-          if (row >= j0 + c) Lm[row][j0 + c] = pi[c][ii] * rs[c];
-        }
+      for (int ii = 0; ii < 4; ++ii) {
+        const double pc = tx == 0 ? pi[0][ii] : tx == 1 ? pi[1][ii] : tx == 2 ? pi[2][ii] : pi[3][ii];
+        const double rc = tx == 0 ? rs[0] : tx == 1 ? rs[1] : tx == 2 ? rs[2] : rs[3];
+        Lm[ty + 16 * ii][j0 + tx] = pc * rc;
       }
+    }
     // rows j0 + c of the inverse, eliminated among themselves, at this thread's columns
     const double (*rb)[NB] = rowb[buf];
     double qk[4][4];
@@ -298,64 +312,82 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* A, long long ld
     }
   }
   __syncthreads();
+}
+
+// One 64-column step of the factorisation in one launch.  Every block factors the (already updated) diagonal block
+// itself -- the chip is idle during these steps, and a separate one-block launch would only add a kernel boundary to
+// the critical path.  Block 0 stores the factor and its inverse; block b >= 1 multiplies rows [64 (b-1), +64) of the
+// panel below the diagonal block by L^-T in place.
+__global__ __launch_bounds__(256) void potrf_panel_kernel(double* Ajj, long long ld, int jb, int rest, double* invd, int32_t* status) {
+  __shared__ PotrfShared sh;
+  __shared__ double Ms[NB][NB + 1];   // Ms[k][c] = Linv[c][k]
+  __shared__ double Xs[NB][NB + 1];
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int b = blockIdx.x;
+  double* X = Ajj + (long long)jb * ld;          // panel below the diagonal block
+  const int r0 = (b - 1) * NB;
+  // this block's panel rows, requested before the factorisation so that their latency hides behind it
+  double xr[16];
+  if (b > 0) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int e = tid + 256 * q, i = e >> 6, j = e & 63;
+      xr[q] = (r0 + i < rest && j < jb) ? X[(long long)(r0 + i) * ld + j] : 0.0;
+    }
+  }
+  double v[4][4];
+  potrf_block(Ajj, ld, jb, sh, v, status, b == 0);
+  if (b == 0) {
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const int i = ty + 16 * ii, k = tx + 16 * kk;
+        const bool in = i < jb && k < jb;
+        invd[i * NB + k] = (in && k <= i) ? v[ii][kk] * sh.rsd[i] : 0.0;
+        if (in) Ajj[(long long)i * ld + k] = (k <= i) ? sh.Lm[i][k] : 0.0;
+      }
+    return;
+  }
 #pragma unroll
   for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       const int i = ty + 16 * ii, k = tx + 16 * kk;
-      const bool in = i < jb && k < jb;
-      invd[i * NB + k] = (in && k <= i) ? v[ii][kk] * rsd[i] : 0.0;
-      if (in) A[(long long)i * ld + k] = (k <= i) ? Lm[i][k] : 0.0;
+      Ms[k][i] = (i < jb && k <= i) ? v[ii][kk] * sh.rsd[i] : 0.0;
     }
-}
-
-// X[rows x jb] <- X * Mt, Mt[k][c] = trans ? Linv[c][k] : Linv[k][c]; one block per 64 rows
-__global__ __launch_bounds__(256) void panel_mul_kernel(double* X, long long ldx, int rows, int jb, const double* invd,
-                                                        int trans) {
-  __shared__ double Xs[NB][NB + 1];
-  __shared__ double Ms[NB][NB + 1];
-  const int tid = threadIdx.x, r0 = blockIdx.x * NB;
-  for (int e = tid; e < NB * NB; e += 256) {
-    const int i = e >> 6, j = e & 63;
-    Xs[i][j] = (r0 + i < rows && j < jb) ? X[(long long)(r0 + i) * ldx + j] : 0.0;
-    Ms[i][j] = trans ? invd[j * NB + i] : invd[e];
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    const int e = tid + 256 * q;
+    Xs[e >> 6][e & 63] = xr[q];
   }
   __syncthreads();
-  const int tx = tid & 15, ty = tid >> 4;
   double acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
   for (int k = 0; k < jb; ++k) {
-    double a[4], b[4];
+    double a[4], bb[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) a[i] = Xs[ty * 4 + i][k];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) b[j] = Ms[k][tx * 4 + j];
+    for (int j = 0; j < 4; ++j) bb[j] = Ms[k][tx * 4 + j];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fma(a[i], b[j], acc[i][j]);
+      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fma(a[i], bb[j], acc[i][j]);
   }
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int r = r0 + ty * 4 + i;
-    if (r >= rows) continue;
+    if (r >= rest) continue;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int c = tx * 4 + j;
-      if (c < jb) X[(long long)r * ldx + c] = acc[i][j];
+      if (c < jb) X[(long long)r * ld + c] = acc[i][j];
     }
   }
-}
-
-static strp_status panel_mul(strp_ctx* ctx, double* X, long long ldx, int rows, int jb, const double* invd, int trans) {
-  if (rows <= 0) return STRP_OK;
-  hipLaunchKernelGGL(panel_mul_kernel, dim3((rows + NB - 1) / NB), dim3(256), 0, ctx->stream, X, ldx, rows, jb, invd,
-                     trans);
-  STRP_HIP(ctx, hipGetLastError());
-  return STRP_OK;
 }
 
 // Two-level right-looking blocking: 64-column steps (diagonal block + panel) update only the rest of their
@@ -370,12 +402,11 @@ strp_status chol_factor(strp_ctx* ctx, double* A, int n, long long ld, double* i
       const int jb = (n - j0 < NB) ? (n - j0) : NB;
       double* Ajj = A + (long long)j0 * ld + j0;
       double* inv = invd + (long long)(j0 / NB) * NB * NB;
-      hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(256), 0, ctx->stream, Ajj, ld, jb, inv, status);
-      STRP_HIP(ctx, hipGetLastError());
       const int rest = n - j0 - jb;
+      hipLaunchKernelGGL(potrf_panel_kernel, dim3(1 + (rest + NB - 1) / NB), dim3(256), 0, ctx->stream, Ajj, ld, jb, rest, inv, status);
+      STRP_HIP(ctx, hipGetLastError());
       if (rest <= 0) continue;
       double* A21 = A + (long long)(j0 + jb) * ld + j0;
-      STRP_TRY(panel_mul(ctx, A21, ld, rest, jb, inv, 1));
       const int pc = Jend - (j0 + jb);   // columns of the outer panel still to be factored
       if (pc > 0) {
         double* A22 = A + (long long)(j0 + jb) * ld + (j0 + jb);
