@@ -247,4 +247,56 @@ strp_status weight_scale(strp_ctx* ctx, const void* src, int src_kind, long long
   return STRP_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// One fp16 plane with k = channel, r = token  ->  the same values as a plane with k = token, r = channel.
+// A block moves 128 tokens x 128 channels: both its source (16 k-groups of one token panel) and its destination
+// (16 k-groups of one channel panel) are contiguous 32 KB runs; the 2-byte transposition happens in LDS.
+// Tokens >= T are written as zero (they are contraction padding on the output side).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void plane_c_to_t_kernel(const unsigned short* src, unsigned short* dst, int C, long long T,
+                                                           long long kg_src, long long kg_dst) {
+  constexpr int GS = 1024 + 8;                    // elements per source k-group in LDS (+16 B against bank conflicts)
+  __shared__ __attribute__((aligned(16))) unsigned short sm[16 * GS];
+  const int tid = threadIdx.x;
+  const long long pt = blockIdx.x;                // token panel
+  const int pc = blockIdx.y;                      // channel panel
+  // load: source k-groups 16 pc .. 16 pc + 15 (those below kg_src) of token panel pt
+  for (int q = tid; q < 2048; q += 256) {
+    const int g = q >> 7, piece = q & 127;        // 128 16-byte pieces (one token each) per k-group
+    const long long cg = (long long)pc * 16 + g;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (cg < kg_src) v = *(const uint4*)(src + ((pt * kg_src + cg) * 128 + piece) * 8);
+    *(uint4*)(sm + g * GS + piece * 8) = v;
+  }
+  __syncthreads();
+  // store: destination k-groups 16 pt .. 16 pt + 15 (those below kg_dst) of channel panel pc
+  for (int q = tid; q < 2048; q += 256) {
+    const int tg = q >> 7, cl = q & 127;          // piece = channel cl, token group tg
+    const long long tgg = pt * 16 + tg;
+    if (tgg >= kg_dst) continue;
+    const unsigned short* col = sm + (cl >> 3) * GS + (cl & 7);
+    unsigned short e[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const long long t = tgg * 8 + j;
+      e[j] = t < T ? col[(tg * 8 + j) * 8] : (unsigned short)0;
+    }
+    uint4 v;
+    v.x = e[0] | ((unsigned)e[1] << 16);
+    v.y = e[2] | ((unsigned)e[3] << 16);
+    v.z = e[4] | ((unsigned)e[5] << 16);
+    v.w = e[6] | ((unsigned)e[7] << 16);
+    *(uint4*)(dst + (((long long)pc * kg_dst + tgg) * 128 + cl) * 8) = v;
+  }
+  (void)C;
+}
+
+strp_status plane_c_to_t(strp_ctx* ctx, const unsigned short* src, unsigned short* dst, int C, long long T) {
+  ProfScope ps(ctx, "plane_c_to_t", 0.0, 4.0 * (double)C * (double)T);
+  dim3 grid((unsigned)((T + 127) / 128), (unsigned)((C + 127) / 128));
+  hipLaunchKernelGGL(plane_c_to_t_kernel, grid, dim3(256), 0, ctx->stream, src, dst, C, T, plane_kg(C), plane_kg(T));
+  STRP_HIP(ctx, hipGetLastError());
+  return STRP_OK;
+}
+
 }  // namespace strp

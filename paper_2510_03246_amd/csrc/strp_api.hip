@@ -233,6 +233,20 @@ __global__ __launch_bounds__(256) void sumsq_kernel(const float* x, long long n,
   }
 }
 
+// per-block partial of sum_i a[i] b[i] -> red[block][0] (red[block][1] = 0)
+__global__ __launch_bounds__(256) void dot_f32_f64_kernel(const float* a, const double* b, long long n, double* red) {
+  double acc = 0.0;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) acc = __builtin_fma((double)a[i], b[i], acc);
+  __shared__ double sh[4];
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o, 64);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    red[2 * (long long)blockIdx.x] = sh[0] + sh[1] + sh[2] + sh[3];
+    red[2 * (long long)blockIdx.x + 1] = 0.0;
+  }
+}
+
 // scalars[dst] = a * scalars[s0] + b * scalars[s1]   (one thread; keeps the objective assembly on device)
 __global__ void axpby_scalar_kernel(double* sc, int dst, double a, int s0, double b, int s1) {
   if (threadIdx.x == 0 && blockIdx.x == 0) sc[dst] = a * sc[s0] + (s1 >= 0 ? b * sc[s1] : 0.0);
@@ -657,12 +671,14 @@ size_t strp_workspace_bytes(const strp_module_desc* desc) {
   upd(nt_partial_elems((int)d, (int)km, T, 0));
   upd(nt_partial_elems((int)km, (int)d, T, 0));
   upd(nt_partial_elems((int)d, (int)d, (long long)kp, 1));
+  upd(nt_partial_elems((int)d, (int)d, T, 1));   // E E^T of the objective
   size_t step = 256 + al(4 * f * 8) + al(d * kp * 4) + al(km * d * 4) +
                 (al(256) + 2 * al(plane_elems(d, km) * 2)) + 2 * (al(256) + 2 * al(plane_elems(km, d) * 2)) +
                 al(part * 4) + 3 * al(nmax * nmax * 8) + 2 * al(invd_max) + al(d * km * 8) * 4 + 2 * al(d * d * 8) +
                 2 * al(plane_elems(km, T) * 2) /* kept rows, token contraction */ +
                 2 * al(plane_elems(T, km) * 2) /* kept rows, channel contraction */ +
                 2 * al(plane_elems(T, d) * 2) /* E */ + red +
+                al(plane_elems(d, T) * 2) + al(d * d * 8) + al(d * d * 4) /* objective: E by tokens, E E^T, M^-2 */ +
                 /* the M-inverse chain keeps its block while the fc1 refit runs beside it */
                 al(nt_partial_elems((int)d, (int)d, (long long)kp, 1) * 4) + al(d * d * 8) + al(invd_max) +
                 2 * (al(256) + 2 * al(plane_elems(km, d) * 2)) + (al(256) + 2 * al(plane_elems(d, d) * 2)) + al(plane_elems(T, km) * 2) + 8192;
@@ -893,10 +909,20 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   PlaneOp Bp;
   memset(&Bp, 0, sizeof(Bp));
   bool chain_forked = false;
+  // First objective term when the a-update runs in the same call: the update solves its least-squares problem exactly, so
+  //   Y - W A_S = E - W W^T M^-1 E = (M - W W^T) M^-1 E = (beta/alpha) M^-1 E,   E = Y - W relu(Z_S),
+  // and |Y - W A_S|_F^2 = (beta/alpha)^2 <M^-2, E E^T>: a d x d Gram of E over the tokens (half the work of the product
+  // W A_S) and two d x d matrices.  One fp16 plane of E is ample for a sum reported to 1e-3.
+  const bool term1_identity = (stages & STRP_STAGE_AUPD) && (stages & STRP_STAGE_OBJ);
+  float* M2f = nullptr;
   if (stages & STRP_STAGE_AUPD) {
     STRP_TAKE(ctx, arena, Md, double, (size_t)d * d);
     STRP_TAKE(ctx, arena, Linv, double, (size_t)d * d);
     STRP_TAKE(ctx, arena, Bf, float, (size_t)s * d);
+    if (term1_identity) {
+      STRP_TAKE(ctx, arena, m2, float, (size_t)d * d);
+      M2f = m2;
+    }
     const size_t al = 255;
     const size_t cbytes = ((nt_partial_elems(d, d, sp, 1) * 4 + al) & ~al) + (((size_t)((d + NB - 1) / NB) * NB * NB * 8 + al) & ~al) +
                           (((size_t)d * d * 8 + al) & ~al) + (512 + 2 * ((plane_elems(s, d) * 2 + al) & ~al)) +
@@ -926,6 +952,15 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
       p.epi = EPI_STORE; p.out = Bf; p.ldo = d;
       gemm_plan_tiles(p, 1);
       STRP_TRY(launch_gemm(ctx, p));
+      if (term1_identity) {   // M^-2 for the first objective term (see the a-update below)
+        GemmP q;
+        memset(&q, 0, sizeof(q));
+        q.P = Mi; q.Q = Mi;
+        q.M = d; q.N = d; q.K = d;
+        q.epi = EPI_STORE; q.out = M2f; q.ldo = d;
+        gemm_plan_tiles(q, 1);
+        STRP_TRY(launch_gemm(ctx, q));
+      }
     }
     STRP_TRY(make_weight_planes(ctx, arena, Bf, SRC_F32, d, s, d, 0, npa, &Bp));
   }
@@ -949,14 +984,7 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     STRP_TRY(make_weight_planes(ctx, arena, W1S, SRC_F32, d, s, d, 0, npa, &W1Sp));
   }
 
-  // A_S as single-plane operand of the objective product: written by the a-update epilogue when both stages run
-  const bool fuse_obj_planes = (stages & STRP_STAGE_AUPD) && (stages & STRP_STAGE_OBJ);
   const bool fuse_pruned = (stages & STRP_STAGE_AUPD) && (stages & STRP_STAGE_ZUPD);
-  unsigned short* akh = nullptr;
-  if (fuse_obj_planes) {
-    STRP_TAKE(ctx, arena, akh2, unsigned short, plane_elems(T, s));
-    akh = akh2;
-  }
   // ---- S7: a-update in residual (Woodbury) form ------------------------------------------------
   //   A_S = relu(Z_S) + W^T M^-1 (Y - W relu(Z_S)),  M = (beta/alpha) I + W W^T,  W = W2[:, S];  A_j = relu(Z_j) for pruned j
   if (stages & STRP_STAGE_AUPD) {
@@ -980,13 +1008,24 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
       gemm_plan_tiles(p, 1);
       STRP_TRY(launch_gemm(ctx, p));
     }
+    if (term1_identity) {   // (alpha/T) |Y - W A_S|^2 = (alpha/T) (beta/alpha)^2 <M^-2, E E^T>
+      Arena a3 = a2;
+      STRP_TAKE(ctx, a3, eth, unsigned short, plane_elems(d, T));
+      STRP_TAKE(ctx, a3, Sd, double, (size_t)d * d);
+      STRP_TAKE(ctx, a3, red, double, 2 * 1024);
+      STRP_TRY(plane_c_to_t(ctx, ekh, eth, d, T));
+      const PlaneOp Et{eth, nullptr, plane_kg(T), (int)((d + 127) / 128), nullptr};
+      STRP_TRY(nt_product(ctx, a3, Et, Et, d, d, T, 1, nullptr, 0, Sd, d, nullptr, 0));
+      hipLaunchKernelGGL(dot_f32_f64_kernel, dim3(1024), dim3(256), 0, ctx->stream, M2f, Sd, (long long)d * d, red);
+      const double c = params->beta / params->alpha;
+      STRP_TRY(launch_block_sum(ctx, red, 1024, sc + SC_T1, nullptr, params->alpha / (double)T * c * c, 1.0));
+    }
     {  // A_S = relu(Z_S) + B E
       GemmP p;
       memset(&p, 0, sizeof(p));
       p.P = Bp; p.Q = PlaneOp{ekh, ekl, plane_kg(d), (int)((T + 127) / 128), nullptr};
       p.M = s; p.N = (int)T; p.K = d;
       p.epi = EPI_AUPD; p.Zs = st->Z; p.As = st->A; p.lda = lda; p.oidx = st->idx;
-      p.k8_hi = akh; p.k8_lo = nullptr; p.k8_kg = plane_kg(s);
       gemm_plan_tiles(p, 1);
       STRP_TRY(launch_gemm(ctx, p));
     }
@@ -1027,23 +1066,23 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   // ---- S9: objective term 1 (one fp16 plane per operand is ample for a 1e-3 sum) and ridge terms ----
   if (stages & STRP_STAGE_OBJ) {
     Arena a2 = arena;
-    PlaneOp Ak8;
-    if (fuse_obj_planes) {
-      Ak8 = PlaneOp{akh, nullptr, plane_kg(s), (int)((T + 127) / 128), nullptr};
-    } else {
-      STRP_TRY(make_c_planes(ctx, a2, st->A, STRP_F32, lda, st->idx, s, T, 0, 1, &Ak8));
+    STRP_TAKE(ctx, a2, red, double, 2 * 1024);
+    if (!term1_identity) {   // A is whatever the caller left: the product itself
+      Arena a3 = a2;
+      PlaneOp Ak8;
+      STRP_TRY(make_c_planes(ctx, a3, st->A, STRP_F32, lda, st->idx, s, T, 0, 1, &Ak8));
+      GemmP p;
+      memset(&p, 0, sizeof(p));
+      p.P = W2Sp; p.P.lo = nullptr; p.Q = Ak8;
+      p.M = d; p.N = (int)T; p.K = s;
+      p.epi = EPI_RESID; p.Yin = st->Y; p.ldy = lda;
+      gemm_plan_tiles(p, 1);
+      const int nb = gemm_grid_blocks(p);
+      STRP_TAKE(ctx, a3, redg, double, 2 * (size_t)nb);
+      p.red = redg;
+      STRP_TRY(launch_gemm(ctx, p));
+      STRP_TRY(launch_block_sum(ctx, redg, nb, sc + SC_T1, nullptr, params->alpha / (double)T, 1.0));
     }
-    GemmP p;
-    memset(&p, 0, sizeof(p));
-    p.P = W2Sp; p.P.lo = nullptr; p.Q = Ak8;
-    p.M = d; p.N = (int)T; p.K = s;
-    p.epi = EPI_RESID; p.Yin = st->Y; p.ldy = lda;
-    gemm_plan_tiles(p, 1);
-    const int nb = gemm_grid_blocks(p);
-    STRP_TAKE(ctx, a2, red, double, 2 * (size_t)(nb > 1024 ? nb : 1024));
-    p.red = red;
-    STRP_TRY(launch_gemm(ctx, p));
-    STRP_TRY(launch_block_sum(ctx, red, nb, sc + SC_T1, nullptr, params->alpha / (double)T, 1.0));
     hipLaunchKernelGGL(sumsq_kernel, dim3(1024), dim3(256), 0, ctx->stream, W2S, (long long)d * sp, red);
     STRP_TRY(launch_block_sum(ctx, red, 1024, sc + SC_W2SQ, nullptr, 1.0, 1.0));
     hipLaunchKernelGGL(sumsq_kernel, dim3(1024), dim3(256), 0, ctx->stream, W1S, (long long)s * d, red);

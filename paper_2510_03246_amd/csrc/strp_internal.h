@@ -156,6 +156,9 @@ strp_status launch_block_sum(strp_ctx* ctx, const double* red, int nblocks, doub
 strp_status split_act(strp_ctx* ctx, const void* src, int src_dtype, long long lds, const int* idx, int rows, long long T,
                       int relu_t, int relu_c, unsigned short* t_hi, unsigned short* t_lo, unsigned short* c_hi,
                       unsigned short* c_lo);
+// One fp16 plane of a [C x T] quantity with k = channel, r = token (plane_elems(T, C)) -> the plane with k = token,
+// r = channel (plane_elems(C, T)); padding tokens zero.
+strp_status plane_c_to_t(strp_ctx* ctx, const unsigned short* src, unsigned short* dst, int C, long long T);
 // Small matrix (weights) -> planes with k = column, r = row: plane_elems(rows, cols); src_kind = SRC_*.
 strp_status split_small(strp_ctx* ctx, const void* src, int src_kind, long long lds, int rows, int cols, int transpose,
                         const float* scale_dev, unsigned short* hi, unsigned short* lo);

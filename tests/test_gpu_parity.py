@@ -468,6 +468,29 @@ def test_free_running_reselect_medium(ctx):
     assert max(err.values()) < TOL_F, err
 
 
+@pytest.mark.parametrize("alpha,beta", [(1.0, 1.0), (2.0, 0.5), (0.25, 3.0)])
+def test_first_objective_term_identity_matches_the_product(ctx, alpha, beta):
+    """A full iteration reports alpha/T |Y - W2 A|^2 through (beta/alpha)^2 <M^-2, E E^T> (valid because its a-update is
+    the exact minimiser); an objective-only call on the same state forms Y - W2 A itself.  Both must agree with each
+    other and with the oracle's definition (ragged T and d, several tiles)."""
+    base = inputs.CONFIGS["opt125m"]
+    d, f, T, k = 264, 1048, 3000, 419
+    cfg = type(base)(**{**base.__dict__, "d": d, "f": f, "T": T, "n_outlier": 3})
+    m = inputs.make_ffn_module(cfg, 0, 11, "cuda", ld=(T + 7) // 8 * 8)
+    mod = strp.FFNModule(ctx, m["W1hat"], m["W2hat"], m["X"], T)
+    p = _params(k, strp.WANDA, reselect=1, alpha=alpha, beta=beta)
+    mod.init(p)
+    st = orc.module_init(m["W1hat"].double().cpu().numpy(), m["W2hat"].double().cpu().numpy(), m["X"][:, :T].double().cpu().numpy())
+    for it in range(2):
+        rep = mod.step(p)
+        terms = orc.admm_step(st, k, alpha, beta, orc.WANDA, select=True)
+        assert rep.status == strp.OK
+        direct = mod.step(_params(k, strp.WANDA, stages=strp.STAGE_OBJ, alpha=alpha, beta=beta))
+        assert abs(rep.terms[0] - direct.terms[0]) <= 3e-4 * direct.terms[0], (it, rep.terms[0], direct.terms[0])
+        assert abs(rep.terms[0] - terms[0]) <= TOL_J * terms[0], (it, rep.terms[0], terms[0])
+        assert np.allclose(np.array(direct.terms[:]), np.array(rep.terms[:]), rtol=3e-4)
+
+
 @pytest.mark.parametrize("mode,level", [(strp.WANDA, 1), (strp.GAIN, 2), (strp.LEMMA, 2)])
 def test_cached_sums_of_pruned_rows_match_streamed_sums(ctx, mode, level):
     """The scoring sums a full iteration keeps for the rows it pruned give the same scores and mask as streaming
