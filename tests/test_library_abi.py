@@ -47,3 +47,22 @@ def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(strp, "LIB_PATH", "/nonexistent/libstrp.so")
     with pytest.raises(FileNotFoundError):
         strp.load_library()
+
+
+def test_binding_structs_mirror_the_header(tmp_path):
+    """Size and last-field offset of every struct the binding marshals, as the C compiler lays the header out."""
+    import subprocess
+    from paper_2510_03246_amd import strp
+    pairs = [("strp_module_desc", "k_max", strp.ModuleDesc), ("strp_score_in", "ldw", strp.ScoreIn),
+             ("strp_module_state", "sums_cached", strp.ModuleState), ("strp_params", "stages", strp.Params),
+             ("strp_report", "status", strp.Report), ("strp_weight_ref", "ld", strp.WeightRef)]
+    src = tmp_path / "layout.c"
+    body = "".join(f'  printf("%zu %zu\\n", sizeof({c}), offsetof({c}, {f}));\n' for c, f, _ in pairs)
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "strp.h"\nint main(void) {\n' + body + "  return 0;\n}\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)], check=True, timeout=120)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True, timeout=30).stdout.split("\n")
+    for (cname, field, cls), line in zip(pairs, out):
+        size, off = (int(x) for x in line.split())
+        assert ctypes.sizeof(cls) == size, cname
+        assert getattr(cls, field).offset == off, (cname, field)
