@@ -42,9 +42,14 @@ __device__ __forceinline__ void load4(const void* src, long long off, float (&v)
 // the 64 tokens of a row, a wavefront 4 rows) and drops the fp16 halves into an LDS image of the output
 // ([k-group][row][8], k-groups padded by one chunk against bank conflicts); phase 2 copies the image out linearly:
 // the block's output is one contiguous 16 KB run per plane.
-template <bool SRC_BF16>
+// WITH_C: the same pass also writes the C-planes of the block's 128 rows x 64 tokens from the LDS image (a chunk = one
+// token's 8 consecutive rows, gathered as 2-byte reads; a wavefront stores 64 consecutive tokens of one row group =
+// 1 KB contiguous).  relu_c on top of an image without relu: relu(x) has the planes of x where hi is not negative
+// and zero planes elsewhere (hi carries the sign of x, also when it rounds to zero).
+template <bool SRC_BF16, bool WITH_C>
 __global__ __launch_bounds__(256) void split_t_kernel(const void* src, long long lds, const int* idx, int rows, long long T,
-                                                      int relu, unsigned short* t_hi, unsigned short* t_lo, long long TGa) {
+                                                      int relu, unsigned short* t_hi, unsigned short* t_lo, long long TGa,
+                                                      int relu_c, unsigned short* c_hi, unsigned short* c_lo, int KGc) {
   constexpr int GP = 128 * 16 + 16;   // bytes per k-group in LDS
   __shared__ __attribute__((aligned(16))) unsigned char sh[8 * GP];
   __shared__ __attribute__((aligned(16))) unsigned char sl[8 * GP];
@@ -85,6 +90,30 @@ __global__ __launch_bounds__(256) void split_t_kernel(const void* src, long long
     const long long o = (((long long)pan * TGa + tg0 + g) * 128 + rr) * 8;
     *(uint4*)(t_hi + o) = *(const uint4*)(sh + g * GP + rr * 16);
     if (t_lo) *(uint4*)(t_lo + o) = *(const uint4*)(sl + g * GP + rr * 16);
+  }
+  if (WITH_C) {
+    const long long tok_c = tg0 * 8 + (t & 63);                  // this thread's token
+    if (tok_c < (((T + 127) >> 7) << 7)) {                        // inside the last token panel
+      const int tl = t & 63;
+      const unsigned char* bh = sh + (tl >> 3) * GP + (tl & 7) * 2;
+      const unsigned char* bl = sl + (tl >> 3) * GP + (tl & 7) * 2;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int g = (t >> 6) + 4 * j;                           // row group of the panel (8 rows)
+        const int rg = pan * 16 + g;
+        if (rg >= KGc) continue;
+        unsigned short h[8], l[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+          h[r] = *(const unsigned short*)(bh + (g * 8 + r) * 16);
+          l[r] = c_lo ? *(const unsigned short*)(bl + (g * 8 + r) * 16) : (unsigned short)0;
+          if (relu_c && (h[r] & 0x8000u)) h[r] = l[r] = 0;
+        }
+        const long long o = (((tok_c >> 7) * KGc + rg) * 128 + (tok_c & 127)) * 8;
+        *(uint4*)(c_hi + o) = make_uint4(sp_pack2(h[0], h[1]), sp_pack2(h[2], h[3]), sp_pack2(h[4], h[5]), sp_pack2(h[6], h[7]));
+        if (c_lo) *(uint4*)(c_lo + o) = make_uint4(sp_pack2(l[0], l[1]), sp_pack2(l[2], l[3]), sp_pack2(l[4], l[5]), sp_pack2(l[6], l[7]));
+      }
+    }
   }
 }
 
@@ -129,17 +158,30 @@ strp_status split_act(strp_ctx* ctx, const void* src, int src_dtype, long long l
   if (lds % 8 || lds < T) return fail(ctx, STRP_EINVAL, "split_act: source pitch must be a multiple of 8 and at least T");
   const double es = src_dtype == STRP_BF16 ? 2.0 : 4.0;
   const double wb = (t_hi ? 2.0 : 0.0) + (t_lo ? 2.0 : 0.0) + (c_hi ? 2.0 : 0.0) + (c_lo ? 2.0 : 0.0);
-  ProfScope ps(ctx, "split_act", 0.0, (es * ((t_hi ? 1.0 : 0.0) + (c_hi ? 1.0 : 0.0)) + wb) * (double)rows * (double)T);
+  const bool one_read = t_hi && c_hi && (relu_t == relu_c || !relu_t) && (t_lo != nullptr) == (c_lo != nullptr);
+  ProfScope ps(ctx, "split_act", 0.0, (es * (one_read ? 1.0 : (t_hi ? 1.0 : 0.0) + (c_hi ? 1.0 : 0.0)) + wb) * (double)rows * (double)T);
+  // both layouts of the same rows in one pass over the source when the C-planes can be derived from the T image
+  const bool fused = t_hi && c_hi && (relu_t == relu_c || !relu_t) && (t_lo != nullptr) == (c_lo != nullptr);
   if (t_hi) {
     const long long TGa = plane_kg(T);
-    dim3 grid((unsigned)((TGa + 7) / 8), (unsigned)((rows + 127) / 128));
-    if (src_dtype == STRP_BF16)
-      hipLaunchKernelGGL((split_t_kernel<true>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, t_hi, t_lo, TGa);
+    const int KGc = (int)plane_kg(rows);
+    const int rc = fused ? (relu_c && !relu_t) : 0;
+    // fused: the blocks reach the end of the last 128-token panel, whose padding the C-planes hold as zeros
+    const long long gx = fused ? 2 * ((T + 127) / 128) : (TGa + 7) / 8;
+    dim3 grid((unsigned)gx, (unsigned)((rows + 127) / 128));
+    if (fused && src_dtype == STRP_BF16)
+      hipLaunchKernelGGL((split_t_kernel<true, true>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, t_hi, t_lo, TGa, rc, c_hi, c_lo, KGc);
+    else if (fused)
+      hipLaunchKernelGGL((split_t_kernel<false, true>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, t_hi, t_lo, TGa, rc, c_hi, c_lo, KGc);
+    else if (src_dtype == STRP_BF16)
+      hipLaunchKernelGGL((split_t_kernel<true, false>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, t_hi, t_lo, TGa, 0,
+                         (unsigned short*)nullptr, (unsigned short*)nullptr, 0);
     else
-      hipLaunchKernelGGL((split_t_kernel<false>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, t_hi, t_lo, TGa);
+      hipLaunchKernelGGL((split_t_kernel<false, false>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, t_hi, t_lo, TGa, 0,
+                         (unsigned short*)nullptr, (unsigned short*)nullptr, 0);
     STRP_HIP(ctx, hipGetLastError());
   }
-  if (c_hi) {
+  if (c_hi && !fused) {
     const int KGa = (int)plane_kg(rows);
     dim3 grid((unsigned)(((T + 127) / 128 * 128 + 255) / 256), (unsigned)((KGa + 3) / 4));
     if (src_dtype == STRP_BF16)

@@ -964,11 +964,36 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     }
     STRP_TRY(make_weight_planes(ctx, arena, Bf, SRC_F32, d, s, d, 0, npa, &Bp));
   }
+  // Z_S is needed by tokens (fc1 refit) and, with relu, by channels (a-update): when both stages run, one pass over
+  // the kept rows of Z writes both sets of planes; the second set stays in the base arena until the a-update.
+  PlaneOp Zk8pre;
+  memset(&Zk8pre, 0, sizeof(Zk8pre));
+  const bool z_planes_once = (stages & STRP_STAGE_REFIT1) && (stages & STRP_STAGE_AUPD);
+  if (z_planes_once) {
+    STRP_TAKE(ctx, arena, zch, unsigned short, plane_elems(T, s));
+    unsigned short* zcl = nullptr;
+    if (npa == 2) {
+      STRP_TAKE(ctx, arena, zcl2, unsigned short, plane_elems(T, s));
+      zcl = zcl2;
+    }
+    Zk8pre = PlaneOp{zch, zcl, plane_kg(s), (int)((T + 127) / 128), nullptr};
+  }
   // ---- S6: fc1 refit with the cached factor of H + lam1 I ------------------------------------
   if (stages & STRP_STAGE_REFIT1) {
     Arena a2 = arena;
     PlaneOp Zrow;
-    STRP_TRY(make_t_planes(ctx, a2, st->Z, STRP_F32, lda, st->idx, s, T, 0, npa, &Zrow));
+    if (z_planes_once) {
+      STRP_TAKE(ctx, a2, zth, unsigned short, plane_elems(s, T));
+      unsigned short* ztl = nullptr;
+      if (npa == 2) {
+        STRP_TAKE(ctx, a2, ztl2, unsigned short, plane_elems(s, T));
+        ztl = ztl2;
+      }
+      STRP_TRY(split_act(ctx, st->Z, STRP_F32, lda, st->idx, s, T, 0, 1, zth, ztl, (unsigned short*)Zk8pre.hi, (unsigned short*)Zk8pre.lo));
+      Zrow = PlaneOp{zth, ztl, plane_kg(T), (s + 127) / 128, nullptr};
+    } else {
+      STRP_TRY(make_t_planes(ctx, a2, st->Z, STRP_F32, lda, st->idx, s, T, 0, npa, &Zrow));
+    }
     RefitIn ri;
     memset(&ri, 0, sizeof(ri));
     ri.Linv = st->cholH; ri.linv_ready = 1;
@@ -990,8 +1015,10 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   if (stages & STRP_STAGE_AUPD) {
     if (chain_forked) STRP_TRY(stream_join(ctx));
     Arena a2 = arena;
-    PlaneOp Zk8;
-    STRP_TRY(make_c_planes(ctx, a2, st->Z, STRP_F32, lda, st->idx, s, T, 1, npa, &Zk8));
+    PlaneOp Zk8 = Zk8pre;
+    if (!z_planes_once) {
+      STRP_TRY(make_c_planes(ctx, a2, st->Z, STRP_F32, lda, st->idx, s, T, 1, npa, &Zk8));
+    }
     STRP_TAKE(ctx, a2, ekh, unsigned short, plane_elems(T, d));
     unsigned short* ekl = nullptr;
     if (npa == 2) {
