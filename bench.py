@@ -23,16 +23,16 @@ PEAK_HBM_GBS = 8000.0
 # rocprofv3 --pmc runs summarised under profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 after the copy-kernel
 # calibration).  Hardware counters cannot be read inside this process; None for classes not measured.
 TRAFFIC_GB = {
-    ("opt6.7b", "gemm_h2x2_partial"): 25.9,    # Gram 30.2, fc2 right-hand side 47.1, W W^T 0.4
-    ("opt6.7b", "gemm_h2x2_aupd"): 57.2,
-    ("opt6.7b", "gemm_h2x2_resid"): 44.6,
-    ("opt6.7b", "gemm_h2x1_zupd"): 36.3,
-    ("opt6.7b", "gemm_h2x1_partial"): 26.1,
-    ("opt6.7b", "gemm_h1x1_partial"): 12.0,    # E E^T of the objective
+    ("opt6.7b", "gemm_h2x2_partial"): 24.8,    # Gram 30.5, fc2 right-hand side 43.5, W W^T 0.4
+    ("opt6.7b", "gemm_h2x2_aupd"): 60.3,
+    ("opt6.7b", "gemm_h2x2_resid"): 44.9,
+    ("opt6.7b", "gemm_h2x1_zupd"): 39.0,
+    ("opt6.7b", "gemm_h2x1_partial"): 32.7,
+    ("opt6.7b", "gemm_h1x1_partial"): 12.9,    # E E^T of the objective
     ("opt6.7b", "plane_c_to_t"): 4.3,
     ("opt6.7b", "row_sums_wanda"): 5.2,        # kept rows only (17.2 when every row is streamed: first selection)
     ("opt6.7b", "pruned_rows_az"): 36.1,
-    ("opt6.7b", "split_act"): 10.4,
+    ("opt6.7b", "split_act"): 13.0,          # A_S by tokens 10.4; Z_S by tokens and by channels in one pass 15.6
 }
 
 
