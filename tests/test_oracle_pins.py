@@ -285,6 +285,26 @@ def test_a_update_is_the_ridge_solution():
     assert np.max(np.abs(grad)) < 1e-9
 
 
+def test_output_residual_after_the_a_update_is_a_scaled_solve_of_the_old_residual():
+    """After the a-update, Y - W2 A = (beta/alpha) M^-1 E with E the residual before it, so the first objective term
+    is (beta/alpha)^2 <M^-2, E E^T> (what the GPU path reports after an a-update); false for any other A."""
+    st = _tiny_state(21, d=6, f=10, T=40)
+    idx = np.array([1, 2, 4, 7, 8])
+    alpha, beta = 0.7, 1.3
+    W2 = orc.refit_fc2(st.Y, st.A, idx, st.lam2, 6, 10)
+    A = orc.a_update(W2, st.Y, st.Z, alpha, beta)
+    W = W2[:, idx]
+    c = beta / alpha
+    Mm = c * np.eye(6) + W @ W.T
+    E = st.Y - W @ np.maximum(st.Z[idx], 0)
+    res = st.Y - W2 @ A
+    assert np.allclose(res, c * np.linalg.solve(Mm, E), rtol=1e-9, atol=1e-11)
+    Minv = np.linalg.inv(Mm)
+    assert np.isclose(np.sum(res * res), c * c * np.sum((Minv @ Minv) * (E @ E.T)), rtol=1e-10)
+    A_other = A + 1e-3
+    assert not np.isclose(np.sum((st.Y - W2 @ A_other) ** 2), c * c * np.sum((Minv @ Minv) * (E @ E.T)), rtol=1e-6)
+
+
 # ---- P6: z-update --------------------------------------------------------------------
 def test_z_update_beats_grid_search():
     st = _tiny_state(13, d=4, f=6, T=10)
