@@ -174,7 +174,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
     }
     // optional operand-plane copy of the produced tile (its rows are the contraction axis of the consumer):
     // this lane's four rows are half of one 16-byte chunk; rows past M inside the last chunk are written as zeros
-    if ((EPI == EPI_STORE || EPI == EPI_INITZ || EPI == EPI_RESID || EPI == EPI_AUPD) && p.k8_hi && ncol && (!EDGE || (mq & ~7) < p.M)) {
+    if ((EPI == EPI_STORE || EPI == EPI_INITZ || EPI == EPI_RESID) && p.k8_hi && ncol && (!EDGE || (mq & ~7) < p.M)) {
       unsigned short h[4], l[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) split_half(outv[r], h[r], l[r]);

@@ -133,7 +133,7 @@ struct GemmP {
   double* red;         // per-block partial sums [gridDim.x][2] (INITZ, RESID, ZUPD)
   int write_out;       // ZUPD: 1 = update Z, 0 = only accumulate the objective sums
   unsigned short* k8_hi;  // optional operand planes of the produced values with k = output row, r = output column
-  unsigned short* k8_lo;  //   (STORE: C, INITZ: relu(C), RESID: Y - C); k8_kg = M / 8 groups, ceil(N/128) panels
+  unsigned short* k8_lo;  //   (STORE: C, INITZ: relu(C), RESID: Y - C; not offered by AUPD / ZUPD); k8_kg = M / 8 groups, ceil(N/128) panels
   long long k8_kg;
 };
 
