@@ -177,19 +177,18 @@ __device__ __forceinline__ double rsqrt_f64(double d) {
 // the eight row indices it needs (p_c(x) = P(x,c) - sum_{c'<c} p_c'(x) u_{c,c'}), and applies the rank-4 update
 //   a_ik -= sum_c (p_c(i) / d_c) p_c(k)            (unpredicated: entries of finished columns are never re-read)
 //   V_i. -= sum_c (p_c(i) / d_c) q_c(.)  for i > j0 + c,   q_c = row j0 + c of the inverse, eliminated likewise
-// so that V ends as Lu^-1 and L^-1 = D^-1/2 Lu^-1.  Column j0 + c of L is p_c(i) d_c^-1/2.
+// so that V ends as Lu^-1 and L^-1 = D^-1/2 Lu^-1.
 struct PotrfShared {
-  double Lm[NB][NB + 1];   // factor, entries on and below the diagonal
   double colb[2][4][NB];
   double rowb[2][4][NB];
   double rsd[NB];          // d_j^-1/2
 };
 
-// On return (after its closing barrier): sh.Lm holds the factor, sh.rsd the inverse square roots of the pivots and
-// v the unit-lower inverse (L^-1 = diag(rsd) v) at this thread's 16 positions.  report: this block raises ENOTPD.
+// On return (after its closing barrier): sh.rsd holds the inverse square roots of the pivots and v the unit-lower
+// inverse (L^-1 = diag(rsd) v) at this thread's 16 positions.  The factor of the block itself is not formed: every
+// consumer (panel multiplication, triangular inverse) works with the inverse.  report: this block raises ENOTPD.
 __device__ __forceinline__ void potrf_block(const double* A, long long ld, int jb, PotrfShared& sh, double (&v)[4][4], int32_t* status,
                                             bool report) {
-  auto& Lm = sh.Lm;
   auto& colb = sh.colb;
   auto& rowb = sh.rowb;
   auto& rsd = sh.rsd;
@@ -274,16 +273,6 @@ __device__ __forceinline__ void potrf_block(const double* A, long long ld, int j
       pk[2][q] = cb[2][xk] - pk[0][q] * u20 - pk[1][q] * u21;
       pk[3][q] = cb[3][xk] - pk[0][q] * u30 - pk[1][q] * u31 - pk[2][q] * u32;
     }
-    // column j0 + c of the factor: thread (ty, tx = c) writes it for rows ty + 16 ii (entries above the diagonal are
-    // written too and never read)
-    if (report && tx < 4) {   // only the block that stores the factor needs it
-#pragma unroll
-      for (int ii = 0; ii < 4; ++ii) {
-        const double pc = tx == 0 ? pi[0][ii] : tx == 1 ? pi[1][ii] : tx == 2 ? pi[2][ii] : pi[3][ii];
-        const double rc = tx == 0 ? rs[0] : tx == 1 ? rs[1] : tx == 2 ? rs[2] : rs[3];
-        Lm[ty + 16 * ii][j0 + tx] = pc * rc;
-      }
-    }
     // rows j0 + c of the inverse, eliminated among themselves, at this thread's columns
     const double (*rb)[NB] = rowb[buf];
     double qk[4][4];
@@ -316,8 +305,9 @@ __device__ __forceinline__ void potrf_block(const double* A, long long ld, int j
 
 // One 64-column step of the factorisation in one launch.  Every block factors the (already updated) diagonal block
 // itself -- the chip is idle during these steps, and a separate one-block launch would only add a kernel boundary to
-// the critical path.  Block 0 stores the factor and its inverse; block b >= 1 multiplies rows [64 (b-1), +64) of the
-// panel below the diagonal block by L^-T in place.
+// the critical path.  Block 0 stores the inverse of the block's factor; block b >= 1 multiplies rows [64 (b-1), +64)
+// of the panel below the diagonal block by L^-T in place.  The diagonal block itself is only read (all blocks load
+// it; nobody writes it), so blocks that start at different times cannot see each other's output.
 __global__ __launch_bounds__(256) void potrf_panel_kernel(double* Ajj, long long ld, int jb, int rest, double* invd, int32_t* status) {
   __shared__ PotrfShared sh;
   __shared__ double Ms[NB][NB + 1];   // Ms[k][c] = Linv[c][k]
@@ -345,7 +335,6 @@ __global__ __launch_bounds__(256) void potrf_panel_kernel(double* Ajj, long long
         const int i = ty + 16 * ii, k = tx + 16 * kk;
         const bool in = i < jb && k < jb;
         invd[i * NB + k] = (in && k <= i) ? v[ii][kk] * sh.rsd[i] : 0.0;
-        if (in) Ajj[(long long)i * ld + k] = (k <= i) ? sh.Lm[i][k] : 0.0;
       }
     return;
   }

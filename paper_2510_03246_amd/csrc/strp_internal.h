@@ -167,10 +167,12 @@ strp_status weight_scale(strp_ctx* ctx, const void* src, int src_kind, long long
 
 // ---- fp64 dense kernels (dense_f64.hip) ---------------------------------------------------
 constexpr int NB = 64;  // block order of the factorisation
-// In-place lower Cholesky of the n x n fp64 matrix A (ld), A += 0 (caller adds the ridge).
-// invd: [ceil(n/NB)][NB*NB] inverses of the diagonal blocks of L.  status: device word.
+// In-place lower Cholesky of the n x n fp64 matrix A (ld); the caller has added the ridge.  On return the blocks of A
+// below the NB x NB diagonal blocks hold L; the diagonal blocks themselves are left as they were when their step
+// began (never needed: invd has their inverses).  invd: [ceil(n/NB)][NB*NB] inverses of the diagonal blocks of L.
+// status: device word.
 strp_status chol_factor(strp_ctx* ctx, double* A, int n, long long ld, double* invd, int32_t* status);
-// Linv [n x n, ld n] = L^-1 from the factor and its inverted diagonal blocks; tmp: n x n scratch.
+// Linv [n x n, ld n] = L^-1 from the off-diagonal blocks of the factor and its inverted diagonal blocks; tmp: n x n scratch.
 strp_status tri_inverse(strp_ctx* ctx, const double* L, int n, long long ldl, const double* invd, double* Linv, double* tmp);
 // In place X <- X (L L^T)^-1 = (X Linv^T) Linv for X [m x n] (ld n); tmp: m x n scratch.
 strp_status apply_inverse_right(strp_ctx* ctx, const double* Linv, int n, double* X, int m, double* tmp);
