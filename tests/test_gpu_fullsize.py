@@ -199,3 +199,31 @@ def test_gain_and_lemma_scores_on_moved_state(run):
         ref = orc.unit_scores(*sums, mode_ref)
         assert np.allclose(score.cpu().numpy()[units], ref, rtol=2e-6, atol=0)
         assert np.isclose(energies.item(), float(score.double().mean().item()), rtol=1e-6)
+
+
+def test_second_selection_from_cached_sums(run):
+    """The iteration kept the scoring sums of the rows it pruned: the next selection (kept rows streamed, pruned rows
+    from the cache) gives the scores and the mask of a selection that streams every row, and sampled scores equal
+    n2_j * sum_t A_jt^2 of the state (runs last: it restores what a selection overwrites)."""
+    mod, cfg, k = run["mod"], run["cfg"], run["k"]
+    assert mod.state.sums_cached == 1
+    saved = {n: getattr(mod, n).clone() for n in ("mask", "idx", "score")}
+    saved_scalars = mod.scalars.clone()
+    sel = strp.Params(ALPHA, BETA, DELTA, strp.WANDA, 1, k, strp.STAGE_SELECT)
+    mod.step(sel)
+    assert mod.state.sums_cached == 0
+    score_cached, mask_cached = mod.score.clone(), mod.mask.clone()
+    mod.mask.copy_(saved["mask"])
+    mod.step(sel)
+    assert torch.allclose(score_cached, mod.score, rtol=1e-6, atol=0)
+    assert torch.equal(mask_cached, mod.mask)
+    rng = np.random.default_rng(3)
+    units = np.concatenate([rng.choice(cfg.f, size=6, replace=False), mod.idx[:3].cpu().numpy()])
+    rows = torch.from_numpy(units).cuda().long()
+    g = (mod.A[rows, :cfg.T].double() ** 2).sum(dim=1)
+    ref = (mod.n2[rows] * g).cpu().numpy()
+    assert np.allclose(score_cached[rows].cpu().numpy(), ref, rtol=2e-6, atol=0)
+    for n, t in saved.items():
+        getattr(mod, n).copy_(t)
+    mod.scalars.copy_(saved_scalars)
+    mod.state.s = k
