@@ -282,7 +282,11 @@ strp_status strp_module_init(strp_ctx* ctx, const strp_module_desc* desc, strp_m
  * module: score + top-k (if due), fc2 refit, fc1 refit, a-update
  *     A = (alpha W2^T W2 + beta I)^-1 (alpha W2^T Y + beta relu(Z)),
  * z-update (exact per-element minimiser of beta(a - relu z)^2 + alpha(z - W1 x)^2) and the
- * objective.  report_host (optional) is filled after synchronising the stream.
+ * objective.  report_host (optional) is filled after synchronising the stream.  The first objective term,
+ * (alpha/T)|Y - W2 A|^2, is formed from Y - W2 A itself when the call does not include the a-update stage; when
+ * it does, A is that update's exact minimiser and the same number is obtained as
+ * (alpha/T)(beta/alpha)^2 <M^-2, E E^T>, E = Y - W2[:,S] relu(Z_S), M = (beta/alpha) I + W2[:,S] W2[:,S]^T
+ * (Appendix A.1, "Updating activation": the normal equations of that step).
  */
 strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_module_state* st,
                            const strp_params* params, strp_report* report_host);
