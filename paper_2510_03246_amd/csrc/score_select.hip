@@ -414,7 +414,7 @@ strp_status launch_alloc(strp_ctx* ctx, const double* energies, int L, const int
 // index-ordered compaction (ballot + popcount prefix) writes mask and ascending kept indices.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ unsigned int score_key(float x) {
-  const unsigned int u = __builtin_bit_cast(unsigned int, x);
+  const unsigned int u = __builtin_bit_cast(unsigned int, x + 0.0f);   // -0 and +0 are one value: both map to +0
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 __device__ __forceinline__ float key_score(unsigned int k) {
@@ -459,15 +459,28 @@ __global__ __launch_bounds__(1024) void topk_kernel(const float* score, int n, i
       if ((key & pmask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
     }
     __syncthreads();
-    if (tid == 0) {
-      unsigned int cum = 0;
-      int d = 255;
-      for (; d > 0; --d) {
-        if (cum + hist[d] >= krem) break;
-        cum += hist[d];
+    if (tid < 64) {
+      // the bucket d with  #(keys in buckets above d) < krem <= #(keys in buckets d and above): lane l owns buckets
+      // 4 l .. 4 l + 3, a wavefront suffix scan gives the count above its group, exactly one (lane, bucket) matches
+      unsigned int h[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) h[j] = hist[4 * tid + j];
+      const unsigned int own = h[0] + h[1] + h[2] + h[3];
+      unsigned int suf = own;   // inclusive suffix sum over lanes >= tid
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const unsigned int v = __shfl_down(suf, o, 64);
+        if (tid + o < 64) suf += v;
       }
-      sel_prefix = prefix | ((unsigned int)d << shift);
-      sel_krem = krem - cum;
+      unsigned int cum = suf - own;   // keys in the groups above this lane's
+#pragma unroll
+      for (int j = 3; j >= 0; --j) {
+        if (cum < krem && cum + h[j] >= krem) {
+          sel_prefix = prefix | ((unsigned int)(4 * tid + j) << shift);
+          sel_krem = krem - cum;
+        }
+        cum += h[j];
+      }
     }
     __syncthreads();
     prefix = sel_prefix;
@@ -521,6 +534,109 @@ __global__ __launch_bounds__(1024) void topk_kernel(const float* score, int n, i
       run_kept += tk;
     }
     __syncthreads();
+  }
+}
+
+// One module's scores (n <= 16384, 0 < k < n): the 16 keys of a thread (elements tid + 1024 j) stay in registers.
+// The k-th largest key is built bit by bit from the top (32 counting rounds: ballots + one barrier each; a radix
+// histogram in LDS serialises on the few exponent buckets real scores fall into).  The index-ordered compaction
+// takes two table scans instead of a barrier chain per 1024 elements: per (round j, wavefront) counts of the keys
+// equal to the threshold, then of the kept keys, scanned in (j, wavefront) order = index order.
+__device__ __forceinline__ int table_scan_256(int val, int* wtot, int tid) {
+  // exclusive prefix of val over threads 0..255 (called by every thread of the block; others pass 0 and ignore)
+  const int lane = tid & 63, wave = tid >> 6;
+  int inc = val;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int v = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += v;
+  }
+  if (lane == 63 && wave < 4) wtot[wave] = inc;
+  __syncthreads();
+  int off = 0;
+  for (int w = 0; w < wave && w < 4; ++w) off += wtot[w];
+  __syncthreads();
+  return off + inc - val;
+}
+
+__global__ __launch_bounds__(1024) void topk_small_kernel(const float* score, int n, int k, int group, uint8_t* mask, int32_t* idx,
+                                                          float* tau) {
+  __shared__ int wcnt[2][16];
+  __shared__ int table[256];      // [round j][wavefront]
+  __shared__ int wtot[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  unsigned int kreg[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const int i = tid + 1024 * j;
+    kreg[j] = i < n ? score_key(score[i]) : 0u;   // a candidate always has a bit set, so padding is never counted
+  }
+  auto count_ge = [&](unsigned int cand, int buf) {
+    int c = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) c += __popcll(__ballot(kreg[j] >= cand));
+    if (lane == 0) wcnt[buf][wave] = c;
+    __syncthreads();
+    int tot = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += wcnt[buf][w];
+    return tot;
+  };
+  unsigned int v = 0;
+  for (int b = 31; b >= 0; --b) {
+    const unsigned int cand = v | (1u << b);
+    if (count_ge(cand, b & 1) >= k) v = cand;
+  }
+  // v = k-th largest key.  Keys above it are kept, of the keys equal to it the krem with the lowest indices.
+  int n_gt = 0;
+  if (v != 0xffffffffu) n_gt = count_ge(v + 1u, 1);   // buffer 1: round b = 0 may still be read from buffer 0
+  const int krem = k - n_gt;
+  if (tid == 0 && tau) *tau = key_score(v);
+  const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  // counts of equal keys per (round, wavefront)
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const unsigned long long beq = __ballot(tid + 1024 * j < n && kreg[j] == v);
+    if (lane == 0) table[j * 16 + wave] = __popcll(beq);
+  }
+  __syncthreads();
+  const int eq_pref = table_scan_256(tid < 256 ? table[tid] : 0, wtot, tid);
+  if (tid < 256) table[tid] = eq_pref;
+  __syncthreads();
+  unsigned int keepbits = 0;
+  int kcnt[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const bool in = tid + 1024 * j < n;
+    const bool eq = in && kreg[j] == v;
+    const unsigned long long beq = __ballot(eq);
+    const int rank = table[j * 16 + wave] + __popcll(beq & lt_mask);
+    const bool keep = in && (kreg[j] > v || (eq && rank < krem));
+    keepbits |= (unsigned int)keep << j;
+    const unsigned long long bk = __ballot(keep);
+    kcnt[j] = __popcll(bk & lt_mask);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const unsigned long long bk = __ballot((keepbits >> j) & 1u);
+    if (lane == 0) table[j * 16 + wave] = __popcll(bk);
+  }
+  __syncthreads();
+  const int kp_pref = table_scan_256(tid < 256 ? table[tid] : 0, wtot, tid);
+  if (tid < 256) table[tid] = kp_pref;
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const int i = tid + 1024 * j;
+    if (i >= n) continue;
+    const bool keep = (keepbits >> j) & 1u;
+    mask[i] = (uint8_t)keep;
+    if (keep) {
+      const long long pos = (long long)(table[j * 16 + wave] + kcnt[j]) * group;
+      for (int c = 0; c < group; ++c) idx[pos + c] = i * group + c;
+    }
   }
 }
 
@@ -918,7 +1034,10 @@ strp_status launch_topk(strp_ctx* ctx, const float* score, int n, int k, int gro
   ProfScope ps(ctx, "topk", 0.0, 5.0 * (double)n + 4.0 * (double)k * group);
   const bool big_path = n > 65536 && group == 1 && k > 0 && k < n;
   if (!big_path) {
-    hipLaunchKernelGGL(topk_kernel, dim3(1), dim3(1024), 0, ctx->stream, score, n, k, group, mask, idx, tau);
+    if (n <= 16 * 1024 && k > 0 && k < n)
+      hipLaunchKernelGGL(topk_small_kernel, dim3(1), dim3(1024), 0, ctx->stream, score, n, k, group, mask, idx, tau);
+    else
+      hipLaunchKernelGGL(topk_kernel, dim3(1), dim3(1024), 0, ctx->stream, score, n, k, group, mask, idx, tau);
     STRP_HIP(ctx, hipGetLastError());
     return STRP_OK;
   }

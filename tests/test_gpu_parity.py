@@ -92,7 +92,8 @@ def test_gram_fast_precision_is_coarser_but_close(ctx):
 # strp_mask_topk
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("n,k,group", [(3072, 1536, 1), (1000, 1, 1), (1000, 999, 1), (28672, 8602, 1), (12, 6, 64),
-                                       (257, 0, 1), (257, 257, 2)])
+                                       (257, 0, 1), (257, 257, 2), (16384, 4915, 1), (16383, 16382, 1), (16385, 5000, 1),
+                                       (2, 1, 1), (64, 63, 1), (1025, 512, 3)])
 def test_mask_topk_exact(ctx, n, k, group):
     rng = np.random.default_rng(n + k)
     score = rng.normal(size=n).astype(np.float32) ** 2
@@ -106,6 +107,26 @@ def test_mask_topk_exact(ctx, n, k, group):
     assert np.array_equal(idx.cpu().numpy().astype(np.int64), io)
     if 0 < k:
         assert float(tau.item()) == np.float32(to)
+
+
+@pytest.mark.parametrize("n", [777, 16384, 20000])
+def test_mask_topk_special_values(ctx, n):
+    """Negative scores, signed zeros, infinities and one repeated value: ordering by value, ties to the lower index."""
+    rng = np.random.default_rng(n)
+    score = rng.normal(size=n).astype(np.float32)
+    score[rng.integers(0, n, size=n // 7)] = 0.0
+    score[rng.integers(0, n, size=n // 9)] = -0.0
+    score[rng.integers(0, n, size=3)] = np.inf
+    score[rng.integers(0, n, size=3)] = -np.inf
+    for k in (1, n // 3, n - 1):
+        mask, idx, tau = ctx.strp_mask_topk(torch.from_numpy(score).cuda(), k)
+        mo, io, to = orc.select_topk(score, k)
+        assert np.array_equal(mask.cpu().numpy(), mo), k
+        assert np.array_equal(idx.cpu().numpy().astype(np.int64), io), k
+        assert float(tau.item()) == np.float32(to)
+    same = np.full(n, 0.25, dtype=np.float32)
+    mask, idx, tau = ctx.strp_mask_topk(torch.from_numpy(same).cuda(), n // 2)
+    assert np.array_equal(idx.cpu().numpy(), np.arange(n // 2)) and float(tau.item()) == 0.25
 
 
 @pytest.mark.parametrize("n,frac,kind", [(48 * 28672, 0.3, "chi2"), ((1 << 22) + 3, 0.5, "normal"), (70001, 0.9, "ties"),
