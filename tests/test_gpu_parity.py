@@ -489,13 +489,16 @@ def test_free_running_reselect_medium(ctx):
     assert max(err.values()) < TOL_F, err
 
 
-@pytest.mark.parametrize("alpha,beta", [(1.0, 1.0), (2.0, 0.5), (0.25, 3.0)])
-def test_first_objective_term_identity_matches_the_product(ctx, alpha, beta):
+@pytest.mark.parametrize("alpha,beta,d,f,T,k", [(1.0, 1.0, 264, 1048, 3000, 419), (2.0, 0.5, 264, 1048, 3000, 419),
+                                                 (0.25, 3.0, 264, 1048, 3000, 419), (1.0, 1.0, 72, 264, 520, 100),
+                                                 (1.0, 2.0, 64, 256, 96, 31), (1.5, 1.0, 776, 1032, 2600, 1031)])
+def test_first_objective_term_identity_matches_the_product(ctx, alpha, beta, d, f, T, k):
     """A full iteration reports alpha/T |Y - W2 A|^2 through (beta/alpha)^2 <M^-2, E E^T> (valid because its a-update is
     the exact minimiser); an objective-only call on the same state forms Y - W2 A itself.  Both must agree with each
-    other and with the oracle's definition (ragged T and d, several tiles)."""
+    other and with the oracle's definition (ragged T and d, several tiles, fewer tokens than a tile, nearly everything
+    kept).  The identity is the better conditioned of the two when the residual is small: it rounds E to fp16, the product
+    rounds A (observed at k = f - 1: 6e-6 against 4e-4 from the oracle)."""
     base = inputs.CONFIGS["opt125m"]
-    d, f, T, k = 264, 1048, 3000, 419
     cfg = type(base)(**{**base.__dict__, "d": d, "f": f, "T": T, "n_outlier": 3})
     m = inputs.make_ffn_module(cfg, 0, 11, "cuda", ld=(T + 7) // 8 * 8)
     mod = strp.FFNModule(ctx, m["W1hat"], m["W2hat"], m["X"], T)
@@ -507,9 +510,9 @@ def test_first_objective_term_identity_matches_the_product(ctx, alpha, beta):
         terms = orc.admm_step(st, k, alpha, beta, orc.WANDA, select=True)
         assert rep.status == strp.OK
         direct = mod.step(_params(k, strp.WANDA, stages=strp.STAGE_OBJ, alpha=alpha, beta=beta))
-        assert abs(rep.terms[0] - direct.terms[0]) <= 3e-4 * direct.terms[0], (it, rep.terms[0], direct.terms[0])
         assert abs(rep.terms[0] - terms[0]) <= TOL_J * terms[0], (it, rep.terms[0], terms[0])
-        assert np.allclose(np.array(direct.terms[:]), np.array(rep.terms[:]), rtol=3e-4)
+        assert abs(direct.terms[0] - terms[0]) <= TOL_J * terms[0], (it, direct.terms[0], terms[0])
+        assert np.allclose(np.array(direct.terms[1:]), np.array(rep.terms[1:]), rtol=1e-6)
 
 
 @pytest.mark.parametrize("mode,level", [(strp.WANDA, 1), (strp.GAIN, 2), (strp.LEMMA, 2)])
