@@ -149,7 +149,7 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma_kernel(const GemmP p) {
   // Instruction order inside a half stage: the fragment reads of the next stage are issued in the shadow of the
   // matrix-core instructions of this one (one LDS read after each of the first MFMAs) instead of ahead of them.
   auto interleave = [&]() {
-    constexpr int NRD = (NPP + NPQ == 4) ? 12 : (NPP + NPQ == 3 ? (NPP == 2 ? 10 : 8) : 6);   // ds_read_b128 per half stage
+    constexpr int NRD = WTM * NPP + WTN * NPQ;   // ds_read_b128 per half stage
     constexpr int NMF = WTM * WTN * (NPP * NPQ == 4 ? 3 : NPP * NPQ);
 #pragma unroll
     for (int i = 0; i < NRD; ++i) {
