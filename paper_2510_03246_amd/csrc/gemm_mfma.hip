@@ -317,15 +317,17 @@ strp_status launch_gemm(strp_ctx* ctx, GemmP& p) {
 }
 
 // ---- split-K reduction -----------------------------------------------------------------------
-// One block reduces a 32 x 32 output tile (thread = column tx, rows ty + 8 i).  Symmetric products: only tiles on
-// or below the diagonal are reduced; the strict lower part is also written transposed through LDS, so the upper
-// half is a bit-exact mirror and the partials are read once, row-contiguously.
+// One block reduces a 64 x 64 output tile (thread = column tx, rows ty + 4 i): a wavefront load is 256 contiguous bytes
+// of one row of one partial.  Symmetric products: only tiles on or below the diagonal are reduced; the strict lower
+// part is also written transposed through LDS, so the upper half is a bit-exact mirror and the partials are read once,
+// row-contiguously.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* part, int splits, int M, int N, int triangle,
                                                            float* outf, long long ldof, double* outd, long long ldod,
                                                            double* diag, int accumulate) {
-  __shared__ double tile[32][33];
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-  const int n0 = blockIdx.x * 32, m0 = blockIdx.y * 32;
+  constexpr int TS = 64;
+  __shared__ double tile[TS][TS + 1];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int n0 = blockIdx.x * TS, m0 = blockIdx.y * TS;
   if (triangle && n0 > m0) return;
   const long long MN = (long long)M * N;
   auto put = [&](int m, int n, double s) {
@@ -336,23 +338,41 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* part, i
     if (outd) outd[(long long)m * ldod + n] = s;
     if (diag && m == n) diag[m] = s;
   };
+  const int n = n0 + tx;
+  double acc[16];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int m = m0 + ty + 8 * i, n = n0 + tx;
-    double s = 0.0;
-    if (m < M && n < N) {
-      const float* src = part + (long long)m * N + n;
-      for (int sp = 0; sp < splits; ++sp) s += (double)src[(long long)sp * MN];
-      if (!triangle || n <= m) put(m, n, s);
+  for (int i = 0; i < 16; ++i) acc[i] = 0.0;
+  {
+    // rows and the column are clamped into range (results of clamped lanes are not stored): the 16 loads of a split
+    // are then unconditional and all in flight together
+    const int nc = n < N ? n : N - 1;
+    long long ro[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int m = m0 + ty + 4 * i;
+      ro[i] = (long long)(m < M ? m : M - 1) * N + nc;
     }
-    tile[ty + 8 * i][tx] = s;
+    for (int sp = 0; sp < splits; ++sp) {
+      const float* src = part + (long long)sp * MN;
+      float v[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = src[ro[i]];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[i] += (double)v[i];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int m = m0 + ty + 4 * i;
+    if (m < M && n < N && (!triangle || n <= m)) put(m, n, acc[i]);
+    tile[ty + 4 * i][tx] = acc[i];
   }
   if (!triangle) return;
   __syncthreads();
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int lo_m = m0 + tx, lo_n = n0 + ty + 8 * i;     // element (lo_m, lo_n) of the lower half, mirrored to (lo_n, lo_m)
-    if (lo_n < lo_m && lo_m < M && lo_n < N) put(lo_n, lo_m, tile[tx][ty + 8 * i]);
+  for (int i = 0; i < 16; ++i) {
+    const int lo_m = m0 + tx, lo_n = n0 + ty + 4 * i;     // element (lo_m, lo_n) of the lower half, mirrored to (lo_n, lo_m)
+    if (lo_n < lo_m && lo_m < M && lo_n < N) put(lo_n, lo_m, tile[tx][ty + 4 * i]);
   }
 }
 
@@ -362,7 +382,7 @@ strp_status launch_splitk_reduce(strp_ctx* ctx, const float* part, int splits, i
   const long long tot = (long long)M * N;
   if (triangle && M != N) return fail(ctx, STRP_EINVAL, "split-K reduce: a symmetric product must be square");
   ProfScope ps(ctx, "splitk_reduce", 0.0, 4.0 * (double)tot * (double)splits * (triangle ? 0.5 : 1.0) + (outf ? 4.0 : 0.0) * tot + (outd ? 8.0 : 0.0) * tot);
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((N + 31) / 32, (M + 31) / 32), dim3(256), 0, ctx->stream, part,
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, ctx->stream, part,
                      splits, M, N, triangle, outf, ldof, outd, ldod, diag, accumulate);
   STRP_HIP(ctx, hipGetLastError());
   return STRP_OK;
