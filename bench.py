@@ -23,12 +23,12 @@ PEAK_HBM_GBS = 8000.0
 # rocprofv3 --pmc runs summarised under profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 after the copy-kernel
 # calibration).  Hardware counters cannot be read inside this process; None for classes not measured.
 TRAFFIC_GB = {
-    ("opt6.7b", "gemm_h2x2_partial"): 24.1,    # Gram 28.4, fc2 right-hand side 43.5, W W^T 0.4
-    ("opt6.7b", "gemm_h2x2_aupd"): 57.4,       # these GEMM figures move by +-15 % between runs (L2 hit rate)
-    ("opt6.7b", "gemm_h2x2_resid"): 50.5,
-    ("opt6.7b", "gemm_h2x1_zupd"): 38.6,
-    ("opt6.7b", "gemm_h2x1_partial"): 25.3,
-    ("opt6.7b", "gemm_h1x1_partial"): 11.3,    # E E^T of the objective
+    ("opt6.7b", "gemm_h2x2_partial"): 25.4,    # Gram 29.4, fc2 right-hand side 46.3, W W^T 0.4
+    ("opt6.7b", "gemm_h2x2_aupd"): 56.8,       # these GEMM figures move by +-15 % between runs (L2 hit rate)
+    ("opt6.7b", "gemm_h2x2_resid"): 56.3,
+    ("opt6.7b", "gemm_h2x1_zupd"): 38.2,
+    ("opt6.7b", "gemm_h2x1_partial"): 28.2,
+    ("opt6.7b", "gemm_h1x1_partial"): 12.1,    # E E^T of the objective
     ("opt6.7b", "plane_c_to_t"): 4.3,
     ("opt6.7b", "row_sums_wanda"): 5.2,        # kept rows only (17.2 when every row is streamed: first selection)
     ("opt6.7b", "pruned_rows_az"): 36.1,
