@@ -250,14 +250,29 @@ strp_status split_small(strp_ctx* ctx, const void* src, int src_kind, long long 
 template <typename TS>
 __global__ __launch_bounds__(256) void absmax_kernel(const TS* src, long long lds, int rows, int cols, unsigned int* slot) {
   float m = 0.0f;
-  const long long n = (long long)rows * cols;
-  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
-    const long long r = i / cols, c = i % cols;
-    m = __builtin_fmaxf(m, __builtin_fabsf((float)small_src(src, r * lds + c)));
+  for (int r = blockIdx.x; r < rows; r += gridDim.x) {   // a block walks whole rows: no division per element
+    const TS* row = src + (long long)r * lds;
+    // eight independent loads per trip keep enough requests in flight for a latency-bound reduction
+    int c = threadIdx.x;
+    for (; c + 7 * 256 < cols; c += 8 * 256) {
+      float v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) v[q] = (float)small_src(row, c + 256 * q);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) m = __builtin_fmaxf(m, __builtin_fabsf(v[q]));
+    }
+    for (; c < cols; c += 256) m = __builtin_fmaxf(m, __builtin_fabsf((float)small_src(row, c)));
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) m = __builtin_fmaxf(m, __shfl_down(m, o, 64));
-  if ((threadIdx.x & 63) == 0 && m > 0.0f) atomicMax(slot, __builtin_bit_cast(unsigned int, m));
+  // one atomic per block: thousands of atomics on one address serialise in L2 and were the whole run time
+  __shared__ float wm[4];
+  if ((threadIdx.x & 63) == 0) wm[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    m = __builtin_fmaxf(__builtin_fmaxf(wm[0], wm[1]), __builtin_fmaxf(wm[2], wm[3]));
+    if (m > 0.0f) atomicMax(slot, __builtin_bit_cast(unsigned int, m));
+  }
 }
 // Pass 2: the slot (max bits) becomes the scale (float) in place.
 __global__ void scale_from_max_kernel(unsigned int* slot) {
@@ -275,8 +290,7 @@ __global__ void scale_from_max_kernel(unsigned int* slot) {
 strp_status weight_scale(strp_ctx* ctx, const void* src, int src_kind, long long lds, int rows, int cols, float* scale_out) {
   STRP_TRY(fill_zero(ctx, scale_out, 4));
   unsigned int* slot = (unsigned int*)scale_out;
-  long long blocks = ((long long)rows * cols + 255) / 256;
-  if (blocks > 2048) blocks = 2048;
+  long long blocks = rows < 1024 ? rows : 1024;
   dim3 grid((unsigned)blocks), block(256);
   if (src_kind == SRC_F64)
     hipLaunchKernelGGL((absmax_kernel<double>), grid, block, 0, ctx->stream, (const double*)src, lds, rows, cols, slot);
