@@ -79,6 +79,48 @@ def select_stress(ctx, torch):
     return res
 
 
+def head_variant(ctx, torch, inputs, strp, cfg):
+    """Head pruning of one attention output projection at the workload's width (units = heads of d/heads channels):
+    group-summed scores, top-k heads, Gram of the kept channels of C, refit of W_O[:, S].  One pass = the four calls."""
+    d, g, T = cfg.d, cfg.d // cfg.heads, cfg.T
+    m = inputs.make_head_module(cfg, 0, 0, "cuda")
+    WO, Cm = m["WOhat"], m["C"]
+    kh = cfg.heads - int(round(cfg.rbar * cfg.heads))
+    Y = torch.empty((d, Cm.shape[1]), dtype=torch.float32, device="cuda")
+    for t0 in range(0, T, 32768):                              # dense target W_O C (harness, not timed)
+        Y[:, t0:t0 + 32768] = WO.float() @ Cm[:, t0:t0 + 32768].float()
+    score = torch.empty(cfg.heads, dtype=torch.float32, device="cuda")
+    energies = torch.zeros(1, dtype=torch.float64, device="cuda")
+    W = torch.empty((d, d), device="cuda")
+    lam = 0.01 * float((Cm[:, :T].float() ** 2).sum().item()) / d
+
+    def one_pass():
+        ctx.strp_score_alloc(Cm, T, strp.WANDA, score, energies, 0, 1, group=g, What=WO)
+        mask, idx, tau = ctx.strp_mask_topk(score, kh, g)
+        G = ctx.strp_gram(Cm, T, idx=idx)
+        ctx.strp_refit(strp.SIDE_FC2, G, lam, Y, Cm, T, idx, W)
+        return idx
+
+    idx = one_pass()
+    torch.cuda.synchronize()
+    if ctx.poll() != strp.OK:
+        raise RuntimeError("head variant: device status word not clean")
+    ctx.profile_enable(True)
+    reps = 3
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        one_pass()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / reps
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    s = int(idx.numel())
+    return dict(heads=cfg.heads, head_dim=g, kept_heads=kh, kept_channels=s, ms_per_pass=ms, tokens_per_s=T / (ms * 1e-3),
+                algorithmic_tflops=(s * (s + 1.0) * T + 2.0 * d * s * T) / (ms * 1e-3) / 1e12,
+                kernels={n: dict(ms=v["ms"] / reps, launches=v["launches"] // reps) for n, v in
+                         sorted(prof.items(), key=lambda kv: -kv[1]["ms"])})
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -90,6 +132,9 @@ def main():
                     help="unit score used by the select stage (the metric is quoted on wanda)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--head-variant", action="store_true",
+                    help="also time head pruning of one attention output projection at the workload's width (scores per "
+                         "head, top-k heads, Gram, refit of W_O); reported under \"head_variant\" in the same line")
     ap.add_argument("--select-stress", action="store_true",
                     help="also time the multi-block top-k on 2^26 synthetic scores and on the 48 x 28672 scores of the "
                          "largest configuration (one global threshold); reported under \"select_stress\" in the same line")
@@ -185,6 +230,8 @@ def main():
     }
     if args.select_stress:
         out["select_stress"] = select_stress(ctx, torch)
+    if args.head_variant:
+        out["head_variant"] = head_variant(ctx, torch, inputs, strp, cfg)
     if not args.no_mfma_ceiling:
         out["mfma_ceiling"] = {"unit": "TFLOP/s", "register_operands": ctx.strp_peak_probe(0),
                                "register_operands_random_data": ctx.strp_peak_probe(2),
