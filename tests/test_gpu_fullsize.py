@@ -227,3 +227,44 @@ def test_second_selection_from_cached_sums(run):
         getattr(mod, n).copy_(t)
     mod.scalars.copy_(saved_scalars)
     mod.state.s = k
+
+
+def test_head_variant_at_full_width(run):
+    """Head pruning of an output projection at config 4's width (32 heads x 128 channels, T = 262144): head scores, the
+    kept heads and sampled rows of the refitted W_O against fp64 (uses the fixture's context and workspace)."""
+    cfg, ctx = run["cfg"], run["mod"].ctx
+    d, g, T = cfg.d, cfg.d // cfg.heads, cfg.T
+    m = inputs.make_head_module(cfg, 0, 0, "cuda")
+    WO, Cm = m["WOhat"], m["C"]
+    kh = cfg.heads - int(round(cfg.rbar * cfg.heads))
+    score = torch.empty(cfg.heads, dtype=torch.float32, device="cuda")
+    energies = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ctx.strp_score_alloc(Cm, T, strp.WANDA, score, energies, 0, 1, group=g, What=WO)
+    n2 = (WO.double() ** 2).sum(dim=0)
+    gsum = torch.zeros(d, dtype=torch.float64, device="cuda")
+    for t0 in range(0, T, 32768):
+        gsum += (Cm[:, t0:min(T, t0 + 32768)].double() ** 2).sum(dim=1)
+    ref_score = (n2 * gsum).view(cfg.heads, g).sum(dim=1).cpu().numpy()
+    assert np.allclose(score.cpu().numpy(), ref_score, rtol=2e-6)
+    mask, idx, tau = ctx.strp_mask_topk(score, kh, g)
+    mo, io, to = orc.select_topk(ref_score.astype(np.float32), kh, g)
+    assert np.array_equal(mask.cpu().numpy(), mo) and np.array_equal(idx.cpu().numpy().astype(np.int64), io)
+    Y = torch.empty((d, Cm.shape[1]), dtype=torch.float32, device="cuda")
+    for t0 in range(0, T, 32768):
+        Y[:, t0:t0 + 32768] = (WO.double() @ Cm[:, t0:t0 + 32768].double()).float()
+    lam = DELTA * float(gsum.sum().item()) / d
+    G = ctx.strp_gram(Cm, T, idx=idx)
+    W = torch.empty((d, d), device="cuda")
+    ctx.strp_refit(strp.SIDE_FC2, G, lam, Y, Cm, T, idx, W)
+    assert ctx.poll() == strp.OK
+    li = idx.long()
+    CS = Cm[li, :T]
+    Gd = f64_nt(CS, CS, T).cpu().numpy()
+    assert rel_fro(G.cpu().numpy(), Gd) < 1e-5
+    rows = torch.tensor([0, 2049, d - 1], device="cuda")
+    R = f64_nt(Y[rows, :T], CS, T).cpu().numpy()
+    ref = np.linalg.solve(Gd + lam * np.eye(li.numel()), R.T).T
+    assert rel_fro(W[rows][:, li].cpu().numpy(), ref) < TOL_F / 4
+    off = torch.ones(d, dtype=torch.bool, device="cuda")
+    off[li] = False
+    assert not bool(W[:, off].any())
