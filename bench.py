@@ -228,6 +228,16 @@ def main():
         "roofline": roof,
         "kernels": kernels,
     }
+    # device memory of the one resident module (the footprint that stays fixed while the model grows in depth)
+    state_bytes = sum(t.numel() * t.element_size() for t in (mod.Z, mod.A, mod.Z0, mod.Y, mod.W1, mod.W2, mod.H, mod.cholH,
+                                                              mod.n2, mod.score, mod.mask, mod.idx, mod.scalars))
+    input_bytes = sum(t.numel() * t.element_size() for t in (m["X"], m["W1hat"], m["W2hat"]))
+    model_weight_bytes = cfg.L * 12 * cfg.d * cfg.d * 2     # 4 d^2 attention + 8 d^2 FFN per layer, bf16
+    out["device_memory"] = {"unit": "bytes", "module_inputs": input_bytes, "module_state": state_bytes,
+                            "plane_cache": mod.cache.numel(), "workspace": ctx.ws.numel() if ctx.ws is not None else 0,
+                            "peak_allocated": torch.cuda.max_memory_allocated(),
+                            "resident_weights_of_this_module": m["W1hat"].numel() * 2 * m["W1hat"].element_size(),
+                            "all_weights_of_the_model_bf16": model_weight_bytes}
     if args.select_stress:
         out["select_stress"] = select_stress(ctx, torch)
     if args.head_variant:
