@@ -121,6 +121,57 @@ def head_variant(ctx, torch, inputs, strp, cfg):
                          sorted(prof.items(), key=lambda kv: -kv[1]["ms"])})
 
 
+def stream_modules(ctx, torch, inputs, strp, cfg, mod, params, n_modules, iters):
+    """Modules one after another on the one resident state: the next module's weights and calibration input come from
+    pinned host memory on a second stream while the current module iterates (double-buffered staging)."""
+    names = ("W1hat", "W2hat", "X")
+    host = []
+    for layer in range(n_modules):
+        m = inputs.make_ffn_module(cfg, layer, 0, "cuda")
+        host.append({n: torch.empty(m[n].shape, dtype=m[n].dtype, pin_memory=True).copy_(m[n]) for n in names})
+        del m
+    stage = [{n: torch.empty(host[0][n].shape, dtype=host[0][n].dtype, device="cuda") for n in names} for _ in range(2)]
+    copy_stream = torch.cuda.Stream()
+    copied = [torch.cuda.Event(enable_timing=True) for _ in range(n_modules)]
+    copy_start = [torch.cuda.Event(enable_timing=True) for _ in range(n_modules)]
+    freed = [torch.cuda.Event() for _ in range(n_modules)]
+    main = torch.cuda.current_stream()
+
+    def enqueue_copy(layer):
+        with torch.cuda.stream(copy_stream):
+            if layer >= 2:
+                copy_stream.wait_event(freed[layer - 2])       # the buffer's previous module is done
+            copy_start[layer].record(copy_stream)
+            for n in names:
+                stage[layer & 1][n].copy_(host[layer][n], non_blocking=True)
+            copied[layer].record(copy_stream)
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    enqueue_copy(0)
+    losses = []
+    for layer in range(n_modules):
+        if layer + 1 < n_modules:
+            enqueue_copy(layer + 1)
+        main.wait_event(copied[layer])
+        buf = stage[layer & 1]
+        mod.rebind_inputs(buf["W1hat"], buf["W2hat"], buf["X"])
+        mod.init(params)
+        for it in range(iters):
+            rep = mod.step(params, report=(it == iters - 1))
+        losses.append(rep.J_ridge)
+        freed[layer].record(main)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    bytes_per_module = sum(host[0][n].numel() * host[0][n].element_size() for n in names)
+    copy_ms = [copy_start[l].elapsed_time(copied[l]) for l in range(n_modules)]
+    return dict(modules=n_modules, iterations_per_module=iters, seconds=dt, seconds_per_module=dt / n_modules,
+                host_to_device_bytes_per_module=bytes_per_module, copy_ms_per_module=sum(copy_ms) / n_modules,
+                copy_gbs=bytes_per_module / (sum(copy_ms) / n_modules * 1e-3) / 1e9,
+                staging_bytes=2 * bytes_per_module, objective_per_module=losses,
+                peak_allocated=torch.cuda.max_memory_allocated())
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -135,6 +186,10 @@ def main():
     ap.add_argument("--head-variant", action="store_true",
                     help="also time head pruning of one attention output projection at the workload's width (scores per "
                          "head, top-k heads, Gram, refit of W_O); reported under \"head_variant\" in the same line")
+    ap.add_argument("--stream-modules", type=int, default=0,
+                    help="also run this many modules one after another on the resident state, their weights and calibration "
+                         "input streamed from pinned host memory beside the compute; reported under \"stream_modules\"")
+    ap.add_argument("--stream-iters", type=int, default=3, help="ADMM iterations per streamed module")
     ap.add_argument("--select-stress", action="store_true",
                     help="also time the multi-block top-k on 2^26 synthetic scores and on the 48 x 28672 scores of the "
                          "largest configuration (one global threshold); reported under \"select_stress\" in the same line")
@@ -240,6 +295,8 @@ def main():
                             "all_weights_of_the_model_bf16": model_weight_bytes}
     if args.select_stress:
         out["select_stress"] = select_stress(ctx, torch)
+    if args.stream_modules:
+        out["stream_modules"] = stream_modules(ctx, torch, inputs, strp, cfg, mod, params, args.stream_modules, args.stream_iters)
     if args.head_variant:
         out["head_variant"] = head_variant(ctx, torch, inputs, strp, cfg)
     if not args.no_mfma_ceiling:

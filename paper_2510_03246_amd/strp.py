@@ -301,6 +301,14 @@ class FFNModule:
         self.state = st
         ctx.ensure_workspace(ctx.workspace_bytes(self.desc))
 
+    def rebind_inputs(self, W1hat: torch.Tensor, W2hat: torch.Tensor, X: torch.Tensor):
+        """Point the state at another module's inputs of the same shapes (the state buffers are reused; call init next)."""
+        assert W1hat.shape == self.W1hat.shape and W2hat.shape == self.W2hat.shape and X.shape == self.X.shape
+        assert W1hat.dtype == self.W1hat.dtype and X.dtype == self.X.dtype and X.stride(0) == self.X.stride(0)
+        self.W1hat, self.W2hat, self.X = W1hat, W2hat, X
+        for name in ("X", "W1hat", "W2hat"):
+            setattr(self.state, name, getattr(self, name).data_ptr())
+
     def init(self, params: Params):
         self.ctx.strp_module_init(self.desc, self.state, params)
 
