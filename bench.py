@@ -124,51 +124,30 @@ def head_variant(ctx, torch, inputs, strp, cfg):
 def stream_modules(ctx, torch, inputs, strp, cfg, mod, params, n_modules, iters):
     """Modules one after another on the one resident state: the next module's weights and calibration input come from
     pinned host memory on a second stream while the current module iterates (double-buffered staging)."""
-    names = ("W1hat", "W2hat", "X")
+    from paper_2510_03246_amd import stream
+
     host = []
     for layer in range(n_modules):
         m = inputs.make_ffn_module(cfg, layer, 0, "cuda")
-        host.append({n: torch.empty(m[n].shape, dtype=m[n].dtype, pin_memory=True).copy_(m[n]) for n in names})
+        host.append(stream.pin(m))
         del m
-    stage = [{n: torch.empty(host[0][n].shape, dtype=host[0][n].dtype, device="cuda") for n in names} for _ in range(2)]
-    copy_stream = torch.cuda.Stream()
-    copied = [torch.cuda.Event(enable_timing=True) for _ in range(n_modules)]
-    copy_start = [torch.cuda.Event(enable_timing=True) for _ in range(n_modules)]
-    freed = [torch.cuda.Event() for _ in range(n_modules)]
-    main = torch.cuda.current_stream()
-
-    def enqueue_copy(layer):
-        with torch.cuda.stream(copy_stream):
-            if layer >= 2:
-                copy_stream.wait_event(freed[layer - 2])       # the buffer's previous module is done
-            copy_start[layer].record(copy_stream)
-            for n in names:
-                stage[layer & 1][n].copy_(host[layer][n], non_blocking=True)
-            copied[layer].record(copy_stream)
-
+    streamer = stream.ModuleStreamer(host)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    enqueue_copy(0)
     losses = []
-    for layer in range(n_modules):
-        if layer + 1 < n_modules:
-            enqueue_copy(layer + 1)
-        main.wait_event(copied[layer])
-        buf = stage[layer & 1]
+    for layer, buf in streamer:
         mod.rebind_inputs(buf["W1hat"], buf["W2hat"], buf["X"])
         mod.init(params)
         for it in range(iters):
             rep = mod.step(params, report=(it == iters - 1))
         losses.append(rep.J_ridge)
-        freed[layer].record(main)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    bytes_per_module = sum(host[0][n].numel() * host[0][n].element_size() for n in names)
-    copy_ms = [copy_start[l].elapsed_time(copied[l]) for l in range(n_modules)]
+    copy_ms = streamer.copy_ms()
     return dict(modules=n_modules, iterations_per_module=iters, seconds=dt, seconds_per_module=dt / n_modules,
-                host_to_device_bytes_per_module=bytes_per_module, copy_ms_per_module=sum(copy_ms) / n_modules,
-                copy_gbs=bytes_per_module / (sum(copy_ms) / n_modules * 1e-3) / 1e9,
-                staging_bytes=2 * bytes_per_module, objective_per_module=losses,
+                host_to_device_bytes_per_module=streamer.bytes_per_module, copy_ms_per_module=sum(copy_ms) / n_modules,
+                copy_gbs=streamer.bytes_per_module / (sum(copy_ms) / n_modules * 1e-3) / 1e9,
+                staging_bytes=streamer.staging_bytes, objective_per_module=losses,
                 peak_allocated=torch.cuda.max_memory_allocated())
 
 
@@ -300,9 +279,10 @@ def main():
     if args.head_variant:
         out["head_variant"] = head_variant(ctx, torch, inputs, strp, cfg)
     if not args.no_mfma_ceiling:
-        out["mfma_ceiling"] = {"unit": "TFLOP/s", "register_operands": ctx.strp_peak_probe(0),
-                               "register_operands_random_data": ctx.strp_peak_probe(2),
-                               "lds_fed_random_data": ctx.strp_peak_probe(1)}
+        from paper_2510_03246_amd import bench_probe
+        out["mfma_ceiling"] = {"unit": "TFLOP/s", "register_operands": bench_probe.mfma_rate(0),
+                               "register_operands_random_data": bench_probe.mfma_rate(2),
+                               "lds_fed_random_data": bench_probe.mfma_rate(1)}
         if roof.get("executed"):
             roof["executed_frac_of_lds_fed_ceiling"] = roof["executed"] / out["mfma_ceiling"]["lds_fed_random_data"]
     if not args.no_cpu_baseline:

@@ -15,8 +15,9 @@
  *     buffers, including the workspace; the library never allocates or frees device memory.
  *   - Calls enqueue work on the stream given to strp_create and return; argument errors are
  *     reported synchronously (nothing is enqueued), numeric failures (non-positive Cholesky
- *     pivot, non-finite input) are recorded in a device status word read by strp_poll and by
- *     strp_admm_step when it fills its report.
+ *     pivot; NaN, Inf or a magnitude above 65504 in an activation that a scoring reduction or an
+ *     operand-plane writer reads: such a value is clamped and the results are meaningless) are
+ *     recorded in a device status word read by strp_poll and by strp_admm_step when it fills its report.
  *   - Leading dimensions are in elements; activation leading dimensions must be multiples of 8
  *     and base pointers 16-byte aligned.  Padding columns (index >= T) are never read as data
  *     and never written.
@@ -38,7 +39,7 @@ typedef enum {
   STRP_EINVAL = 1,     /* bad argument (null pointer, k > n, n % group != 0, ld < T, misalignment) */
   STRP_ENOMEM = 2,     /* workspace missing or too small                                        */
   STRP_ENOTPD = 3,     /* Cholesky met a non-positive pivot                                      */
-  STRP_ENONFINITE = 4, /* NaN/Inf met in a reduction                                              */
+  STRP_ENONFINITE = 4, /* NaN/Inf, or a magnitude above 65504 (the fp16 operand range), in an input       */
   STRP_EHIP = 5,       /* a HIP runtime call failed                                               */
   STRP_ESTATE = 6      /* call sequence error (e.g. admm_step before module_init)                 */
 } strp_status;
@@ -46,8 +47,10 @@ typedef enum {
 typedef enum { STRP_BF16 = 0, STRP_F32 = 1 } strp_dtype;
 typedef enum { STRP_SCORE_WANDA = 0, STRP_SCORE_LEMMA = 1, STRP_SCORE_GAIN = 2 } strp_score_mode;
 typedef enum { STRP_SIDE_FC1 = 0, STRP_SIDE_FC2 = 1 } strp_side;
-/* How fp32 operands enter the bf16 matrix cores: rounded once (FAST) or as a two-term
- * bf16 split hi+lo with the three leading cross products (SPLIT, ~2^-16 relative). */
+/* How fp32 operands enter the fp16 matrix cores: rounded once to fp16 (FAST, 2^-12 relative) or as a two-term
+ * fp16 split hi + lo with the three leading cross products hi*hi + hi*lo + lo*hi (SPLIT, ~2^-22 relative).
+ * The setting is captured by strp_module_init together with the operand planes it writes; strp_admm_step on that
+ * module returns STRP_ESTATE if the context's precision has been changed since (initialise the module again). */
 typedef enum { STRP_PREC_FAST = 0, STRP_PREC_SPLIT = 1 } strp_precision;
 
 typedef struct strp_ctx strp_ctx;
@@ -239,6 +242,9 @@ typedef struct {
                           while the last iteration wrote those rows (1: sum A^2, 2: all four) and sit in `cache`,
                           so the next selection streams the kept rows only; strp_module_init clears it.  Z, A and
                           mask must not be changed by the caller between iterations (or set this field to 0).   */
+  int32_t precision;   /* host field: 0 until strp_module_init has run on this state, then 1 + the strp_precision its
+                          operand planes were written with; strp_admm_step refuses (STRP_ESTATE) to run on an
+                          uninitialised state or under a different precision                                        */
 } strp_module_state;
 
 typedef struct {
@@ -290,15 +296,6 @@ strp_status strp_module_init(strp_ctx* ctx, const strp_module_desc* desc, strp_m
  */
 strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_module_state* st,
                            const strp_params* params, strp_report* report_host);
-
-/*
- * strp_peak_probe -- measurement aid (no part of the method): sustained rate, in TFLOP/s on *tflops_out (host),
- * of the fp16 matrix-core instruction the GEMMs use.  kind 0: constant register operands, nothing else running
- * (the issue limit); kind 2: the same with random fp16 values in the operand registers; kind 1: the GEMM's inner loop without its memory side (fragments re-read from LDS every
- * stage, random fp16 data).  Runs for about `milliseconds` twice and times the second run.  Needs 512 KiB of the
- * context's workspace; synchronises the stream.  Errors: STRP_EINVAL, STRP_ENOMEM, STRP_EHIP.
- */
-strp_status strp_peak_probe(strp_ctx* ctx, int32_t kind, double milliseconds, double* tflops_out);
 
 #ifdef __cplusplus
 }

@@ -1,4 +1,5 @@
-"""Build libstrp.so (gfx950 only) from the HIP sources under csrc/ with hipcc."""
+"""Build libstrp.so (gfx950 only) from the HIP sources under csrc/ with hipcc, and libstrp_bench.so, the
+benchmark's matrix-core rate probe (its own library: no part of the product ABI)."""
 from __future__ import annotations
 
 import os
@@ -11,7 +12,9 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libstrp.so")
-SOURCES = ["gemm_mfma.hip", "gemm_dma.hip", "split_planes.hip", "dense_f64.hip", "score_select.hip", "peak_probe.hip", "strp_api.hip"]
+SOURCES = ["gemm_mfma.hip", "gemm_dma.hip", "split_planes.hip", "dense_f64.hip", "score_select.hip", "strp_api.hip"]
+BENCH_LIB = os.path.join(HERE, "libstrp_bench.so")
+BENCH_SOURCES = ["bench_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
@@ -29,16 +32,21 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(verbose: bool = True) -> str:
-    os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+def _link(objs, lib, verbose):
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("link failed:\n" + res.stdout + res.stderr)
     if verbose:
-        print("built", LIB)
+        print("built", lib)
+
+
+def build(verbose: bool = True) -> str:
+    os.makedirs(OBJ, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=4) as ex:
+        objs = list(ex.map(_compile, SOURCES + BENCH_SOURCES))
+    _link(objs[:len(SOURCES)], LIB, verbose)
+    _link(objs[len(SOURCES):], BENCH_LIB, verbose)
     return LIB
 
 

@@ -1,3 +1,4 @@
+// Benchmark helper, built as its own shared library (libstrp_bench.so) and no part of libstrp.so or its ABI.
 // Measurement aid: the sustained rate of v_mfma_f32_32x32x16_f16 on this chip, so that the GEMM figures can be read
 // against what the matrix cores deliver in practice and not only against the nominal 2.5 PFLOP/s.
 //   kind 0: back-to-back MFMA on constant register operands (no LDS, no memory): the instruction's issue limit
@@ -6,7 +7,9 @@
 //   kind 1: the GEMM's inner loop without its memory side: eight wavefronts per CU, each 4 x 2 tiles, three passes
 //           per 16-deep stage, operand fragments re-read from LDS every stage, LDS filled with random fp16 values
 //           (operand toggling is what the power management reacts to)
-#include "strp_internal.h"
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
 
 namespace strp {
 
@@ -131,35 +134,39 @@ __global__ __launch_bounds__(512, 1) void probe_mfma_lds_kernel(float* out, int 
 
 using namespace strp;
 
-extern "C" strp_status strp_peak_probe(strp_ctx* ctx, int32_t kind, double milliseconds, double* tflops_out) {
-  if (!ctx) return STRP_EINVAL;
-  if (!tflops_out || (kind < 0 || kind > 2) || !(milliseconds > 0.0) || milliseconds > 2000.0)
-    return fail(ctx, STRP_EINVAL, "peak_probe: kind 0, 1 or 2, 0 < milliseconds <= 2000");
-  Arena arena(ctx);
-  STRP_TAKE(ctx, arena, out, float, 256 * 512);
+// hip_stream: the stream to run on; scratch: 512 KiB of device memory (256-byte aligned).  Returns 0, 1 (bad argument)
+// or 5 (a HIP call failed).  Runs for about `milliseconds` twice, times the second run, synchronises the stream.
+extern "C" int strp_bench_mfma_rate(void* hip_stream, void* scratch, size_t scratch_bytes, int32_t kind, double milliseconds,
+                                    double* tflops_out) {
+  if (!scratch || scratch_bytes < 256 * 512 * sizeof(float) || !tflops_out || kind < 0 || kind > 2 || !(milliseconds > 0.0) ||
+      milliseconds > 2000.0)
+    return 1;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  float* out = (float*)scratch;
   hipEvent_t e0, e1;
-  STRP_HIP(ctx, hipEventCreate(&e0));
-  STRP_HIP(ctx, hipEventCreate(&e1));
+  if (hipEventCreate(&e0) != hipSuccess) return 5;
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return 5; }
   const double flops_per_iter = kind == 1 ? 24.0 * 32768.0 : 8.0 * 32768.0;   // per wavefront
   // ~25 ns per MFMA pair of wavefronts at full rate: size the run to the requested duration (long enough for the
   // power management to settle), then measure
   int iters = (int)(milliseconds * 1e-3 / ((kind == 1 ? 24.0 : 8.0) * 2.0 * 13.4e-9));
   if (iters < 1000) iters = 1000;
   float ms = 0.0f;
-  for (int rep = 0; rep < 2; ++rep) {   // the first run warms the clocks
-    STRP_HIP(ctx, hipEventRecord(e0, ctx->stream));
+  bool ok = true;
+  for (int rep = 0; rep < 2 && ok; ++rep) {   // the first run warms the clocks
+    ok = ok && hipEventRecord(e0, stream) == hipSuccess;
     if (kind == 0)
-      hipLaunchKernelGGL(probe_mfma_reg_kernel, dim3(256), dim3(512), 0, ctx->stream, out, iters);
+      hipLaunchKernelGGL(probe_mfma_reg_kernel, dim3(256), dim3(512), 0, stream, out, iters);
     else if (kind == 2)
-      hipLaunchKernelGGL(probe_mfma_rand_kernel, dim3(256), dim3(512), 0, ctx->stream, out, iters, 5u + rep);
+      hipLaunchKernelGGL(probe_mfma_rand_kernel, dim3(256), dim3(512), 0, stream, out, iters, 5u + rep);
     else
-      hipLaunchKernelGGL(probe_mfma_lds_kernel, dim3(256), dim3(512), 0, ctx->stream, out, iters, 17u + rep);
-    STRP_HIP(ctx, hipEventRecord(e1, ctx->stream));
-    STRP_HIP(ctx, hipEventSynchronize(e1));
-    STRP_HIP(ctx, hipEventElapsedTime(&ms, e0, e1));
+      hipLaunchKernelGGL(probe_mfma_lds_kernel, dim3(256), dim3(512), 0, stream, out, iters, 17u + rep);
+    ok = ok && hipEventRecord(e1, stream) == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
+         hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
   }
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
+  if (!ok || !(ms > 0.0f)) return 5;
   *tflops_out = 256.0 * 8.0 * (double)iters * flops_per_iter / ((double)ms * 1e-3) / 1e12;
-  return STRP_OK;
+  return 0;
 }

@@ -27,7 +27,7 @@ constexpr int PLANE_STAGE_BYTES = 2 * ROWS * 16;   // one plane of one operand i
 
 __device__ __forceinline__ void lds_dma_16(const void* gptr, unsigned lds_addr) {
   // m0 = LDS byte address of lane 0's chunk; lane l lands at m0 + 16 l
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
 
 template <int N>

@@ -221,12 +221,11 @@ __global__ __launch_bounds__(256, WT == 4 ? 1 : 2) void gemm_kernel(const GemmP 
 // ---------------------------------------------------------------------------------------------
 void gemm_plan_tiles(GemmP& p, int want_splits) {
   {
-    // 256x256 tiles with the LDS-DMA pipeline when they still give most CUs a block; STRP_TILE=128 forces the small tile
-    static const int env_wt = getenv("STRP_TILE") ? atoi(getenv("STRP_TILE")) : 0;
+    // 256x256 tiles with the LDS-DMA pipeline when they still give most CUs a block
     const long long t4m = (p.M + 255) / 256, t4n = (p.N + 255) / 256;
     const long long n4 = p.triangle ? t4m * (t4m + 1) / 2 : t4m * t4n;
     const bool big = p.M >= 256 && p.N >= 256 && n4 * (want_splits > 1 ? want_splits : 1) >= 192 && p.K >= 256;
-    p.wt = (big && env_wt != 128 && p.force_wt != 2) ? 4 : 2;
+    p.wt = (big && p.force_wt != 2) ? 4 : 2;
   }
   const int ROWS = 64 * p.wt, BK = p.wt == 2 ? 64 : 32;
   p.tilesM = (p.M + ROWS - 1) / ROWS;
@@ -240,10 +239,8 @@ void gemm_plan_tiles(GemmP& p, int want_splits) {
     p.gridN = p.tilesN;
   }
   {
-    // tile group: 32 tiles, shaped to the grid (STRP_GROUP=<gm> overrides the row count, for experiments)
-    static const int env_gm = getenv("STRP_GROUP") ? atoi(getenv("STRP_GROUP")) : 0;
-    int gm = env_gm > 0 ? env_gm : 4;
-    if (gm > 32) gm = 32;
+    // tile group: 32 tiles, shaped to the grid
+    int gm = 4;
     while (gm > 1 && gm > p.gridM) gm >>= 1;
     int gn = 32 / gm;
     while (gn > 1 && gn / 2 >= p.gridN) { gn >>= 1; if (gm * 2 <= p.gridM) gm <<= 1; }

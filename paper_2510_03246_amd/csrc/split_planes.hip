@@ -49,8 +49,10 @@ __device__ __forceinline__ void load4(const void* src, long long off, float (&v)
 template <bool SRC_BF16, bool WITH_C>
 __global__ __launch_bounds__(256) void split_t_kernel(const void* src, long long lds, const int* idx, int rows, long long T,
                                                       int relu, unsigned short* t_hi, unsigned short* t_lo, long long TGa,
-                                                      int relu_c, unsigned short* c_hi, unsigned short* c_lo, int KGc) {
+                                                      int relu_c, unsigned short* c_hi, unsigned short* c_lo, int KGc,
+                                                      int32_t* status) {
   constexpr int GP = 128 * 16 + 16;   // bytes per k-group in LDS
+  bool bad = false;                   // a value the fp16 planes cannot hold: NaN, Inf or |x| > 65504
   __shared__ __attribute__((aligned(16))) unsigned char sh[8 * GP];
   __shared__ __attribute__((aligned(16))) unsigned char sl[8 * GP];
   const int t = threadIdx.x, piece = t & 15, rsub = t >> 4;
@@ -75,6 +77,7 @@ __global__ __launch_bounds__(256) void split_t_kernel(const void* src, long long
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       float x = (tok + c < T) ? v[i][c] : 0.0f;
+      bad |= !(__builtin_fabsf(x) <= 65504.0f);
       if (relu) x = __builtin_fmaxf(x, 0.0f);
       sp_split_half(x, h[c], l[c]);
     }
@@ -82,6 +85,7 @@ __global__ __launch_bounds__(256) void split_t_kernel(const void* src, long long
     *(uint2*)(sh + o) = make_uint2(sp_pack2(h[0], h[1]), sp_pack2(h[2], h[3]));
     if (t_lo) *(uint2*)(sl + o) = make_uint2(sp_pack2(l[0], l[1]), sp_pack2(l[2], l[3]));
   }
+  if (bad) atomicCAS(status, 0, (int32_t)STRP_ENONFINITE);
   __syncthreads();
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -121,10 +125,12 @@ __global__ __launch_bounds__(256) void split_t_kernel(const void* src, long long
 // channels (4 k-groups).  Every load of a row is 1 KB contiguous per wavefront, every store 1 KB contiguous.
 template <bool SRC_BF16>
 __global__ __launch_bounds__(256) void split_c_kernel(const void* src, long long lds, const int* idx, int rows, long long T,
-                                                      int relu, unsigned short* c_hi, unsigned short* c_lo, int KGa) {
+                                                      int relu, unsigned short* c_hi, unsigned short* c_lo, int KGa,
+                                                      int32_t* status) {
   const long long tok = (long long)blockIdx.x * 256 + threadIdx.x;
   const int rg0 = blockIdx.y * 4;
   if (tok >= (((T + 127) >> 7) << 7)) return;   // past the last token panel
+  bool bad = false;
   float v[4][8];
 #pragma unroll
   for (int g = 0; g < 4; ++g)
@@ -137,8 +143,10 @@ __global__ __launch_bounds__(256) void split_c_kernel(const void* src, long long
         if (SRC_BF16) x = __builtin_bit_cast(float, (unsigned int)((const unsigned short*)src)[srow * lds + tok] << 16);
         else x = ((const float*)src)[srow * lds + tok];
       }
+      bad |= !(__builtin_fabsf(x) <= 65504.0f);
       v[g][r] = relu ? __builtin_fmaxf(x, 0.0f) : x;
     }
+  if (bad) atomicCAS(status, 0, (int32_t)STRP_ENONFINITE);
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
     if (rg0 + g >= KGa) continue;
@@ -155,6 +163,7 @@ strp_status split_act(strp_ctx* ctx, const void* src, int src_dtype, long long l
                       int relu_t, int relu_c, unsigned short* t_hi, unsigned short* t_lo, unsigned short* c_hi,
                       unsigned short* c_lo) {
   if (rows <= 0 || T <= 0) return fail(ctx, STRP_EINVAL, "split_act: empty");
+  if (!ctx->status_dev) return fail(ctx, STRP_ENOMEM, "split_act: no workspace set");
   if (lds % 8 || lds < T) return fail(ctx, STRP_EINVAL, "split_act: source pitch must be a multiple of 8 and at least T");
   const double es = src_dtype == STRP_BF16 ? 2.0 : 4.0;
   const double wb = (t_hi ? 2.0 : 0.0) + (t_lo ? 2.0 : 0.0) + (c_hi ? 2.0 : 0.0) + (c_lo ? 2.0 : 0.0);
@@ -170,24 +179,24 @@ strp_status split_act(strp_ctx* ctx, const void* src, int src_dtype, long long l
     const long long gx = fused ? 2 * ((T + 127) / 128) : (TGa + 7) / 8;
     dim3 grid((unsigned)gx, (unsigned)((rows + 127) / 128));
     if (fused && src_dtype == STRP_BF16)
-      hipLaunchKernelGGL((split_t_kernel<true, true>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, t_hi, t_lo, TGa, rc, c_hi, c_lo, KGc);
+      hipLaunchKernelGGL((split_t_kernel<true, true>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, t_hi, t_lo, TGa, rc, c_hi, c_lo, KGc, ctx->status_dev);
     else if (fused)
-      hipLaunchKernelGGL((split_t_kernel<false, true>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, t_hi, t_lo, TGa, rc, c_hi, c_lo, KGc);
+      hipLaunchKernelGGL((split_t_kernel<false, true>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, t_hi, t_lo, TGa, rc, c_hi, c_lo, KGc, ctx->status_dev);
     else if (src_dtype == STRP_BF16)
       hipLaunchKernelGGL((split_t_kernel<true, false>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, t_hi, t_lo, TGa, 0,
-                         (unsigned short*)nullptr, (unsigned short*)nullptr, 0);
+                         (unsigned short*)nullptr, (unsigned short*)nullptr, 0, ctx->status_dev);
     else
       hipLaunchKernelGGL((split_t_kernel<false, false>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_t, t_hi, t_lo, TGa, 0,
-                         (unsigned short*)nullptr, (unsigned short*)nullptr, 0);
+                         (unsigned short*)nullptr, (unsigned short*)nullptr, 0, ctx->status_dev);
     STRP_HIP(ctx, hipGetLastError());
   }
   if (c_hi && !fused) {
     const int KGa = (int)plane_kg(rows);
     dim3 grid((unsigned)(((T + 127) / 128 * 128 + 255) / 256), (unsigned)((KGa + 3) / 4));
     if (src_dtype == STRP_BF16)
-      hipLaunchKernelGGL((split_c_kernel<true>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_c, c_hi, c_lo, KGa);
+      hipLaunchKernelGGL((split_c_kernel<true>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_c, c_hi, c_lo, KGa, ctx->status_dev);
     else
-      hipLaunchKernelGGL((split_c_kernel<false>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_c, c_hi, c_lo, KGa);
+      hipLaunchKernelGGL((split_c_kernel<false>), grid, dim3(256), 0, ctx->stream, src, lds, idx, rows, T, relu_c, c_hi, c_lo, KGa, ctx->status_dev);
     STRP_HIP(ctx, hipGetLastError());
   }
   return STRP_OK;

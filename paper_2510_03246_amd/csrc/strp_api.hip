@@ -828,6 +828,7 @@ strp_status strp_module_init(strp_ctx* ctx, const strp_module_desc* desc, strp_m
   st->s = 0;
   st->iter = 0;
   st->sums_cached = 0;
+  st->precision = 1 + prec;
   return STRP_OK;
 }
 
@@ -850,6 +851,11 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   if (params->mode < STRP_SCORE_WANDA || params->mode > STRP_SCORE_GAIN) return fail(ctx, STRP_EINVAL, "admm_step: unknown score mode");
   if (!ctx->ws) return fail(ctx, STRP_ENOMEM, "admm_step: no workspace set");
   const int prec = ctx->precision;
+  // the plane cache was laid out and written under the precision of strp_module_init: another one would read other offsets
+  if (st->precision == 0) return fail(ctx, STRP_ESTATE, "admm_step: strp_module_init has not run on this state");
+  if (st->precision != 1 + prec)
+    return fail(ctx, STRP_ESTATE, "admm_step: the context's precision (%d) differs from the one the module was initialised with (%d)",
+                prec, st->precision - 1);
   const int npa = planes_for(STRP_F32, prec);
   CacheView cv;
   cache_layout(desc, prec, (char*)st->cache, &cv);

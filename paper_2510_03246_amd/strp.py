@@ -24,7 +24,7 @@ STAGE_ALL = 63
 
 EXPORTS = [
     "strp_create", "strp_destroy", "strp_last_error", "strp_set_precision", "strp_set_workspace",
-    "strp_poll", "strp_workspace_bytes", "strp_module_cache_bytes", "strp_profile_enable", "strp_profile_read", "strp_gram", "strp_score_alloc", "strp_mask_topk", "strp_topk_workspace_bytes", "strp_weight_energy", "strp_alloc_inverse", "strp_peak_probe",
+    "strp_poll", "strp_workspace_bytes", "strp_module_cache_bytes", "strp_profile_enable", "strp_profile_read", "strp_gram", "strp_score_alloc", "strp_mask_topk", "strp_topk_workspace_bytes", "strp_weight_energy", "strp_alloc_inverse",
     "strp_refit", "strp_module_init", "strp_admm_step",
 ]
 
@@ -52,7 +52,7 @@ class ModuleState(C.Structure):
                 ("Z0", C.c_void_p), ("Y", C.c_void_p), ("W1", C.c_void_p), ("W2", C.c_void_p), ("H", C.c_void_p),
                 ("cholH", C.c_void_p), ("n2", C.c_void_p), ("score", C.c_void_p), ("mask", C.c_void_p),
                 ("idx", C.c_void_p), ("scalars", C.c_void_p), ("cache", C.c_void_p), ("s", C.c_int32), ("iter", C.c_int32),
-                ("sums_cached", C.c_int32)]
+                ("sums_cached", C.c_int32), ("precision", C.c_int32)]
 
 
 class Params(C.Structure):
@@ -103,7 +103,6 @@ def load_library():
     lib.strp_topk_workspace_bytes.restype = C.c_size_t
     lib.strp_topk_workspace_bytes.argtypes = [C.c_int32]
     lib.strp_weight_energy.argtypes = [vp, C.POINTER(WeightRef), i32, C.c_double, C.c_double, C.c_double, vp]
-    lib.strp_peak_probe.argtypes = [vp, i32, C.c_double, C.POINTER(C.c_double)]
     lib.strp_alloc_inverse.argtypes = [vp, vp, i32, vp, vp, C.c_double, C.c_double, C.c_double, vp, vp]
     lib.strp_gram.argtypes = [vp, vp, C.c_int, i32, i64, i64, vp, i32, vp, i32, vp, C.c_int]
     lib.strp_score_alloc.argtypes = [vp, C.POINTER(ScoreIn), vp, vp, i32, i32, vp, vp, dbl, dbl, dbl, vp, vp]
@@ -236,12 +235,6 @@ class Context:
         for r, m in zip(refs, mats):
             r.W, r.dtype, r.rows, r.cols, r.ld = m.data_ptr(), dtype_code(m), m.shape[0], m.shape[1], m.stride(0)
         self.check(self.lib.strp_weight_energy(self.h, refs, len(mats), float(var_coef), float(l2_coef), float(scale), _ptr(energy)))
-
-    def strp_peak_probe(self, kind: int, milliseconds: float = 200.0) -> float:
-        self.ensure_workspace(1 << 20)
-        out = C.c_double(0.0)
-        self.check(self.lib.strp_peak_probe(self.h, kind, float(milliseconds), C.byref(out)))
-        return out.value
 
     def strp_alloc_inverse(self, energies, n_units, rbar, temperature, rmax=0.95, group_id=None):
         L = energies.numel()

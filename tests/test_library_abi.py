@@ -54,7 +54,7 @@ def test_binding_structs_mirror_the_header(tmp_path):
     import subprocess
     from paper_2510_03246_amd import strp
     pairs = [("strp_module_desc", "k_max", strp.ModuleDesc), ("strp_score_in", "ldw", strp.ScoreIn),
-             ("strp_module_state", "sums_cached", strp.ModuleState), ("strp_params", "stages", strp.Params),
+             ("strp_module_state", "precision", strp.ModuleState), ("strp_params", "stages", strp.Params),
              ("strp_report", "status", strp.Report), ("strp_weight_ref", "ld", strp.WeightRef)]
     src = tmp_path / "layout.c"
     body = "".join(f'  printf("%zu %zu\\n", sizeof({c}), offsetof({c}, {f}));\n' for c, f, _ in pairs)

@@ -439,3 +439,40 @@ def test_inverse_allocation_identities():
     assert r1[0] == 0.3
     rc, _ = orc.inverse_allocation(np.array([1.0, 50.0]), np.array([100, 100]), 0.9, 0.05)
     assert np.max(rc) == 0.95 and np.min(rc) >= 0.0
+
+
+# ---- hand-worked 2 x 2 module: initialisation constants and every term of the objective ------------
+def _hand_module():
+    W1hat = np.array([[1.0, -1.0], [2.0, 0.0]])
+    W2hat = np.array([[1.0, 0.0], [0.5, -1.0]])
+    X = np.array([[1.0, 2.0], [3.0, -1.0]])
+    return orc.module_init(W1hat, W2hat, X, delta=0.1)
+
+
+def test_module_init_hand_values():
+    """Z0 = W1hat X = [[-2, 3], [2, 4]]; A0 = ReLU; Y = W2hat A0 = [[0, 3], [-2, -2.5]]; H = X X^T = [[5, 1], [1, 10]];
+    lam1 = delta tr(H) / d = 0.1 * 15 / 2; lam2 = delta |A0|_F^2 / f = 0.1 * (9 + 4 + 16) / 2 (worked by hand)."""
+    st = _hand_module()
+    assert np.array_equal(st.Z0, [[-2.0, 3.0], [2.0, 4.0]])
+    assert np.array_equal(st.A0, [[0.0, 3.0], [2.0, 4.0]])
+    assert np.array_equal(st.Y, [[0.0, 3.0], [-2.0, -2.5]])
+    assert np.array_equal(st.H, [[5.0, 1.0], [1.0, 10.0]])
+    assert st.lam1 == pytest.approx(0.75, rel=1e-15)
+    assert st.lam2 == pytest.approx(1.45, rel=1e-15)
+    assert np.array_equal(st.Z, st.Z0) and np.array_equal(st.A, st.A0)
+
+
+def test_objective_terms_hand_values():
+    """alpha = 2, beta = 3, T = 2 on a state written by hand (unit 1 pruned):
+       Y - W2 A = [[-0.5, 1], [-2, -2.5]]  -> 11.5;   A - ReLU(Z) = [[0.5, 0], [0, 0]] -> 0.25;
+       Z - W1 X = [[-2, 0], [1, 3]] -> 14;  |W2|^2 = |W1|^2 = 1;  lam2 = 1.45, lam1 = 0.75.
+       terms = [2 * 11.5, 3 * 0.25, 2 * 14, 2 * 1.45 * 1, 2 * 0.75 * 1] / 2."""
+    st = _hand_module()
+    st.Z = np.array([[-1.0, 2.0], [1.0, 3.0]])
+    st.A = np.array([[0.5, 2.0], [1.0, 3.0]])
+    st.W1 = np.array([[1.0, 0.0], [0.0, 0.0]])
+    st.W2 = np.array([[1.0, 0.0], [0.0, 0.0]])
+    terms = orc.objective_terms(st, 2.0, 3.0)
+    assert np.allclose(terms, [11.5, 0.375, 14.0, 1.45, 0.75], rtol=1e-14, atol=0)
+    assert orc.objective(st, 2.0, 3.0) == pytest.approx(28.075, rel=1e-14)
+    assert orc.objective(st, 2.0, 3.0, ridge=False) == pytest.approx(25.875, rel=1e-14)
