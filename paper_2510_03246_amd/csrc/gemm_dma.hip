@@ -25,10 +25,15 @@ constexpr int NSTAGE = 4;
 constexpr int PLANE_STAGE_BYTES = 2 * ROWS * 16;   // one plane of one operand in one stage: 8 KB
 }  // namespace dma
 
+// m0 is written here, so it is named as clobbered; the compiler treats m0 as a reserved register (it never keeps a
+// value in it across statements) and warns about the listing, which is silenced for this one statement.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void lds_dma_16(const void* gptr, unsigned lds_addr) {
   // m0 = LDS byte address of lane 0's chunk; lane l lands at m0 + 16 l
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
