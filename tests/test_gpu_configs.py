@@ -139,6 +139,8 @@ def test_streamed_modules_match_the_oracle_and_memory_stays_one_module():
     cfg = inputs.with_tokens(inputs.CONFIGS["opt125m"], 8192)
     k = cfg.f - int(round(cfg.rbar * cfg.f))
     n_modules, iters = 3, 2
+    torch.cuda.synchronize()
+    base = torch.cuda.memory_allocated()                       # whatever other tests of this process still hold
     host = [stream.pin(inputs.make_ffn_module(cfg, layer, 0, "cpu")) for layer in range(n_modules)]
     ctx = strp.Context(0)
     streamer = stream.ModuleStreamer(host)
@@ -163,7 +165,7 @@ def test_streamed_modules_match_the_oracle_and_memory_stays_one_module():
     assert peaks[0] == peaks[-1], peaks                       # no growth with the number of modules
     resident = sum(t.numel() * t.element_size() for t in (mod.Z, mod.A, mod.Z0, mod.Y, mod.W1, mod.W2, mod.H, mod.cholH,
                                                           mod.cache, ctx.ws))
-    assert peaks[-1] < resident + streamer.staging_bytes + (64 << 20)
+    assert peaks[-1] - base < resident + streamer.staging_bytes + (64 << 20)
     ctx.close()
     for layer, res in enumerate(results):
         hm = host[layer]
