@@ -196,6 +196,23 @@ strp_status strp_mask_topk(strp_ctx* ctx, const float* score, int32_t n, int32_t
 size_t strp_topk_workspace_bytes(int32_t n);
 
 /*
+ * strp_mask_topk_static -- strp_mask_topk (group = 1) for callers that cannot allocate or hand over device memory:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same results
+ * (mask, ascending idx, tau) and the same argument meaning; the select's scratch (per-block histograms, candidate
+ * lists, counters) is a fixed array inside the library instead of the context's workspace, so the call needs no
+ * workspace and allocates nothing on the host or the device (it also records no profile entry).  The array takes
+ * 16 * STRP_TOPK_STATIC_MAX_N + 8 MiB = 32 MiB of device memory on every GPU the library is used on, from the moment
+ * the library is loaded until the process ends.
+ * Limits: n <= STRP_TOPK_STATIC_MAX_N (enough for the 48 x 28672 unit scores of the largest configuration at once);
+ * more returns STRP_EINVAL and nothing is enqueued.  All calls on one GPU share the one array, which keeps the last
+ * call's contents (each call clears the counters it needs): calls that overlap in time on one GPU -- two contexts on
+ * different streams -- race; serialise them.  Other errors as strp_mask_topk.
+ */
+#define STRP_TOPK_STATIC_MAX_N 1572864
+strp_status strp_mask_topk_static(strp_ctx* ctx, const float* score, int32_t n, int32_t k, uint8_t* mask, int32_t* idx,
+                                  float* tau);
+
+/*
  * strp_refit -- closed-form ridge least-squares recovery of the surviving weights
  * (W = z a^+ restricted to the kept support; Appendix A.1, Alg. 3 prune+recover lines).
  *   R = Lhs_rows * Rhs_rows^T over the T tokens,  Wsub = R (Gram + lambda I)^-1.

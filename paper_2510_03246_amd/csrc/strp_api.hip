@@ -29,6 +29,15 @@ struct Profiler {
   }
 };
 
+// Scratch of strp_mask_topk_static (the entry point for callers that cannot allocate): per-block histograms, candidate
+// lists and counters of the multi-block select, for up to STRP_TOPK_STATIC_MAX_N scores.  Every GPU the library runs on
+// holds its own copy of the array until the process ends; in host code the array's name is only a handle for
+// hipGetSymbolAddress, the device address is resolved once per device in strp_create and kept in g_topk_scratch.
+constexpr size_t TOPK_STATIC_BYTES = 16 * (size_t)STRP_TOPK_STATIC_MAX_N + (8u << 20);
+static __device__ __align__(256) unsigned char topk_static_scratch[TOPK_STATIC_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void* g_topk_scratch[MAX_DEVICES];
+
 namespace strp {
 
 int prof_begin(strp_ctx* ctx, const char* name, double flops, double bytes) {
@@ -302,6 +311,17 @@ strp_status strp_create(strp_ctx** out, int device, void* hip_stream) {
     if (c->aux) (void)hipStreamDestroy(c->aux);
     c->aux = nullptr;
   }
+  // device address of this GPU's copy of the static select scratch (the device was made current above)
+  if (device < MAX_DEVICES && !g_topk_scratch[device]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(topk_static_scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      (void)hipHostFree(c->pinned);
+      delete c;
+      return STRP_EHIP;
+    }
+    g_topk_scratch[device] = ptr;
+  }
   *out = c;
   return STRP_OK;
 }
@@ -458,6 +478,26 @@ strp_status strp_alloc_inverse(strp_ctx* ctx, const double* energies, int32_t L,
 }
 
 size_t strp_topk_workspace_bytes(int32_t n) { return n > 0 ? topk_scratch_bytes(n) + 512 : 0; }
+
+strp_status strp_mask_topk_static(strp_ctx* ctx, const float* score, int32_t n, int32_t k, uint8_t* mask, int32_t* idx, float* tau) {
+  if (!ctx) return STRP_EINVAL;
+  if (!score || !mask || !idx) return fail(ctx, STRP_EINVAL, "mask_topk_static: null argument");
+  if (n <= 0 || k < 0 || k > n) return fail(ctx, STRP_EINVAL, "mask_topk_static: need n > 0 and 0 <= k <= n");
+  if (n > STRP_TOPK_STATIC_MAX_N)
+    return fail(ctx, STRP_EINVAL, "mask_topk_static: %d scores exceed the static scratch (at most %d); use strp_mask_topk with a workspace",
+                n, (int)STRP_TOPK_STATIC_MAX_N);
+  const size_t need = (k > 0 && k < n) ? topk_scratch_bytes(n) : 0;
+  if (need > TOPK_STATIC_BYTES) return fail(ctx, STRP_EINVAL, "mask_topk_static: %zu bytes of scratch needed, %zu held", need, TOPK_STATIC_BYTES);
+  void* scratch = ctx->device < MAX_DEVICES ? g_topk_scratch[ctx->device] : nullptr;
+  if (need && !scratch) return fail(ctx, STRP_ESTATE, "mask_topk_static: no static scratch resolved for device %d", ctx->device);
+  // no timing records here: they would create HIP events
+  Profiler* pr = ctx->prof;
+  const bool was_on = pr && pr->on;
+  if (pr) pr->on = false;
+  const strp_status st = launch_topk(ctx, score, n, k, 1, mask, idx, tau, scratch, need);
+  if (pr) pr->on = was_on;
+  return st;
+}
 
 }  // extern "C"
 

@@ -24,7 +24,7 @@ STAGE_ALL = 63
 
 EXPORTS = [
     "strp_create", "strp_destroy", "strp_last_error", "strp_set_precision", "strp_set_workspace",
-    "strp_poll", "strp_workspace_bytes", "strp_module_cache_bytes", "strp_profile_enable", "strp_profile_read", "strp_gram", "strp_score_alloc", "strp_mask_topk", "strp_topk_workspace_bytes", "strp_weight_energy", "strp_alloc_inverse",
+    "strp_poll", "strp_workspace_bytes", "strp_module_cache_bytes", "strp_profile_enable", "strp_profile_read", "strp_gram", "strp_score_alloc", "strp_mask_topk", "strp_mask_topk_static", "strp_topk_workspace_bytes", "strp_weight_energy", "strp_alloc_inverse",
     "strp_refit", "strp_module_init", "strp_admm_step",
 ]
 
@@ -107,6 +107,7 @@ def load_library():
     lib.strp_gram.argtypes = [vp, vp, C.c_int, i32, i64, i64, vp, i32, vp, i32, vp, C.c_int]
     lib.strp_score_alloc.argtypes = [vp, C.POINTER(ScoreIn), vp, vp, i32, i32, vp, vp, dbl, dbl, dbl, vp, vp]
     lib.strp_mask_topk.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.strp_mask_topk_static.argtypes = [vp, vp, i32, i32, vp, vp, vp]
     lib.strp_refit.argtypes = [vp, C.c_int, vp, i32, dbl, vp, C.c_int, vp, C.c_int, i64, vp, C.c_int, i64, i64, vp,
                                i32, vp, i32, i32]
     lib.strp_module_init.argtypes = [vp, C.POINTER(ModuleDesc), C.POINTER(ModuleState), C.POINTER(Params)]
@@ -227,6 +228,11 @@ class Context:
             self.ensure_workspace(need)
         self.check(self.lib.strp_mask_topk(self.h, _ptr(score), n, k, group, _ptr(mask), _ptr(idx), _ptr(tau)))
         return mask, idx[: k * group], tau
+
+    def strp_mask_topk_static(self, score, k, mask, idx, tau, n=None):
+        """The allocation-free variant: every buffer, outputs included, is the caller's; nothing is allocated here."""
+        n = score.numel() if n is None else n
+        self.check(self.lib.strp_mask_topk_static(self.h, _ptr(score), n, k, _ptr(mask), _ptr(idx), _ptr(tau)))
 
     def strp_weight_energy(self, mats, var_coef, l2_coef, scale, energy):
         """energy (device double, 1 element) += scale (|W|_1 + var_coef Var(W) + l2_coef |W|_2) over the 2-D tensors in mats."""
