@@ -19,41 +19,63 @@ if ROOT not in sys.path:
 PEAK_F16_TFLOPS = 2500.0   # MI355X dense fp16/bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
-# HBM-side bytes per launch (GB, averaged over the launches of the class in one iteration) from the two
-# rocprofv3 --pmc runs summarised under profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 after the copy-kernel
-# calibration).  Hardware counters cannot be read inside this process; None for classes not measured.
-TRAFFIC_GB = {
-    ("opt6.7b", "gemm_h2x2_partial"): 25.4,    # Gram 29.4, fc2 right-hand side 46.3, W W^T 0.4
-    ("opt6.7b", "gemm_h2x2_aupd"): 56.8,       # these GEMM figures move by +-15 % between runs (L2 hit rate)
-    ("opt6.7b", "gemm_h2x2_resid"): 56.3,
-    ("opt6.7b", "gemm_h2x1_zupd"): 38.2,
-    ("opt6.7b", "gemm_h2x1_partial"): 28.2,
-    ("opt6.7b", "gemm_h1x1_partial"): 12.1,    # E E^T of the objective
-    ("opt6.7b", "plane_c_to_t"): 4.3,
-    ("opt6.7b", "row_sums_wanda"): 5.2,        # kept rows only (17.2 when every row is streamed: first selection)
-    ("opt6.7b", "pruned_rows_az"): 36.1,
-    ("opt6.7b", "split_act"): 13.0,          # A_S by tokens 10.4; Z_S by tokens and by channels in one pass 15.6
-}
 
 
-def cpu_baseline(cfg_name: str, sample_tokens: int, score_mode: str = "wanda"):
-    """The oracle as it stands, timed on the host cores on a bounded token sample of the same module."""
-    import numpy as np  # noqa: F401
+def measured_traffic(workload: str, kernel_class: str):
+    """HBM bytes per launch of a kernel class (GB) from the tracked summary of the two rocprofv3 --pmc runs
+    (profiles/traffic_<workload>.json, written by paper_2510_03246_amd.profile_summary; hardware counters cannot be read
+    inside this process).  The file carries the hash of the kernel sources it was measured on: with other sources
+    the figure is stale and None is returned, with a note."""
+    from paper_2510_03246_amd import profile_summary
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.json")
+    if not os.path.exists(path):
+        return None, f"no {os.path.relpath(path, ROOT)}"
+    js = json.load(open(path))
+    entry = js.get("classes", {}).get(kernel_class)
+    if entry is None:
+        return None, f"class not in {os.path.relpath(path, ROOT)}"
+    if js.get("sources_sha256") != profile_summary.sources_hash():
+        return None, (f"{os.path.relpath(path, ROOT)} was measured on other kernel sources ({entry['traffic_gb']:.1f} GB per launch "
+                      "there); rerun the --pmc profile")
+    return entry["traffic_gb"], js.get("unit", "GB per launch")
+
+
+def cpu_baseline(cfg_name: str, sample_tokens: int, score_mode: str = "wanda", timed_iters: int = 2):
+    """The oracle as it stands, timed on the host cores on a bounded token sample of the same module: one warm-up
+    iteration, then `timed_iters` timed ones.  The oracle's a-update factors the full f x f system, a cost that does
+    not depend on the token count; it is timed separately (the same library solve on the same matrix with a single
+    right-hand side) so that the per-token rate can be read beside the sample's rate."""
+    import numpy as np
     import torch
 
     from oracle import strp_oracle as orc
     from paper_2510_03246_amd import inputs
 
-    cfg = inputs.with_tokens(inputs.CONFIGS[cfg_name], sample_tokens)
+    full = inputs.CONFIGS[cfg_name]
+    cfg = inputs.with_tokens(full, sample_tokens)
     m = inputs.make_ffn_module(cfg, 0, 0, "cpu")
     st = orc.module_init(*(m[n].double().numpy() for n in ("W1hat", "W2hat", "X")))
     k = cfg.f - int(round(cfg.rbar * cfg.f))
+    mode = {"wanda": orc.WANDA, "lemma": orc.LEMMA, "gain": orc.GAIN}[score_mode]
+    orc.admm_step(st, k, 1.0, 1.0, mode, select=True)                      # warm-up
+    times = []
+    for _ in range(timed_iters):
+        t0 = time.perf_counter()
+        orc.admm_step(st, k, 1.0, 1.0, mode, select=True)
+        times.append(time.perf_counter() - t0)
+    dt = sum(times) / len(times)
+    lhs = st.W2.T @ st.W2 + np.eye(cfg.f)
     t0 = time.perf_counter()
-    orc.admm_step(st, k, 1.0, 1.0, {"wanda": orc.WANDA, "lemma": orc.LEMMA, "gain": orc.GAIN}[score_mode], select=True)
-    dt = time.perf_counter() - t0
+    np.linalg.solve(lhs, np.ones((cfg.f, 1)))
+    t_fixed = time.perf_counter() - t0
+    per_token = max(dt - t_fixed, 1e-9) / sample_tokens
     return dict(value=sample_tokens / dt, unit="calib tokens/s", cores=torch.get_num_threads(), kind="oracle",
-                sample=f"one oracle ADMM iteration (fp64 numpy) on {cfg_name} d={cfg.d} f={cfg.f} k={k} with "
-                       f"{sample_tokens} of the {inputs.CONFIGS[cfg_name].T} tokens: {dt:.1f} s")
+                seconds_per_iteration=dt, token_independent_seconds=t_fixed,
+                tokens_per_s_without_the_token_independent_part=1.0 / per_token,
+                projected_tokens_per_s_at_32768_tokens=32768.0 / (t_fixed + per_token * 32768.0),
+                sample=f"oracle ADMM iterations (fp64 numpy) on {cfg_name} d={cfg.d} f={cfg.f} k={k} with {sample_tokens} of "
+                       f"the {full.T} tokens: 1 warm-up + {timed_iters} timed, {dt:.1f} s each, of which {t_fixed:.1f} s is the "
+                       f"f x f factorisation of the a-update (independent of the token count)")
 
 
 def select_stress(ctx, torch):
@@ -161,7 +183,8 @@ def main():
     ap.add_argument("--score-mode", default="wanda", choices=("wanda", "lemma", "gain"),
                     help="unit score used by the select stage (the metric is quoted on wanda)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=2048,
+                    help="tokens of the oracle's timed sample (8192 or 32768 give the fuller baseline; minutes of CPU time)")
     ap.add_argument("--head-variant", action="store_true",
                     help="also time head pruning of one attention output projection at the workload's width (scores per "
                          "head, top-k heads, Gram, refit of W_O); reported under \"head_variant\" in the same line")
@@ -176,6 +199,9 @@ def main():
                     help="skip the sustained-rate measurement of the fp16 matrix-core instruction (register-only, and fed from "
                          "LDS with random data in the GEMM's wavefront shape; about one second, outside the timed region) "
                          "that is reported under \"mfma_ceiling\"")
+    ap.add_argument("--dump-launches", default="",
+                    help="write the library's per-launch records of the timed region (kernel class names in enqueue order) "
+                         "to this JSON file, for paper_2510_03246_amd.profile_summary")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="before the timed region run one elementwise copy kernel that reads 1 GiB and writes 1 GiB, "
                          "as the known-size reference for scaling hardware byte counters")
@@ -220,6 +246,10 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof = ctx.profile_read()
+    if args.dump_launches:
+        with open(args.dump_launches, "w") as f:
+            json.dump({"workload": args.workload, "steps": args.steps,
+                       "launches": [name for name, _, _, _ in ctx.profile_launches()]}, f)
     ctx.profile_enable(False)
     if rep.status != strp.OK:
         raise RuntimeError(f"device status {rep.status} in the timed region")
@@ -230,6 +260,7 @@ def main():
     dom_name, dom = max(prof.items(), key=lambda kv: kv[1]["ms"])
     is_gemm = dom_name.startswith("gemm")
     avg_ms = dom["ms"] / dom["launches"]
+    traffic, traffic_note = measured_traffic(args.workload, dom_name)
     if is_gemm:
         # class name gemm_h<p>x<q>_<epilogue>: p, q = fp16 planes per operand; a p x q product issues
         # p*q - (1 if p == q == 2) MFMA passes per algorithmic multiply-add (hi*hi + hi*lo + lo*hi)
@@ -237,15 +268,14 @@ def main():
         passes = npp * npq - (1 if npp * npq == 4 else 0)
         achieved = dom["flops"] / dom["launches"] / (avg_ms * 1e-3) / 1e12
         roof = dict(bound="mfma", kernel=dom_name, achieved=achieved, peak=PEAK_F16_TFLOPS, unit="TFLOP/s",
-                    frac=achieved / PEAK_F16_TFLOPS, traffic=TRAFFIC_GB.get((args.workload, dom_name)),
-                    traffic_unit="GB per launch (FETCH_SIZE + WRITE_SIZE, copy-calibrated; profiles/)",
+                    frac=achieved / PEAK_F16_TFLOPS, traffic=traffic, traffic_unit=traffic_note,
                     algorithmic_gb=dom["bytes"] / dom["launches"] / 1e9, avg_ms=avg_ms,
                     launches_per_step=dom["launches"] / args.steps, mfma_passes=passes,
                     executed=achieved * passes, executed_frac=achieved * passes / PEAK_F16_TFLOPS)
     else:
         achieved = dom["bytes"] / dom["launches"] / (avg_ms * 1e-3) / 1e9
         roof = dict(bound="hbm", kernel=dom_name, achieved=achieved, peak=PEAK_HBM_GBS, unit="GB/s",
-                    frac=achieved / PEAK_HBM_GBS, traffic=TRAFFIC_GB.get((args.workload, dom_name)),
+                    frac=achieved / PEAK_HBM_GBS, traffic=traffic, traffic_unit=traffic_note,
                     avg_ms=avg_ms, launches_per_step=dom["launches"] / args.steps)
     kernels = {n: dict(ms_per_step=v["ms"] / args.steps, launches=v["launches"] // args.steps,
                        tflops=v["flops"] / max(v["ms"], 1e-9) / 1e9, gbs=v["bytes"] / max(v["ms"], 1e-9) / 1e6)

@@ -53,6 +53,13 @@ typedef enum { STRP_SIDE_FC1 = 0, STRP_SIDE_FC2 = 1 } strp_side;
  * module returns STRP_ESTATE if the context's precision has been changed since (initialise the module again). */
 typedef enum { STRP_PREC_FAST = 0, STRP_PREC_SPLIT = 1 } strp_precision;
 
+/* The six token-sized products of one strp_admm_step iteration (C = P Q over the named contraction):
+ *   GRAM  G  = A_S A_S^T          RHS2  R2 = Y A_S^T            RHS1  R1 = Z_S X^T        (over the tokens)
+ *   RESID E  = Y - W2_S relu(Z_S) AUPD  A_S = relu(Z_S) + B E   ZUPD  Z1 = W1_S X         (over channels)
+ * P is the first factor named, Q the second. */
+typedef enum { STRP_PROD_GRAM = 0, STRP_PROD_RHS2 = 1, STRP_PROD_RHS1 = 2, STRP_PROD_RESID = 3, STRP_PROD_AUPD = 4,
+               STRP_PROD_ZUPD = 5, STRP_PROD_COUNT = 6 } strp_product;
+
 typedef struct strp_ctx strp_ctx;
 
 /* Context: host object holding the device id, the caller's stream and the workspace. */
@@ -60,6 +67,12 @@ strp_status strp_create(strp_ctx** out, int device, void* hip_stream);
 strp_status strp_destroy(strp_ctx* ctx);
 const char* strp_last_error(const strp_ctx* ctx);
 strp_status strp_set_precision(strp_ctx* ctx, strp_precision prec);
+/* Under STRP_PREC_SPLIT: how many fp16 planes (1 = hi only, 2 = hi + lo) of its P and of its Q operand one product
+ * of strp_admm_step multiplies; an operand that exists as one plane only (a bf16 input) is not affected.  2 x 2 runs
+ * three matrix-core passes per product, 2 x 1 and 1 x 2 two, 1 x 1 one.  Defaults: see the table in the library's
+ * design notes (the cheapest setting whose free-running error stays below a quarter of the 2e-3 tolerance).
+ * Errors: STRP_EINVAL. */
+strp_status strp_set_product_planes(strp_ctx* ctx, strp_product product, int32_t planes_p, int32_t planes_q);
 /* Caller-owned scratch used by every entry point below (256-byte aligned). */
 strp_status strp_set_workspace(strp_ctx* ctx, void* dev_ptr, size_t bytes);
 /* Synchronise the stream and return the device status word (STRP_OK, STRP_ENOTPD, ...). */
@@ -78,6 +91,9 @@ typedef struct {
 } strp_profile_entry;
 strp_status strp_profile_enable(strp_ctx* ctx, int on);
 strp_status strp_profile_read(strp_ctx* ctx, strp_profile_entry* out_host, int32_t max_entries, int32_t* n_out);
+/* The same records one by one, in the order the work was enqueued (launches = 1 in every entry; at most
+ * max_entries of them): lets an external kernel trace be matched to the library's kernel classes. */
+strp_status strp_profile_launches(strp_ctx* ctx, strp_profile_entry* out_host, int32_t max_entries, int32_t* n_out);
 
 /* ---- module description shared by the stateful entry points ------------------------- */
 typedef struct {

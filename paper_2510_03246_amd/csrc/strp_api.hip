@@ -296,6 +296,7 @@ strp_status strp_create(strp_ctx** out, int device, void* hip_stream) {
   c->device = device;
   c->stream = (hipStream_t)hip_stream;
   c->precision = STRP_PREC_SPLIT;
+  for (int i = 0; i < 8; ++i) c->prod_planes[i][0] = c->prod_planes[i][1] = 2;
   if (hipHostMalloc(&c->pinned, 4096, hipHostMallocDefault) != hipSuccess) {
     delete c;
     return STRP_EHIP;
@@ -349,6 +350,15 @@ strp_status strp_set_precision(strp_ctx* ctx, strp_precision prec) {
   return STRP_OK;
 }
 
+strp_status strp_set_product_planes(strp_ctx* ctx, strp_product product, int32_t planes_p, int32_t planes_q) {
+  if (!ctx) return STRP_EINVAL;
+  if (product < 0 || product >= STRP_PROD_COUNT || planes_p < 1 || planes_p > 2 || planes_q < 1 || planes_q > 2)
+    return fail(ctx, STRP_EINVAL, "set_product_planes: product in [0, %d), planes 1 or 2", (int)STRP_PROD_COUNT);
+  ctx->prod_planes[product][0] = (unsigned char)planes_p;
+  ctx->prod_planes[product][1] = (unsigned char)planes_q;
+  return STRP_OK;
+}
+
 strp_status strp_profile_enable(strp_ctx* ctx, int on) {
   if (!ctx) return STRP_EINVAL;
   if (!ctx->prof) ctx->prof = new (std::nothrow) Profiler();
@@ -381,6 +391,28 @@ strp_status strp_profile_read(strp_ctx* ctx, strp_profile_entry* out_host, int32
     out_host[j].ms += ms;
     out_host[j].flops += r.flops;
     out_host[j].bytes += r.bytes;
+  }
+  *n_out = n;
+  return STRP_OK;
+}
+
+strp_status strp_profile_launches(strp_ctx* ctx, strp_profile_entry* out_host, int32_t max_entries, int32_t* n_out) {
+  if (!ctx || !out_host || !n_out || max_entries <= 0) return ctx ? fail(ctx, STRP_EINVAL, "profile_launches: bad argument") : STRP_EINVAL;
+  *n_out = 0;
+  if (!ctx->prof) return STRP_OK;
+  STRP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  int n = 0;
+  for (auto& r : ctx->prof->recs) {
+    if (n == max_entries) break;
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, r.e0, r.e1) != hipSuccess) ms = -1.0f;
+    memset(&out_host[n], 0, sizeof(out_host[n]));
+    strncpy(out_host[n].name, r.name, sizeof(out_host[n].name) - 1);
+    out_host[n].launches = 1;
+    out_host[n].ms = ms;
+    out_host[n].flops = r.flops;
+    out_host[n].bytes = r.bytes;
+    ++n;
   }
   *n_out = n;
   return STRP_OK;
@@ -504,6 +536,12 @@ strp_status strp_mask_topk_static(strp_ctx* ctx, const float* score, int32_t n, 
 namespace strp {
 
 static inline int planes_for(int dtype, int prec) { return (dtype == STRP_F32 && prec == STRP_PREC_SPLIT) ? 2 : 1; }
+// the operand as product `prod` of strp_admm_step is set to see it: without its lo plane when one plane was asked for
+static inline PlaneOp operand_for(const strp_ctx* ctx, int prod, int side, const PlaneOp& op) {
+  PlaneOp o = op;
+  if (ctx->prod_planes[prod][side] < 2) o.lo = nullptr;
+  return o;
+}
 
 // Planes of `rows` (optionally gathered) activation rows for a product that contracts over the tokens.
 static strp_status make_t_planes(strp_ctx* ctx, Arena& arena, const void* src, int dtype, long long lds, const int* idx, int rows,
@@ -926,13 +964,16 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     STRP_TAKE(ctx, a2, Gd, double, (size_t)s * s);
     PlaneOp Arow;
     STRP_TRY(make_t_planes(ctx, a2, st->A, STRP_F32, lda, st->idx, s, T, 0, npa, &Arow));
-    STRP_TRY(nt_product(ctx, a2, Arow, Arow, s, s, T, 1, nullptr, 0, Gd, s, nullptr, 0));
+    STRP_TRY(nt_product(ctx, a2, operand_for(ctx, STRP_PROD_GRAM, 0, Arow), operand_for(ctx, STRP_PROD_GRAM, 1, Arow), s, s, T, 1, nullptr,
+                        0, Gd, s, nullptr, 0));
     hipLaunchKernelGGL(add_diag_kernel, dim3(blocks_for(s)), dim3(256), 0, ctx->stream, Gd, (long long)s, s, 0.0, sc + SC_LAM2);
     RefitIn ri;
     memset(&ri, 0, sizeof(ri));
     STRP_TAKE(ctx, a2, Ginv, double, (size_t)s * s);
     ri.sys = Gd; ri.sys_ready = 1; ri.Linv = Ginv; ri.linv_ready = 0;
-    ri.Lhs = cv.Yt; ri.Rhs = Arow; ri.m = d; ri.n = s; ri.T = T;
+    ri.Lhs = operand_for(ctx, STRP_PROD_RHS2, 0, cv.Yt);
+    ri.Rhs = operand_for(ctx, STRP_PROD_RHS2, 1, Arow);
+    ri.m = d; ri.n = s; ri.T = T;
     double* sol = nullptr;
     STRP_TRY(ridge_solve(ctx, a2, ri, &sol));
     STRP_TRY(scatter_weights(ctx, sol, s, STRP_SIDE_FC2, st->idx, s, st->W2, d, f));
@@ -1043,7 +1084,9 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     RefitIn ri;
     memset(&ri, 0, sizeof(ri));
     ri.Linv = st->cholH; ri.linv_ready = 1;
-    ri.Lhs = Zrow; ri.Rhs = cv.Xt; ri.m = s; ri.n = d; ri.T = T;
+    ri.Lhs = operand_for(ctx, STRP_PROD_RHS1, 0, Zrow);
+    ri.Rhs = operand_for(ctx, STRP_PROD_RHS1, 1, cv.Xt);
+    ri.m = s; ri.n = d; ri.T = T;
     double* sol = nullptr;
     STRP_TRY(ridge_solve(ctx, a2, ri, &sol));
     STRP_TRY(scatter_weights(ctx, sol, d, STRP_SIDE_FC1, st->idx, s, st->W1, f, d));
@@ -1074,7 +1117,8 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     {  // E = Y - W relu(Z_S), kept only as K8 planes
       GemmP p;
       memset(&p, 0, sizeof(p));
-      p.P = W2Sp; p.Q = Zk8;
+      p.P = operand_for(ctx, STRP_PROD_RESID, 0, W2Sp);
+      p.Q = operand_for(ctx, STRP_PROD_RESID, 1, Zk8);
       p.M = d; p.N = (int)T; p.K = s;
       p.epi = EPI_RESID; p.Yin = st->Y; p.ldy = lda;
       p.k8_hi = ekh; p.k8_lo = ekl; p.k8_kg = plane_kg(d);
@@ -1096,7 +1140,8 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     {  // A_S = relu(Z_S) + B E
       GemmP p;
       memset(&p, 0, sizeof(p));
-      p.P = Bp; p.Q = PlaneOp{ekh, ekl, plane_kg(d), (int)((T + 127) / 128), nullptr};
+      p.P = operand_for(ctx, STRP_PROD_AUPD, 0, Bp);
+      p.Q = operand_for(ctx, STRP_PROD_AUPD, 1, PlaneOp{ekh, ekl, plane_kg(d), (int)((T + 127) / 128), nullptr});
       p.M = s; p.N = (int)T; p.K = d;
       p.epi = EPI_AUPD; p.Zs = st->Z; p.As = st->A; p.lda = lda; p.oidx = st->idx;
       gemm_plan_tiles(p, 1);
@@ -1114,7 +1159,8 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     Arena a2 = arena;
     GemmP p;
     memset(&p, 0, sizeof(p));
-    p.P = W1Sp; p.Q = cv.Xc;
+    p.P = operand_for(ctx, STRP_PROD_ZUPD, 0, W1Sp);
+    p.Q = operand_for(ctx, STRP_PROD_ZUPD, 1, cv.Xc);
     p.M = s; p.N = (int)T; p.K = d;
     p.epi = EPI_ZUPD; p.Zs = st->Z; p.As = st->A; p.lda = lda; p.oidx = st->idx; p.alpha = alpha; p.beta = beta;
     p.write_out = zupd ? 1 : 0;

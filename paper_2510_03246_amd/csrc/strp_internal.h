@@ -18,6 +18,7 @@ struct strp_ctx {
   void* pinned;        // small pinned host buffer for report read-back
   char err[512];
   struct Profiler* prof;  // optional per-kernel event timing (host object)
+  unsigned char prod_planes[8][2];  // fp16 planes (1 or 2) of the P and Q operand per strp_product of strp_admm_step
   hipStream_t aux;        // second stream (default priority) for work that is independent of what `stream` runs
   hipEvent_t ev_fork, ev_join;
 };

@@ -19,12 +19,13 @@ BF16, F32 = 0, 1
 WANDA, LEMMA, GAIN = 0, 1, 2
 SIDE_FC1, SIDE_FC2 = 0, 1
 PREC_FAST, PREC_SPLIT = 0, 1
+PROD_GRAM, PROD_RHS2, PROD_RHS1, PROD_RESID, PROD_AUPD, PROD_ZUPD = range(6)
 STAGE_SELECT, STAGE_REFIT2, STAGE_REFIT1, STAGE_AUPD, STAGE_ZUPD, STAGE_OBJ = 1, 2, 4, 8, 16, 32
 STAGE_ALL = 63
 
 EXPORTS = [
-    "strp_create", "strp_destroy", "strp_last_error", "strp_set_precision", "strp_set_workspace",
-    "strp_poll", "strp_workspace_bytes", "strp_module_cache_bytes", "strp_profile_enable", "strp_profile_read", "strp_gram", "strp_score_alloc", "strp_mask_topk", "strp_mask_topk_static", "strp_topk_workspace_bytes", "strp_weight_energy", "strp_alloc_inverse",
+    "strp_create", "strp_destroy", "strp_last_error", "strp_set_precision", "strp_set_product_planes", "strp_set_workspace",
+    "strp_poll", "strp_workspace_bytes", "strp_module_cache_bytes", "strp_profile_enable", "strp_profile_read", "strp_profile_launches", "strp_gram", "strp_score_alloc", "strp_mask_topk", "strp_mask_topk_static", "strp_topk_workspace_bytes", "strp_weight_energy", "strp_alloc_inverse",
     "strp_refit", "strp_module_init", "strp_admm_step",
 ]
 
@@ -92,10 +93,12 @@ def load_library():
     lib.strp_last_error.argtypes = [vp]
     lib.strp_last_error.restype = C.c_char_p
     lib.strp_set_precision.argtypes = [vp, C.c_int]
+    lib.strp_set_product_planes.argtypes = [vp, C.c_int, i32, i32]
     lib.strp_set_workspace.argtypes = [vp, vp, C.c_size_t]
     lib.strp_poll.argtypes = [vp]
     lib.strp_profile_enable.argtypes = [vp, C.c_int]
     lib.strp_profile_read.argtypes = [vp, C.POINTER(ProfileEntry), i32, C.POINTER(i32)]
+    lib.strp_profile_launches.argtypes = [vp, C.POINTER(ProfileEntry), i32, C.POINTER(i32)]
     lib.strp_workspace_bytes.argtypes = [C.POINTER(ModuleDesc)]
     lib.strp_workspace_bytes.restype = C.c_size_t
     lib.strp_module_cache_bytes.argtypes = [C.POINTER(ModuleDesc)]
@@ -176,6 +179,9 @@ class Context:
     def set_precision(self, prec: int):
         self.check(self.lib.strp_set_precision(self.h, prec))
 
+    def set_product_planes(self, product: int, planes_p: int, planes_q: int):
+        self.check(self.lib.strp_set_product_planes(self.h, product, planes_p, planes_q))
+
     def poll(self) -> int:
         return self.lib.strp_poll(self.h)
 
@@ -189,6 +195,13 @@ class Context:
         self.check(self.lib.strp_profile_read(self.h, buf, 64, C.byref(n)))
         return {buf[i].name.decode(): dict(launches=buf[i].launches, ms=buf[i].ms, flops=buf[i].flops,
                                            bytes=buf[i].bytes) for i in range(n.value)}
+
+    def profile_launches(self, max_entries: int = 4096):
+        """The records since profile_enable one by one, in enqueue order: [(name, ms, flops, bytes), ...]."""
+        buf = (ProfileEntry * max_entries)()
+        n = C.c_int32(0)
+        self.check(self.lib.strp_profile_launches(self.h, buf, max_entries, C.byref(n)))
+        return [(buf[i].name.decode(), buf[i].ms, buf[i].flops, buf[i].bytes) for i in range(n.value)]
 
     def workspace_bytes(self, desc: ModuleDesc) -> int:
         return int(self.lib.strp_workspace_bytes(C.byref(desc)))
