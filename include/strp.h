@@ -271,10 +271,12 @@ typedef struct {
                           cached scoring sums (see sums_cached)                                  */
   int32_t s;           /* kept units of the current mask (host field, set by the library)   */
   int32_t iter;        /* inner iterations done (host field)                                */
-  int32_t sums_cached; /* host field, set by the library: the scoring sums of the pruned rows were accumulated
-                          while the last iteration wrote those rows (1: sum A^2, 2: all four) and sit in `cache`,
-                          so the next selection streams the kept rows only; strp_module_init clears it.  Z, A and
-                          mask must not be changed by the caller between iterations (or set this field to 0).   */
+  int32_t sums_cached; /* host field, set by the library: which of the four token sums of the scores `cache` holds for
+                          EVERY row of the current Z and A (bit 0: sum A^2; bit 1: sum A relu(Z0) and sum Z0 Z; bit 2:
+                          sum Z0^2).  A full iteration leaves them there (the pruned rows' from the pass that writes those
+                          rows, the kept rows' from the epilogues of the a- and z-update products), so the next selection
+                          streams no row; strp_module_init clears it.  A caller that changes Z or A between iterations
+                          must set this field to 0.                                                              */
   int32_t precision;   /* host field: 0 until strp_module_init has run on this state, then 1 + the strp_precision its
                           operand planes were written with; strp_admm_step refuses (STRP_ESTATE) to run on an
                           uninitialised state or under a different precision                                        */

@@ -82,10 +82,16 @@ __device__ __forceinline__ bool decode_tile(const GemmP& p, int bid, int nblocks
 // prove that the state tensors do not overlap.)  Only the stores are predicated.  Offsets are recomputed where
 // they are used rather than kept: 16 64-bit offsets next to 128 accumulators would spill.
 // ZWRITE (EPI_ZUPD only): true = apply the z rule and store Z, false = only accumulate the objective sums.
+// Row sums (AUPD / ZUPD with p.rs_out): rs0 / rs1 collect, per element position e of this lane, the scoring terms of the
+// values just produced (AUPD: a^2 and, with p.rs_z0, a relu(z0); ZUPD: z0 z); they run over the column tiles of the
+// wavefront and are reduced over the lanes by rowsum_flush.
 template <int EPI, bool ZWRITE, bool EDGE>
 __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16, float unscale, int m_tile, int n, int split,
-                                              const int* rowmap, int m_blk, double& red0, double& red1) {
+                                              const int* rowmap, int m_blk, double& red0, double& red1, float (&rs0)[16],
+                                              float (&rs1)[16]) {
   constexpr bool GATHER = (EPI == EPI_AUPD || EPI == EPI_ZUPD);
+  const bool rsum = GATHER && ZWRITE && p.rs_out != nullptr;
+  const bool rs_z0 = rsum && p.rs_z0 != nullptr;
   const bool ncol = !EDGE || n < p.N;
   const int nc = ncol ? n : p.N - 1;
   int rowid[16];         // GATHER: state row of each element's output row (0 for rows past M)
@@ -114,6 +120,15 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
       const long long o = offset(e);
       in0[e] = src[o];
       if (EPI == EPI_ZUPD && !ZWRITE) in1[e] = p.Zs[o];
+    }
+    if (GATHER && ZWRITE) {
+      if (rs_z0) {   // uniform over the grid: a scalar branch around 16 more loads
+#pragma unroll
+        for (int e = 0; e < 16; ++e) in1[e] = p.rs_z0[offset(e)];
+      } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) in1[e] = 0.0f;
+      }
     }
   }
   const float inv_ab = 1.0f / (p.alpha + p.beta);
@@ -151,6 +166,10 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
         const float a = __builtin_fmaxf(in0[e], 0.0f) + v;
         if (ok) p.As[offset(e)] = a;
         outv[r] = ok ? a : 0.0f;
+        if (rsum) {
+          rs0[e] += ok ? a * a : 0.0f;
+          rs1[e] += ok ? a * __builtin_fmaxf(in1[e], 0.0f) : 0.0f;
+        }
       } else {  // EPI_ZUPD
         const float a = in0[e];
         const float z1 = v;
@@ -163,6 +182,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
           const float costp = p.beta * (a - cp) * (a - cp) + p.alpha * (cp - z1) * (cp - z1);
           z = costm < costp ? cm : cp;
           if (ok) p.Zs[offset(e)] = z;
+          if (rs_z0) rs0[e] += ok ? in1[e] * z : 0.0f;
         } else {
           z = in1[e];
         }
@@ -188,33 +208,70 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
   red1 += (double)s1;
 }
 
+// Sum rs[e] over the 32 lanes of each half wavefront (= the 32 columns of a tile; the caller has already added the
+// wavefront's column tiles) and store one value per output row: p.rs_out[(q * slots + slot) * M + row], slot = the
+// wavefront's strip of columns (64 in both kernels).  A halving butterfly: each exchange keeps half of the values a lane still holds, so
+// 8 + 4 + 2 + 1 + 1 shuffles do what 16 five-step reductions would; a lane ends with position e = (lane / 2) % 16.
+// A strip that lies wholly past column N (last block of a ragged N) has no slot and is dropped.
+__device__ __forceinline__ void rowsum_flush(const GemmP& p, const float (&rs)[16], int q, int m_tile, int slot) {
+  const int l5 = threadIdx.x & 31;
+  const bool b4 = l5 & 16, b3 = l5 & 8, b2 = l5 & 4, b1 = l5 & 2;
+  float v8[8], v4[4], v2[2];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v8[i] = (b4 ? rs[8 + i] : rs[i]) + __shfl_xor(b4 ? rs[i] : rs[8 + i], 16, 64);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) v4[i] = (b3 ? v8[4 + i] : v8[i]) + __shfl_xor(b3 ? v8[i] : v8[4 + i], 8, 64);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) v2[i] = (b2 ? v4[2 + i] : v4[i]) + __shfl_xor(b2 ? v4[i] : v4[2 + i], 4, 64);
+  float v1 = (b1 ? v2[1] : v2[0]) + __shfl_xor(b1 ? v2[0] : v2[1], 2, 64);
+  v1 += __shfl_xor(v1, 1, 64);
+  const int e = (l5 >> 1) & 15;
+  const int row = m_tile + 8 * (e >> 2) + (e & 3);
+  if (!(l5 & 1) && row < p.M && slot < p.rs_slots) p.rs_out[((long long)q * p.rs_slots + slot) * p.M + row] = v1;
+}
+
 // Compile-time walk over the WTM x WTN tiles of a wavefront (constant indices keep the accumulators in registers).
 // The scheduling barrier keeps the compiler from hoisting the next tile's loads and offsets over this tile.
 template <int EPI, bool ZWRITE, int WTM, int WTN, int IJ>
 struct EpilogueWalk {
   static __device__ __forceinline__ void run(const GemmP& p, floatx16 (&acc)[WTM][WTN], float unscale, int mbase, int nbase, int split,
-                                             const int* rowmap, int m_blk, double& red0, double& red1) {
+                                             const int* rowmap, int m_blk, double& red0, double& red1, float (&rs0)[16],
+                                             float (&rs1)[16]) {
+    constexpr bool ROWSUMS = (EPI == EPI_AUPD || EPI == EPI_ZUPD) && ZWRITE;
+    if (ROWSUMS && IJ % WTN == 0) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) rs0[e] = rs1[e] = 0.0f;
+    }
     // interior tiles (the common case, decided per wavefront) skip every bounds predicate
     const int mt = mbase + (IJ / WTN) * 32, nt = nbase + (IJ % WTN) * 32;
     const bool edge = __builtin_amdgcn_readfirstlane(mt) + 32 > p.M || __builtin_amdgcn_readfirstlane(nt) + 32 > p.N;
-    if (edge) epilogue_tile<EPI, ZWRITE, true>(p, acc[IJ / WTN][IJ % WTN], unscale, mt, nt, split, rowmap, m_blk, red0, red1);
-    else epilogue_tile<EPI, ZWRITE, false>(p, acc[IJ / WTN][IJ % WTN], unscale, mt, nt, split, rowmap, m_blk, red0, red1);
+    if (edge) epilogue_tile<EPI, ZWRITE, true>(p, acc[IJ / WTN][IJ % WTN], unscale, mt, nt, split, rowmap, m_blk, red0, red1, rs0, rs1);
+    else epilogue_tile<EPI, ZWRITE, false>(p, acc[IJ / WTN][IJ % WTN], unscale, mt, nt, split, rowmap, m_blk, red0, red1, rs0, rs1);
+    if (ROWSUMS && IJ % WTN == WTN - 1 && p.rs_out) {
+      if (EPI == EPI_AUPD) {
+        rowsum_flush(p, rs0, 0, mt, nbase / (32 * WTN));
+        if (p.rs_z0) rowsum_flush(p, rs1, 1, mt, nbase / (32 * WTN));
+      } else if (p.rs_z0) {
+        rowsum_flush(p, rs0, 0, mt, nbase / (32 * WTN));
+      }
+    }
     __builtin_amdgcn_sched_barrier(0);
-    EpilogueWalk<EPI, ZWRITE, WTM, WTN, IJ + 1>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1);
+    EpilogueWalk<EPI, ZWRITE, WTM, WTN, IJ + 1>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1, rs0, rs1);
   }
 };
 template <int EPI, bool ZWRITE, int WTM, int WTN>
 struct EpilogueWalk<EPI, ZWRITE, WTM, WTN, WTM * WTN> {
   static __device__ __forceinline__ void run(const GemmP&, floatx16 (&)[WTM][WTN], float, int, int, int, const int*, int, double&,
-                                             double&) {}
+                                             double&, float (&)[16], float (&)[16]) {}
 };
 template <int EPI, int WTM, int WTN>
 __device__ __forceinline__ void epilogue(const GemmP& p, floatx16 (&acc)[WTM][WTN], float unscale, int mbase, int nbase, int split,
                                          const int* rowmap, int m_blk, double& red0, double& red1) {
+  float rs0[16], rs1[16];
   if (EPI == EPI_ZUPD && !p.write_out)
-    EpilogueWalk<EPI, false, WTM, WTN, 0>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1);
+    EpilogueWalk<EPI, false, WTM, WTN, 0>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1, rs0, rs1);
   else
-    EpilogueWalk<EPI, true, WTM, WTN, 0>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1);
+    EpilogueWalk<EPI, true, WTM, WTN, 0>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1, rs0, rs1);
 }
 
 }  // namespace strp

@@ -31,24 +31,12 @@ __device__ __forceinline__ float bf16hi(unsigned int w) { return __builtin_bit_c
 // ---------------------------------------------------------------------------------------------
 template <bool A_BF16, bool FULL>
 __global__ __launch_bounds__(256) void row_sums_kernel(const void* Av, const float* Z, const float* Z0, long long ld,
-                                                       long long T, int rows, double* sums, int32_t* status,
-                                                       const uint8_t* kept_mask, const double* cached) {
+                                                       long long T, int rows, double* sums, int32_t* status) {
   const int r = blockIdx.x;
   const int tid = threadIdx.x;
   double g = 0.0, e = 0.0, u = 0.0, v = 0.0;
   const long long T8 = T & ~7LL;
-  // a row whose sums were accumulated when it was last written is not streamed again (block-uniform branch)
-  const bool have = cached && !kept_mask[r];
-  if (have) {
-    if (tid == 0) {
-      g = cached[r];
-      if (FULL) {
-        e = cached[(long long)rows + r];
-        u = cached[2LL * rows + r];
-        v = cached[3LL * rows + r];
-      }
-    }
-  } else if (A_BF16 && !FULL) {
+  if (A_BF16 && !FULL) {
     const uint4* a8 = (const uint4*)((const unsigned short*)Av + (long long)r * ld);
     for (long long c = tid; c < T8 / 8; c += 256) {
       const uint4 w = a8[c];
@@ -129,28 +117,66 @@ __global__ __launch_bounds__(256) void row_sums_kernel(const void* Av, const flo
 }
 
 strp_status launch_row_sums(strp_ctx* ctx, const void* A, int a_dtype, const float* Z, const float* Z0, long long ld,
-                            long long T, int rows, int mode, double* sums, const uint8_t* kept_mask, const double* cached,
-                            int n_cached) {
+                            long long T, int rows, int mode, double* sums) {
   const bool full = mode != STRP_SCORE_WANDA;
-  if (!kept_mask || !cached) {
-    cached = nullptr;
-    n_cached = 0;
-  }
-  const int streamed = rows - n_cached;
   if (full && a_dtype != STRP_F32) return fail(ctx, STRP_EINVAL, "score: LEMMA/GAIN need fp32 auxiliaries");
   dim3 grid(rows), block(256);
   const double es = a_dtype == STRP_BF16 ? 2.0 : 4.0;
-  ProfScope ps(ctx, full ? "row_sums_full" : "row_sums_wanda", (full ? 8.0 : 2.0) * (double)streamed * (double)T,
-               (full ? 12.0 : es) * (double)streamed * (double)T);
+  ProfScope ps(ctx, full ? "row_sums_full" : "row_sums_wanda", (full ? 8.0 : 2.0) * (double)rows * (double)T,
+               (full ? 12.0 : es) * (double)rows * (double)T);
   if (full)
-    hipLaunchKernelGGL((row_sums_kernel<false, true>), grid, block, 0, ctx->stream, A, Z, Z0, ld, T, rows, sums, ctx->status_dev, kept_mask,
-                       cached);
+    hipLaunchKernelGGL((row_sums_kernel<false, true>), grid, block, 0, ctx->stream, A, Z, Z0, ld, T, rows, sums, ctx->status_dev);
   else if (a_dtype == STRP_BF16)
-    hipLaunchKernelGGL((row_sums_kernel<true, false>), grid, block, 0, ctx->stream, A, Z, Z0, ld, T, rows, sums, ctx->status_dev, kept_mask,
-                       (const double*)nullptr);
+    hipLaunchKernelGGL((row_sums_kernel<true, false>), grid, block, 0, ctx->stream, A, Z, Z0, ld, T, rows, sums, ctx->status_dev);
   else
-    hipLaunchKernelGGL((row_sums_kernel<false, false>), grid, block, 0, ctx->stream, A, Z, Z0, ld, T, rows, sums, ctx->status_dev, kept_mask,
-                       cached);
+    hipLaunchKernelGGL((row_sums_kernel<false, false>), grid, block, 0, ctx->stream, A, Z, Z0, ld, T, rows, sums, ctx->status_dev);
+  STRP_HIP(ctx, hipGetLastError());
+  return STRP_OK;
+}
+
+// Scoring sums of the kept rows from the strips the a- and z-update epilogues wrote: part[q][strip][m] (fp32, one value
+// per output row m and 64-column strip) -> rowsums[qdst[q] * f + idx[m]] (fp64).  Two fixed-order levels: 16 chunks of
+// strips per row, then the 16 chunk sums.
+constexpr int RS_CHUNKS = 16;
+__global__ __launch_bounds__(256) void rowsum_chunk_kernel(const float* part, int slots, int M, double* chunk_sums) {
+  const int m = blockIdx.x * 256 + threadIdx.x;
+  const int c = blockIdx.y, q = blockIdx.z;
+  if (m >= M) return;
+  const int per = (slots + RS_CHUNKS - 1) / RS_CHUNKS;
+  const int s0 = c * per, s1 = (s0 + per < slots) ? s0 + per : slots;
+  const float* src = part + (long long)q * slots * M + m;
+  double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;   // four independent chains keep four loads in flight
+  int sidx = s0;
+  for (; sidx + 3 < s1; sidx += 4) {
+    a0 += (double)src[(long long)sidx * M];
+    a1 += (double)src[(long long)(sidx + 1) * M];
+    a2 += (double)src[(long long)(sidx + 2) * M];
+    a3 += (double)src[(long long)(sidx + 3) * M];
+  }
+  for (; sidx < s1; ++sidx) a0 += (double)src[(long long)sidx * M];
+  chunk_sums[((long long)q * RS_CHUNKS + c) * M + m] = (a0 + a1) + (a2 + a3);
+}
+__global__ __launch_bounds__(256) void rowsum_final_kernel(const double* chunk_sums, int M, const int32_t* idx, double* rowsums, int f,
+                                                           int qdst0, int qdst1, int32_t* status) {
+  const int m = blockIdx.x * 256 + threadIdx.x;
+  const int q = blockIdx.y;
+  if (m >= M) return;
+  double t = 0.0;
+#pragma unroll
+  for (int c = 0; c < RS_CHUNKS; ++c) t += chunk_sums[((long long)q * RS_CHUNKS + c) * M + m];
+  rowsums[(long long)(q == 0 ? qdst0 : qdst1) * f + idx[m]] = t;
+  if (!(fabs(t) <= 1.79e308)) atomicCAS(status, 0, (int)STRP_ENONFINITE);
+}
+
+size_t rowsum_scratch_bytes(int nq, int M) { return sizeof(double) * (size_t)nq * RS_CHUNKS * (size_t)M; }
+
+strp_status launch_rowsum_reduce(strp_ctx* ctx, const float* part, int nq, int slots, int M, const int32_t* idx, double* rowsums, int f,
+                                 int qdst0, int qdst1, double* chunk_sums) {
+  if (nq <= 0 || M <= 0 || slots <= 0) return STRP_OK;
+  ProfScope ps(ctx, "rowsum_reduce", 0.0, 4.0 * (double)nq * (double)slots * (double)M);
+  hipLaunchKernelGGL(rowsum_chunk_kernel, dim3((M + 255) / 256, RS_CHUNKS, nq), dim3(256), 0, ctx->stream, part, slots, M, chunk_sums);
+  hipLaunchKernelGGL(rowsum_final_kernel, dim3((M + 255) / 256, nq), dim3(256), 0, ctx->stream, (const double*)chunk_sums, M, idx, rowsums, f,
+                     qdst0, qdst1, ctx->status_dev);
   STRP_HIP(ctx, hipGetLastError());
   return STRP_OK;
 }

@@ -264,6 +264,8 @@ __global__ void axpby_scalar_kernel(double* sc, int dst, double a, int s0, doubl
 static unsigned blocks_for(long long n) { return (unsigned)((n + 255) / 256); }
 
 // scalar slots of strp_module_state::scalars
+// bits of strp_module_state::sums_cached: which token sums cv.rowsums holds for EVERY row of the current state
+enum { SUMS_G = 1, SUMS_EU = 2, SUMS_V = 4 };
 enum { SC_LAM1 = 0, SC_LAM2 = 1, SC_SUMA0 = 2, SC_TRH = 3, SC_T1 = 4, SC_T2 = 5, SC_T3 = 6, SC_T4 = 7, SC_T5 = 8,
        SC_TAU = 9, SC_ENERGY = 10, SC_TMP0 = 11, SC_TMP1 = 12, SC_TMP2 = 13, SC_TMP3 = 14, SC_W2SQ = 15, SC_W1SQ = 16, SC_COUNT = 32 };
 
@@ -301,17 +303,6 @@ strp_status strp_create(strp_ctx** out, int device, void* hip_stream) {
     delete c;
     return STRP_EHIP;
   }
-  // Optional second stream for independent chains (same, default, priority), off unless STRP_TWO_STREAMS=1: the
-  // fp64 factorisation chains do overlap with the large products, but their small kernels then wait for a CU
-  // behind the product's resident blocks (measured: 0.7 % faster end to end, per-class timings no longer additive).
-  const char* two = getenv("STRP_TWO_STREAMS");
-  if (two && two[0] == '1' && (hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking) != hipSuccess ||
-      hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess)) {
-    (void)hipGetLastError();
-    if (c->aux) (void)hipStreamDestroy(c->aux);
-    c->aux = nullptr;
-  }
   // device address of this GPU's copy of the static select scratch (the device was made current above)
   if (device < MAX_DEVICES && !g_topk_scratch[device]) {
     void* ptr = nullptr;
@@ -329,12 +320,6 @@ strp_status strp_create(strp_ctx** out, int device, void* hip_stream) {
 
 strp_status strp_destroy(strp_ctx* ctx) {
   if (!ctx) return STRP_EINVAL;
-  if (ctx->aux) {
-    (void)hipStreamSynchronize(ctx->aux);
-    (void)hipStreamDestroy(ctx->aux);
-    (void)hipEventDestroy(ctx->ev_fork);
-    (void)hipEventDestroy(ctx->ev_join);
-  }
   if (ctx->pinned) (void)hipHostFree(ctx->pinned);
   delete ctx->prof;
   delete ctx;
@@ -464,7 +449,7 @@ strp_status strp_score_alloc(strp_ctx* ctx, const strp_score_in* in, float* unit
     STRP_TRY(launch_colnorm2(ctx, in->What, in->w_dtype, in->w_rows, in->n_channels, in->ldw, n2buf));
     n2 = n2buf;
   }
-  STRP_TRY(launch_row_sums(ctx, in->A, in->a_dtype, in->Z, in->Z0, in->ld, in->T, in->n_channels, in->mode, sums, nullptr, nullptr, 0));
+  STRP_TRY(launch_row_sums(ctx, in->A, in->a_dtype, in->Z, in->Z0, in->ld, in->T, in->n_channels, in->mode, sums));
   STRP_TRY(launch_unit_scores(ctx, sums, n2, in->n_channels, in->group, in->mode, unit_score, energies + layer_idx));
   if (r_out) STRP_TRY(launch_alloc(ctx, energies, L, n_units, group_id, rbar, temperature, rmax, 0, r_out, nprune_out));
   return STRP_OK;
@@ -590,19 +575,6 @@ static strp_status make_weight_planes(strp_ctx* ctx, Arena& arena, const void* s
   return STRP_OK;
 }
 
-strp_status stream_fork(strp_ctx* ctx) {
-  if (!ctx->aux) return STRP_OK;
-  STRP_HIP(ctx, hipEventRecord(ctx->ev_fork, ctx->stream));
-  STRP_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->ev_fork, 0));
-  return STRP_OK;
-}
-strp_status stream_join(strp_ctx* ctx) {
-  if (!ctx->aux) return STRP_OK;
-  STRP_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->aux));
-  STRP_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));
-  return STRP_OK;
-}
-
 // number of K splits of a token-contraction product: enough blocks to fill the chip and fp32
 // accumulation chains of at most 8192 tokens (partials are then summed in fp64)
 static int plan_splits(int ntiles, long long K) {
@@ -663,23 +635,13 @@ static strp_status ridge_solve(strp_ctx* ctx, Arena& arena, const RefitIn& in, d
   const bool factor = !in.linv_ready;
   if (factor) {
     if (in.sys_ready == 0) STRP_TRY(f32_to_f64_ridge(ctx, in.Gram, in.ldg, in.sys, n, n, in.lam, in.lam_dev));
-    // The factorisation is a long chain of small kernels that leaves most of the chip idle; the right-hand side
-    // is one large product that does not depend on it.  They run side by side on the two streams, each in its
-    // own part of the arena.
     const size_t fbytes = (((size_t)((n + NB - 1) / NB) * NB * NB * 8 + 255) & ~size_t(255)) + (((size_t)n * n * 8 + 255) & ~size_t(255));
     STRP_TAKE(ctx, arena, fscratch, char, fbytes);
-    STRP_TRY(stream_fork(ctx));
-    if (ctx->aux) {
-      AuxScope on_aux(ctx);
-      STRP_TRY(factor_and_invert(ctx, Arena(fscratch, fbytes), in.sys, n, in.Linv));
-    } else {
-      STRP_TRY(factor_and_invert(ctx, Arena(fscratch, fbytes), in.sys, n, in.Linv));
-    }
+    STRP_TRY(factor_and_invert(ctx, Arena(fscratch, fbytes), in.sys, n, in.Linv));
   }
   STRP_TAKE(ctx, arena, R, double, (size_t)m * n);
   STRP_TAKE(ctx, arena, tmp, double, (size_t)m * n);
   STRP_TRY(nt_product(ctx, arena, in.Lhs, in.Rhs, m, n, in.T, 0, nullptr, 0, R, n, nullptr, 0));
-  if (factor) STRP_TRY(stream_join(ctx));
   STRP_TRY(apply_inverse_right(ctx, in.Linv, n, R, m, tmp));
   *sol_out = R;
   return STRP_OK;
@@ -759,7 +721,9 @@ size_t strp_workspace_bytes(const strp_module_desc* desc) {
                 al(plane_elems(d, T) * 2) + al(d * d * 8) + al(d * d * 4) /* objective: E by tokens, E E^T, M^-2 */ +
                 /* the M-inverse chain keeps its block while the fc1 refit runs beside it */
                 al(nt_partial_elems((int)d, (int)d, (long long)kp, 1) * 4) + al(d * d * 8) + al(invd_max) +
-                2 * (al(256) + 2 * al(plane_elems(km, d) * 2)) + (al(256) + 2 * al(plane_elems(d, d) * 2)) + al(plane_elems(T, km) * 2) + 8192;
+                2 * (al(256) + 2 * al(plane_elems(km, d) * 2)) + (al(256) + 2 * al(plane_elems(d, d) * 2)) + al(plane_elems(T, km) * 2) + 8192 +
+                /* strip sums of the kept rows from the a- and z-update epilogues */
+                al(2 * (size_t)((T + 63) / 64) * km * 4) + al((size_t)((T + 63) / 64) * km * 4) + al(rowsum_scratch_bytes(2, (int)km));
   return (init > step ? init : step) + (1 << 20);
 }
 
@@ -942,19 +906,23 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   Arena arena(ctx);
 
   // ---- S2/S4: scores and top-k ---------------------------------------------------------
+  // The token sums every score is built from live in the module cache (cv.rowsums, [4][f]): sum A^2, sum A relu(Z0),
+  // sum Z0 Z, sum Z0^2.  A full iteration leaves them there for every row -- the pruned rows' from the pass that writes
+  // those rows, the kept rows' from the epilogues of the a- and z-update products (sum Z0^2 never changes after it has
+  // been streamed once) -- so that only a selection on a state the library did not produce streams the rows.
+  const bool wanda = params->mode == STRP_SCORE_WANDA;
   if (do_select) {
-    Arena a2 = arena;
-    STRP_TAKE(ctx, a2, sums, double, 4 * (size_t)f);
-    // rows pruned by the previous iteration had their sums accumulated while that iteration wrote them
-    const bool cached = st->sums_cached >= (params->mode == STRP_SCORE_WANDA ? 1 : 2) && st->s > 0;
-    STRP_TRY(launch_row_sums(ctx, st->A, STRP_F32, st->Z, st->Z0, lda, T, f, params->mode, sums, cached ? st->mask : nullptr,
-                             cached ? cv.rowsums : nullptr, cached ? f - st->s : 0));
-    STRP_TRY(launch_unit_scores(ctx, sums, st->n2, f, 1, params->mode, st->score, sc + SC_ENERGY));
+    const bool have = (st->sums_cached & SUMS_G) && (wanda || ((st->sums_cached & SUMS_EU) && (st->sums_cached & SUMS_V)));
+    if (!have) {
+      STRP_TRY(launch_row_sums(ctx, st->A, STRP_F32, st->Z, st->Z0, lda, T, f, params->mode, cv.rowsums));
+      st->sums_cached = wanda ? (st->sums_cached & SUMS_V) | SUMS_G : SUMS_G | SUMS_EU | SUMS_V;
+    }
+    STRP_TRY(launch_unit_scores(ctx, cv.rowsums, st->n2, f, 1, params->mode, st->score, sc + SC_ENERGY));
     STRP_TRY(launch_topk(ctx, st->score, f, params->k, 1, st->mask, st->idx, (float*)(sc + SC_TAU), nullptr, 0));
     st->s = params->k;
   }
-  // the cached sums describe the state and the mask as the last iteration left them: void them before either changes
-  if (do_select || (stages & (STRP_STAGE_AUPD | STRP_STAGE_ZUPD))) st->sums_cached = 0;
+  // the sums describe the state as it is now: void them before an update changes it (sum Z0^2 stays valid)
+  if (stages & (STRP_STAGE_AUPD | STRP_STAGE_ZUPD)) st->sums_cached &= SUMS_V;
   const int s = st->s;
   const long long sp = round_up(s, 8);
 
@@ -991,11 +959,9 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     STRP_TRY(make_weight_planes(ctx, arena, W2S, SRC_F32, sp, d, s, 0, npa, &W2Sp));
   }
   // ---- a-update, part 1: B = W^T M^-1 with M = (beta/alpha) I + W W^T, W = W2[:, S] -------------------------
-  // Needs only the refitted W2 and is a chain of small fp64 kernels that leaves most of the chip idle, so it runs
-  // on the second stream beside the fc1 refit.  Its buffers come from the base arena and stay until the step ends.
+  // Needs only the refitted W2.  Its buffers come from the base arena and stay until the step ends.
   PlaneOp Bp;
   memset(&Bp, 0, sizeof(Bp));
-  bool chain_forked = false;
   // First objective term when the a-update runs in the same call: the update solves its least-squares problem exactly, so
   //   Y - W A_S = E - W W^T M^-1 E = (M - W W^T) M^-1 E = (beta/alpha) M^-1 E,   E = Y - W relu(Z_S),
   // and |Y - W A_S|_F^2 = (beta/alpha)^2 <M^-2, E E^T>: a d x d Gram of E over the tokens (half the work of the product
@@ -1015,10 +981,6 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
                           (((size_t)d * d * 8 + al) & ~al) + (512 + 2 * ((plane_elems(s, d) * 2 + al) & ~al)) +
                           (512 + 2 * ((plane_elems(d, d) * 2 + al) & ~al)) + 4096;
     STRP_TAKE(ctx, arena, cblock, char, cbytes);
-    STRP_TRY(stream_fork(ctx));
-    chain_forked = true;
-    AuxScope on_aux(ctx);
-    if (!ctx->aux) ctx->stream = on_aux.saved;   // no second stream: the chain simply runs in order
     Arena a2(cblock, cbytes);
     STRP_TRY(nt_product(ctx, a2, W2Sp, W2Sp, d, d, sp, 1, nullptr, 0, Md, d, nullptr, 0));
     hipLaunchKernelGGL(add_diag_kernel, dim3(blocks_for(d)), dim3(256), 0, ctx->stream, Md, (long long)d, d, params->beta / params->alpha, (const double*)nullptr);
@@ -1099,10 +1061,24 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   }
 
   const bool fuse_pruned = (stages & STRP_STAGE_AUPD) && (stages & STRP_STAGE_ZUPD);
+  // scoring sums of the kept rows, collected by the two epilogues that write those rows (64-column strips, fp32)
+  const int rs_slots = (int)((T + 63) / 64);
+  float* rsA = nullptr;
+  float* rsZ = nullptr;
+  double* rs_chunks = nullptr;
+  if (fuse_pruned) {
+    STRP_TAKE(ctx, arena, rsa_, float, (size_t)(wanda ? 1 : 2) * rs_slots * s);
+    STRP_TAKE(ctx, arena, rsc_, double, rowsum_scratch_bytes(2, s) / sizeof(double));
+    rsA = rsa_;
+    rs_chunks = rsc_;
+    if (!wanda) {
+      STRP_TAKE(ctx, arena, rsz_, float, (size_t)rs_slots * s);
+      rsZ = rsz_;
+    }
+  }
   // ---- S7: a-update in residual (Woodbury) form ------------------------------------------------
   //   A_S = relu(Z_S) + W^T M^-1 (Y - W relu(Z_S)),  M = (beta/alpha) I + W W^T,  W = W2[:, S];  A_j = relu(Z_j) for pruned j
   if (stages & STRP_STAGE_AUPD) {
-    if (chain_forked) STRP_TRY(stream_join(ctx));
     Arena a2 = arena;
     PlaneOp Zk8 = Zk8pre;
     if (!z_planes_once) {
@@ -1144,8 +1120,10 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
       p.Q = operand_for(ctx, STRP_PROD_AUPD, 1, PlaneOp{ekh, ekl, plane_kg(d), (int)((T + 127) / 128), nullptr});
       p.M = s; p.N = (int)T; p.K = d;
       p.epi = EPI_AUPD; p.Zs = st->Z; p.As = st->A; p.lda = lda; p.oidx = st->idx;
+      p.rs_out = rsA; p.rs_z0 = (rsA && !wanda) ? st->Z0 : nullptr; p.rs_slots = rs_slots;
       gemm_plan_tiles(p, 1);
       STRP_TRY(launch_gemm(ctx, p));
+      if (rsA) STRP_TRY(launch_rowsum_reduce(ctx, rsA, wanda ? 1 : 2, rs_slots, s, st->idx, cv.rowsums, f, 0, 1, rs_chunks));
     }
     if (!fuse_pruned) {
       ProfScope ps(ctx, "pruned_rows_a", 0.0, 8.0 * (double)(f - s) * (double)T);
@@ -1164,19 +1142,23 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     p.M = s; p.N = (int)T; p.K = d;
     p.epi = EPI_ZUPD; p.Zs = st->Z; p.As = st->A; p.lda = lda; p.oidx = st->idx; p.alpha = alpha; p.beta = beta;
     p.write_out = zupd ? 1 : 0;
+    p.rs_out = (zupd && rsZ) ? rsZ : nullptr; p.rs_z0 = p.rs_out ? st->Z0 : nullptr; p.rs_slots = rs_slots;
     gemm_plan_tiles(p, 1);
     const int nb = gemm_grid_blocks(p);
     STRP_TAKE(ctx, a2, red, double, 2 * (size_t)(nb > f ? nb : f));
     p.red = red;
     STRP_TRY(launch_gemm(ctx, p));
     STRP_TRY(launch_block_sum(ctx, red, nb, sc + SC_TMP0, sc + SC_TMP1, 1.0, 1.0));
+    if (p.rs_out) STRP_TRY(launch_rowsum_reduce(ctx, rsZ, 1, rs_slots, s, st->idx, cv.rowsums, f, 2, 2, rs_chunks));
     {
       ProfScope ps(ctx, fuse_pruned ? "pruned_rows_az" : "pruned_rows_z", 0.0, (fuse_pruned ? 12.0 : 8.0) * (double)(f - s) * (double)T);
       const bool keep_sums = fuse_pruned && zupd;   // the rows are in registers in their final state: sum them for the next selection
-      const float* z0_for_sums = params->mode == STRP_SCORE_WANDA ? nullptr : st->Z0;
+      const float* z0_for_sums = wanda ? nullptr : st->Z0;
       hipLaunchKernelGGL(pruned_rows_kernel, dim3(f), dim3(256), 0, ctx->stream, st->mask, st->Z, st->A, lda, T, fuse_pruned ? 2 : 1, alpha, beta,
                          zupd ? 1 : 0, red, keep_sums ? z0_for_sums : nullptr, keep_sums ? cv.rowsums : nullptr, f);
-      if (keep_sums) st->sums_cached = z0_for_sums ? 2 : 1;
+      // every row's sums are now in place: the kept rows' from the two epilogues, the pruned rows' from this pass
+      // (which also rewrites their sum Z0^2; the kept rows' is only there if it was streamed before)
+      if (keep_sums) st->sums_cached = (st->sums_cached & SUMS_V) | SUMS_G | (z0_for_sums ? SUMS_EU : 0);
     }
     STRP_TRY(launch_block_sum(ctx, red, f, sc + SC_TMP2, sc + SC_TMP3, 1.0, 1.0));
     hipLaunchKernelGGL(axpby_scalar_kernel, dim3(1), dim3(1), 0, ctx->stream, sc, (int)SC_T2, params->beta / (double)T, (int)SC_TMP0, params->beta / (double)T, (int)SC_TMP2);

@@ -19,8 +19,6 @@ struct strp_ctx {
   char err[512];
   struct Profiler* prof;  // optional per-kernel event timing (host object)
   unsigned char prod_planes[8][2];  // fp16 planes (1 or 2) of the P and Q operand per strp_product of strp_admm_step
-  hipStream_t aux;        // second stream (default priority) for work that is independent of what `stream` runs
-  hipEvent_t ev_fork, ev_join;
 };
 
 struct Profiler;
@@ -36,19 +34,6 @@ struct ProfScope {
   int rec;
   ProfScope(strp_ctx* c, const char* name, double flops, double bytes) : ctx(c), rec(prof_begin(c, name, flops, bytes)) {}
   ~ProfScope() { prof_end(ctx, rec); }
-};
-
-// ---- fork / join between the context's two streams -----------------------------------------------
-// fork: everything enqueued on ctx->stream so far happens before what follows on ctx->aux.
-// AuxScope: while alive, ctx->stream IS the aux stream, so every helper enqueues there.
-// join: everything enqueued on ctx->aux so far happens before what follows on ctx->stream.
-strp_status stream_fork(strp_ctx* ctx);
-strp_status stream_join(strp_ctx* ctx);
-struct AuxScope {
-  strp_ctx* ctx;
-  hipStream_t saved;
-  explicit AuxScope(strp_ctx* c) : ctx(c), saved(c->stream) { c->stream = c->aux; }
-  ~AuxScope() { ctx->stream = saved; }
 };
 
 // ---- error helpers -------------------------------------------------------------------
@@ -136,6 +121,12 @@ struct GemmP {
   unsigned short* k8_hi;  // optional operand planes of the produced values with k = output row, r = output column
   unsigned short* k8_lo;  //   (STORE: C, INITZ: relu(C), RESID: Y - C; not offered by AUPD / ZUPD); k8_kg = M / 8 groups, ceil(N/128) panels
   long long k8_kg;
+  // AUPD / ZUPD, optional: scoring sums of the rows being written, one fp32 partial per output row and 64-column strip,
+  //   rs_out[(q * rs_slots + strip) * M + m];  AUPD: q = 0 sum a^2, q = 1 sum a relu(z0) (iff rs_z0); ZUPD: q = 0 sum z0 z
+  //   (iff rs_z0).  rs_z0 = the Z0 state tensor (leading dimension lda, rows gathered like Zs).  rs_slots = ceil(N / 64).
+  float* rs_out;
+  const float* rs_z0;
+  int rs_slots;
 };
 
 strp_status launch_gemm(strp_ctx* ctx, GemmP& p);
@@ -188,11 +179,13 @@ strp_status f32_to_f64_ridge(strp_ctx* ctx, const float* Af, long long ldf, doub
                              double lam, const double* lam_dev);
 
 // ---- reductions, scores, allocation, select (score_select.hip) ------------------------------
-// cached (optional, fp32 A only): rows with kept_mask[r] == 0 take their sums from cached[4][rows] instead of
-// being streamed; n_cached = number of such rows (for the traffic figure of the timing record)
 strp_status launch_row_sums(strp_ctx* ctx, const void* A, int a_dtype, const float* Z, const float* Z0,
-                            long long ld, long long T, int rows, int mode, double* sums /*[4][rows]*/,
-                            const uint8_t* kept_mask, const double* cached, int n_cached);
+                            long long ld, long long T, int rows, int mode, double* sums /*[4][rows]*/);
+// part[nq][slots][M] fp32 strip sums written by the AUPD / ZUPD epilogues -> rowsums[qdst * f + idx[m]] (fp64);
+// chunk_sums: rowsum_scratch_bytes(nq, M) bytes of scratch.
+strp_status launch_rowsum_reduce(strp_ctx* ctx, const float* part, int nq, int slots, int M, const int32_t* idx, double* rowsums, int f,
+                                 int qdst0, int qdst1, double* chunk_sums);
+size_t rowsum_scratch_bytes(int nq, int M);
 strp_status launch_colnorm2(strp_ctx* ctx, const void* W, int w_dtype, int rows, int cols, long long ldw,
                             double* n2);
 strp_status launch_unit_scores(strp_ctx* ctx, const double* sums, const double* n2, int n_channels, int group,

@@ -241,19 +241,23 @@ def test_gain_select_inside_a_step(run):
 
 
 def test_second_selection_from_cached_sums(run):
-    """The iteration kept the scoring sums of the rows it pruned: the next selection (kept rows streamed, pruned rows
-    from the cache) gives the scores and the mask of a selection that streams every row, and sampled scores equal
-    n2_j * sum_t A_jt^2 of the state (runs last: it restores what a selection overwrites)."""
+    """The iteration kept the scoring sums of every row (pruned rows: the pass that writes them; kept rows: the epilogues
+    of the a- and z-update products): the next selection streams nothing and gives the scores and the mask of a selection
+    that streams every row, and sampled scores equal n2_j * sum_t A_jt^2 of the state (restores what a selection
+    overwrites)."""
     mod, cfg, k = run["mod"], run["cfg"], run["k"]
-    assert mod.state.sums_cached == 1
+    assert mod.state.sums_cached & 1
     saved = {n: getattr(mod, n).clone() for n in ("mask", "idx", "score")}
     saved_scalars = mod.scalars.clone()
     sel = strp.Params(ALPHA, BETA, DELTA, strp.WANDA, 1, k, strp.STAGE_SELECT)
+    mod.ctx.profile_enable(True)
     mod.step(sel)
-    assert mod.state.sums_cached == 0
+    assert not any(n.startswith("row_sums") for n in mod.ctx.profile_read())      # nothing was streamed
+    mod.ctx.profile_enable(False)
     score_cached, mask_cached = mod.score.clone(), mod.mask.clone()
-    mod.mask.copy_(saved["mask"])
+    mod.state.sums_cached = 0
     mod.step(sel)
+    assert mod.state.sums_cached & 1
     assert torch.allclose(score_cached, mod.score, rtol=1e-6, atol=0)
     assert torch.equal(mask_cached, mod.mask)
     rng = np.random.default_rng(3)

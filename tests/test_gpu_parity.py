@@ -515,10 +515,12 @@ def test_first_objective_term_identity_matches_the_product(ctx, alpha, beta, d, 
         assert np.allclose(np.array(direct.terms[1:]), np.array(rep.terms[1:]), rtol=1e-6)
 
 
-@pytest.mark.parametrize("mode,level", [(strp.WANDA, 1), (strp.GAIN, 2), (strp.LEMMA, 2)])
-def test_cached_sums_of_pruned_rows_match_streamed_sums(ctx, mode, level):
-    """The scoring sums a full iteration keeps for the rows it pruned give the same scores and mask as streaming
-    every row again, and the oracle's scores (ragged T: vector body and scalar tail of the row loop)."""
+@pytest.mark.parametrize("mode,flags", [(strp.WANDA, 1), (strp.GAIN, 7), (strp.LEMMA, 7)])
+def test_cached_sums_match_streamed_sums(ctx, mode, flags):
+    """A full iteration leaves the scoring sums of every row in the module cache (the pruned rows' from the pass that
+    writes them, the kept rows' from the epilogues of the a- and z-update products): a selection from them gives the same
+    scores and mask as streaming every row again, and the oracle's scores (ragged T and k: edge tiles of the epilogues,
+    vector body and scalar tail of the row loop)."""
     base = inputs.CONFIGS["opt125m"]
     d, f, T, k = 136, 520, 1003, 200
     cfg = type(base)(**{**base.__dict__, "d": d, "f": f, "T": T, "n_outlier": 2})
@@ -532,25 +534,36 @@ def test_cached_sums_of_pruned_rows_match_streamed_sums(ctx, mode, level):
     for it in range(2):
         mod.step(p)
         orc.admm_step(st, k, 1.0, 1.0, omode, select=True)
-    assert mod.state.sums_cached == level
-    old_mask = mod.mask.clone()
+    assert mod.state.sums_cached == flags
     sel = _params(k, mode, reselect=1, stages=strp.STAGE_SELECT)
-    mod.step(sel)                       # pruned rows from the cache
-    assert mod.state.sums_cached == 0   # a selection voids it
+    mod.step(sel)                       # from the cached sums: no row is streamed
+    assert mod.state.sums_cached == flags
     score_cached, mask_cached = mod.score.clone(), mod.mask.clone()
-    mod.mask.copy_(old_mask)
+    mod.state.sums_cached = 0           # as after a change of the state from outside
     mod.step(sel)                       # every row streamed
+    assert mod.state.sums_cached == flags
     assert torch.allclose(score_cached, mod.score, rtol=1e-6, atol=0)
     assert torch.equal(mask_cached, mod.mask)
     score = orc.module_scores(st, omode)
-    assert np.allclose(mod.score.cpu().numpy(), score, rtol=5e-3, atol=5e-3 * float(np.abs(score).max()))
+    assert np.allclose(mod.score.cpu().numpy(), score, rtol=2e-4, atol=2e-4 * float(np.abs(score).max()))
     # a selection in another mode must not use sums the cache does not hold
     mod.step(p)
-    if level == 1:
+    if mode == strp.WANDA:
         mod.step(_params(k, strp.GAIN, reselect=1, stages=strp.STAGE_SELECT))
         orc.admm_step(st, k, 1.0, 1.0, omode, select=True)
         score = orc.module_scores(st, orc.GAIN)
-        assert np.allclose(mod.score.cpu().numpy(), score, rtol=5e-3, atol=5e-3 * float(np.abs(score).max()))
+        assert np.allclose(mod.score.cpu().numpy(), score, rtol=2e-4, atol=2e-4 * float(np.abs(score).max()))
+    # a GAIN iteration on a state whose sum Z0^2 was never streamed (the mask came from a WANDA selection, no selection
+    # in this call) must not claim that it holds all four sums
+    mod.init(p)
+    mod.step(_params(k, strp.WANDA, reselect=1, stages=strp.STAGE_SELECT))
+    mod.step(_params(k, strp.GAIN, reselect=0))
+    assert mod.state.sums_cached == 3
+    mod.step(_params(k, strp.GAIN, reselect=1, stages=strp.STAGE_SELECT))
+    assert mod.state.sums_cached == 7
+    streamed = mod.score.clone()
+    mod.step(_params(k, strp.GAIN, reselect=1, stages=strp.STAGE_SELECT))
+    assert torch.equal(streamed, mod.score)
 
 
 @pytest.mark.parametrize("name,d,f,T,k,dt", [("all kept", 72, 264, 520, 264, "bf16"), ("k=8", 136, 520, 1003, 8, "bf16"),
