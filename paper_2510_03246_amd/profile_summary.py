@@ -85,10 +85,10 @@ def classify(dispatches, launches):
     tail = gemm_idx[len(gemm_idx) - len(gemm_records):]
     for i, cls in zip(tail, gemm_records):
         dispatches[i]["cls"] = cls
-    # the timed region starts at the scoring pass ahead of its first GEMM
+    # the timed region starts at the selection ahead of its first GEMM (scores, then top-k, then the plane writer)
     start = tail[0] if tail else len(dispatches)
     for i in range(start, max(start - 12, -1), -1):
-        if "row_sums_kernel" in dispatches[i]["name"]:
+        if "unit_scores_kernel" in dispatches[i]["name"]:
             start = i
             break
     for d in dispatches[start:]:

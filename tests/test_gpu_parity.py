@@ -732,3 +732,42 @@ def test_precision_change_between_init_and_step_is_refused(ctx):
         assert rep.status == strp.OK
     finally:
         ctx.set_precision(strp.PREC_SPLIT)
+
+
+def test_product_planes_trade_accuracy_for_passes(ctx):
+    """strp_set_product_planes: with every product on both planes (the default) three free-running iterations stay
+    within a quarter of the tolerance; dropping the lo plane of one operand in the four three-pass products, or of
+    every operand, is coarser but still a valid (finite, mask-preserving at this size) run; bad arguments are refused."""
+    base = inputs.CONFIGS["opt125m"]
+    d, f, T, k = 264, 1048, 3000, 419
+    cfg = type(base)(**{**base.__dict__, "d": d, "f": f, "T": T, "n_outlier": 3})
+    m = inputs.make_ffn_module(cfg, 0, 1, "cuda", ld=(T + 7) // 8 * 8)
+    mod = strp.FFNModule(ctx, m["W1hat"], m["W2hat"], m["X"], T)
+    p = _params(k)
+    st = orc.module_init(m["W1hat"].double().cpu().numpy(), m["W2hat"].double().cpu().numpy(), m["X"][:, :T].double().cpu().numpy())
+    for it in range(3):
+        orc.admm_step(st, k, 1.0, 1.0, orc.WANDA, select=(it == 0))
+    settings = {"2x2": [], "2x1": [(strp.PROD_GRAM, 2, 1), (strp.PROD_RHS2, 2, 1), (strp.PROD_RESID, 2, 1), (strp.PROD_AUPD, 2, 1)],
+                "1x1": [(q, 1, 1) for q in range(6)]}
+    worst = {}
+    try:
+        for name, setting in settings.items():
+            for q in range(6):
+                ctx.set_product_planes(q, 2, 2)
+            for q, a, b in setting:
+                ctx.set_product_planes(q, a, b)
+            mod.init(p)
+            for it in range(3):
+                rep = mod.step(p)
+            assert rep.status == strp.OK
+            assert np.array_equal(mod.mask.cpu().numpy(), st.mask)
+            worst[name] = max(_compare_state(mod, st, T).values())
+    finally:
+        for q in range(6):
+            ctx.set_product_planes(q, 2, 2)
+    assert worst["2x2"] < TOL_F / 4, worst
+    assert worst["2x2"] < worst["2x1"] < TOL_F and worst["2x2"] < worst["1x1"] < 5 * TOL_F, worst
+    for bad in ((6, 2, 2), (-1, 1, 1), (0, 0, 2), (0, 2, 3)):
+        with pytest.raises(strp.StrpError) as e:
+            ctx.set_product_planes(*bad)
+        assert e.value.status == strp.EINVAL
