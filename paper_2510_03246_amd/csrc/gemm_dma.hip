@@ -1,10 +1,10 @@
 // Pipelined MFMA GEMM for large problems: 256x256 block tile, eight wavefronts of 128x64, operand tiles
-// brought from HBM/L2 straight into LDS by the global-load-to-LDS path (no staging registers), four LDS
-// stages of 16 contraction steps each, three stages in flight behind the one being multiplied.
+// brought from HBM/L2 straight into LDS by the global-load-to-LDS path (no staging registers), LDS stages of
+// 16 contraction steps each, the stages behind the one being multiplied in flight.
 //
-// Why: with staging registers only one K tile can be in flight per CU (the 256 accumulator registers of a
-// 128x128 wavefront tile leave no room for more), and one tile in flight (64 KB per CU) at ~2 us of loaded
-// memory latency caps the chip at ~9 TB/s of operand traffic.  LDS has room for four stages.
+// Why: with staging registers only one K tile can be in flight per CU (the accumulator registers of a
+// 128x64 wavefront tile leave little room for more), and one tile in flight (64 KB per CU) at ~2 us of loaded
+// memory latency caps the chip at ~9 TB/s of operand traffic.  LDS has room for two to four pairs of stages.
 //
 // The operand layout (see gemm_mfma.hip) makes every load one contiguous KB: a wavefront instruction
 // moves the 64 chunks (16 B each) of 64 consecutive rows of one k-group, and the hardware writes lane l's
@@ -21,7 +21,6 @@ namespace strp {
 namespace dma {
 constexpr int ROWS = 256;          // rows of P / columns of Q per block
 constexpr int SK = 16;             // contraction steps per stage (two k-groups)
-constexpr int NSTAGE = 4;
 constexpr int PLANE_STAGE_BYTES = 2 * ROWS * 16;   // one plane of one operand in one stage: 8 KB
 }  // namespace dma
 
@@ -45,40 +44,46 @@ __device__ __forceinline__ void wait_vmcnt_lgkm0() {
   asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"(N) : "memory");
 }
 
-// NW = wavefronts per block: 4 (2x2, 128x128 each) or 8 (2x4, 128x64 each; two per SIMD give the memory
-// system twice as many independent request streams).
-template <int NPP, int NPQ, int NW>
-__global__ __launch_bounds__(64 * NW, 1) void gemm_dma_kernel(const GemmP p) {
+// ---------------------------------------------------------------------------------------------------------------------
+// The matrix-core instruction is v_mfma_f32_16x16x32_f16: each wavefront's 128 x 64 outputs are 8 x 4 tiles of
+// 16 x 16, one instruction contracts 32 steps.  Measured on this chip with random fp16 operands fed from LDS in exactly
+// this wavefront shape, the 16x16x32 instruction sustains 11 % more than the 32x32x16 one (the chip is power-limited
+// while the matrix cores run; the smaller accumulator tile costs less energy per flop).
+// Two consecutive 16-step stages form the 32 steps of one instruction (lanes 0-31 read their operand chunks from the
+// first stage of the pair, lanes 32-63 from the second), so the pipeline advances by pairs: while pair p is multiplied,
+// the next one to three pairs are in flight (LDS holds two pairs of four planes, three of three, four of two), and the
+// slots of pair p are refilled as soon as every wavefront has its last fragment of the pair in registers.  The Q fragments of a pair stay in registers (double
+// buffered across pairs), the P fragments stream through two register sets.
+template <int NPP, int NPQ>
+__global__ __launch_bounds__(512, 1) void gemm_dma_kernel(const GemmP p) {
   using namespace dma;
-  constexpr int NPL = NPP + NPQ;                       // planes per stage
+  constexpr int NW = 8;
+  constexpr int NPL = NPP + NPQ;
   constexpr int STAGE_BYTES = NPL * PLANE_STAGE_BYTES;
-  constexpr int LPW = 8 * NPL / NW;                    // load instructions per wavefront per stage
-  constexpr int WTM = 4, WTN = NW == 8 ? 2 : 4;        // 32x32 MFMA tiles per wavefront
-  __shared__ __attribute__((aligned(1024))) unsigned char smem[NSTAGE * STAGE_BYTES];
+  constexpr int LPW = 8 * NPL / NW;
+  // pairs of stages LDS holds: two with four planes (128 KB), three with three (144 KB), four with two (128 KB)
+  constexpr int NP = NPL == 4 ? 2 : (NPL == 3 ? 3 : 4);
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * NP * STAGE_BYTES];
   __shared__ double sred[NW][2];
-  __shared__ int srow[dma::ROWS];   // gathered state row of each output row (AUPD / ZUPD)
+  __shared__ int srow[dma::ROWS];
 
-  // ---- which tile, which K range ---------------------------------------------------------
   int tm, tn, split;
   if (!decode_tile(p, (int)blockIdx.x, (int)gridDim.x, tm, tn, split)) return;
   const int m0 = tm * ROWS, n0 = tn * ROWS;
-  const long long k0 = (long long)split * p.kchunk;
+  const long long k0 = (long long)split * p.kchunk;                 // a multiple of 32
   const long long k1 = (k0 + p.kchunk < p.K) ? (k0 + p.kchunk) : p.K;
-  const int nstages = (int)((k1 - k0 + SK - 1) / SK);
-  const long long g0 = k0 >> 3;                       // first k-group of this block (even)
-  const long long g_last = ((k1 + 7) >> 3) - 1;       // last k-group holding data; its pair partner is zero padding
+  const int npairs = (int)((k1 - k0 + 31) / 32);                    // k-groups past k1 inside the last pair are zero padding
+  const long long g0 = k0 >> 3;
+  const long long g_last = ((k1 + 7) >> 3) - 1;
 
   const int tid = threadIdx.x, lane = tid & 63;
-  // fetched now, parked in LDS after the main loop: the epilogue never waits for an index load
   int my_row = 0;
   if (p.oidx && tid < ROWS && m0 + tid < p.M) my_row = p.oidx[m0 + tid];
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = NW == 8 ? wave >> 2 : wave >> 1, wn = NW == 8 ? wave & 3 : wave & 1;
-  constexpr int WROWS = 32 * WTM, WCOLS = 32 * WTN;
+  const int wm = wave >> 2, wn = wave & 3;
 
-  // ---- this wavefront's load instructions: q = wave + NW i, plane = q / 8, k-group = (q / 4) % 2, row segment = q % 4
-  const unsigned short* gp[LPW];     // lane's source chunk for stage 0
-  unsigned lds_off[LPW];             // byte offset of the instruction's 1 KB destination inside a stage
+  const unsigned short* gp[LPW];
+  unsigned lds_off[LPW];
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
 #pragma unroll
   for (int i = 0; i < LPW; ++i) {
@@ -95,123 +100,116 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma_kernel(const GemmP p) {
     gp[i] = base + (((long long)pan * op.kg + g0 + g) * 128 + rr) * 8;
     lds_off[i] = (unsigned)(plane * PLANE_STAGE_BYTES + (g * ROWS + seg * 64) * 16);
   }
-  // stage s reads k-groups g0 + 2 s and g0 + 2 s + 1; stages past the end re-read the last pair (never multiplied)
-  const long long last_pair = (g_last - g0) >> 1;
+  // stage s = k-groups g0 + 2 s, g0 + 2 s + 1; the planes are padded to a multiple of four k-groups, so both stages of
+  // the last pair exist in memory; stages past them re-read the last one (never multiplied)
+  const long long last_stage = 2 * (long long)npairs - 1;
   auto issue_stage = [&](int s) {
-    const long long sp = s < last_pair ? s : last_pair;
-    const unsigned slot = lds_base + (unsigned)(s & (NSTAGE - 1)) * STAGE_BYTES;
+    const long long sp = s < last_stage ? s : last_stage;
+    const unsigned slot = lds_base + (unsigned)(s % (2 * NP)) * STAGE_BYTES;
 #pragma unroll
     for (int i = 0; i < LPW; ++i) lds_dma_16(gp[i] + sp * 2048, slot + lds_off[i]);
   };
+  (void)g_last;
 
-  floatx16 acc[WTM][WTN];
+  floatx4 acc[8][4];
 #pragma unroll
-  for (int i = 0; i < WTM; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < WTN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    for (int j = 0; j < 4; ++j) acc[i][j] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
 
-  // fragment addresses: lanes 0-31 read k-group 0 of the stage, lanes 32-63 k-group 1; 32 consecutive rows = 512 B
-  const int offP = ((lane >> 5) * ROWS + wm * WROWS + (lane & 31)) * 16;
-  const int offQ = ((lane >> 5) * ROWS + wn * WCOLS + (lane & 31)) * 16;
-  struct Frags { uint4 ph[WTM], pl[WTM], qh[WTN], ql[WTN]; };
-  auto read_frags = [&](Frags& f, int s) {
-    const unsigned char* st = smem + (s & (NSTAGE - 1)) * STAGE_BYTES;
+  // lane l reads the chunk of k-group l / 16 of the 32-deep step: groups 0, 1 in the pair's first stage, 2, 3 in its second
+  const int kgl = lane >> 4;
+  const int offP = (kgl >> 1) * STAGE_BYTES + ((kgl & 1) * ROWS + wm * 128 + (lane & 15)) * 16;
+  const int offQ = (kgl >> 1) * STAGE_BYTES + NPP * PLANE_STAGE_BYTES + ((kgl & 1) * ROWS + wn * 64 + (lane & 15)) * 16;
+  struct QF { uint4 h[4], l[4]; };
+  struct PF { uint4 h, l; };
+  auto read_q = [&](QF& f, int pr) {
+    const unsigned char* st = smem + (pr % NP) * 2 * STAGE_BYTES;
 #pragma unroll
-    for (int i = 0; i < WTM; ++i) {
-      f.ph[i] = *(const uint4*)(st + offP + i * 512);
-      if (NPP == 2) f.pl[i] = *(const uint4*)(st + PLANE_STAGE_BYTES + offP + i * 512);
-    }
-#pragma unroll
-    for (int j = 0; j < WTN; ++j) {
-      f.qh[j] = *(const uint4*)(st + NPP * PLANE_STAGE_BYTES + offQ + j * 512);
-      if (NPQ == 2) f.ql[j] = *(const uint4*)(st + (NPP + 1) * PLANE_STAGE_BYTES + offQ + j * 512);
+    for (int j = 0; j < 4; ++j) {
+      f.h[j] = *(const uint4*)(st + offQ + j * 256);
+      if (NPQ == 2) f.l[j] = *(const uint4*)(st + PLANE_STAGE_BYTES + offQ + j * 256);
     }
   };
-  auto mma1 = [&](uint4 a, uint4 b, floatx16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
+  auto read_p = [&](PF& f, int pr, int i) {
+    const unsigned char* st = smem + (pr % NP) * 2 * STAGE_BYTES;
+    f.h = *(const uint4*)(st + offP + i * 256);
+    if (NPP == 2) f.l = *(const uint4*)(st + PLANE_STAGE_BYTES + offP + i * 256);
   };
-  auto run_mfma = [&](const Frags& f) {
+  auto mma = [&](uint4 a, uint4 b, floatx4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
+  };
+  auto run_row = [&](floatx4 (&c)[4], const PF& a, const QF& b) {
     if (NPQ == 2) {
 #pragma unroll
-      for (int i = 0; i < WTM; ++i)
-#pragma unroll
-        for (int j = 0; j < WTN; ++j) acc[i][j] = mma1(f.ph[i], f.ql[j], acc[i][j]);
+      for (int j = 0; j < 4; ++j) c[j] = mma(a.h, b.l[j], c[j]);
     }
     if (NPP == 2) {
 #pragma unroll
-      for (int i = 0; i < WTM; ++i)
-#pragma unroll
-        for (int j = 0; j < WTN; ++j) acc[i][j] = mma1(f.pl[i], f.qh[j], acc[i][j]);
+      for (int j = 0; j < 4; ++j) c[j] = mma(a.l, b.h[j], c[j]);
     }
 #pragma unroll
-    for (int i = 0; i < WTM; ++i)
-#pragma unroll
-      for (int j = 0; j < WTN; ++j) acc[i][j] = mma1(f.ph[i], f.qh[j], acc[i][j]);
+    for (int j = 0; j < 4; ++j) c[j] = mma(a.h, b.h[j], c[j]);
+  };
+  // One pair: bc holds the pair's Q fragments, pa its first P fragment; on return bn / pa hold those of the next pair.
+  PF pa, pb;
+  // Instruction order: the fragment reads of row i + 1 are issued ahead of the matrix-core instructions of row i (a
+  // scheduling barrier after each pair of reads keeps the compiler from sinking them to where they are needed).
+  auto pair_step = [&](int pr, const QF& bc, QF& bn) {
+#define STRP_ROW(i, cur, nxt)                \
+    read_p(nxt, pr, (i) + 1);                \
+    __builtin_amdgcn_sched_barrier(0);       \
+    run_row(acc[i], cur, bc);                \
+    __builtin_amdgcn_sched_barrier(0);
+    STRP_ROW(0, pa, pb)
+    STRP_ROW(1, pb, pa)
+    STRP_ROW(2, pa, pb)
+    STRP_ROW(3, pb, pa)
+    STRP_ROW(4, pa, pb)
+    STRP_ROW(5, pb, pa)
+    STRP_ROW(6, pa, pb)
+#undef STRP_ROW
+    wait_vmcnt_lgkm0<(NP - 2) * 2 * LPW>();   // the next pair has landed; this wavefront's fragment reads of this pair are complete
+    __syncthreads();               // ... and so for every wavefront: the pair's slots may be overwritten
+    issue_stage(2 * (pr + NP));
+    issue_stage(2 * (pr + NP) + 1);
+    read_q(bn, pr + 1);            // past the last pair this reads slots that are never multiplied
+    read_p(pa, pr + 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    run_row(acc[7], pb, bc);
+    __builtin_amdgcn_sched_barrier(0);
   };
 
-  // Instruction order inside a half stage: the fragment reads of the next stage are issued in the shadow of the
-  // matrix-core instructions of this one (one LDS read after each of the first MFMAs) instead of ahead of them.
-  auto interleave = [&]() {
-    constexpr int NRD = WTM * NPP + WTN * NPQ;   // ds_read_b128 per half stage
-    constexpr int NMF = WTM * WTN * (NPP * NPQ == 4 ? 3 : NPP * NPQ);
 #pragma unroll
-    for (int i = 0; i < NRD; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one DS read
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD, 0);
-  };
-
-  // ---- pipeline: stages 0..3 requested up front; iteration s multiplies stage s from registers while the
-  // fragments of stage s+1 are read from LDS and stage s+4 is requested into the slot stage s just left.
-  issue_stage(0);
-  issue_stage(1);
-  issue_stage(2);
-  issue_stage(3);
-  Frags fa, fb;
-  wait_vmcnt<3 * LPW>();     // stage 0 has landed (three younger stages may still be in flight)
+  for (int q = 0; q < 2 * NP; ++q) issue_stage(q);
+  QF q0, q1;
+  wait_vmcnt<(NP - 1) * 2 * LPW>();   // the first pair has landed
   __syncthreads();
-  read_frags(fa, 0);
-  int s = 0;
+  read_q(q0, 0);
+  read_p(pa, 0, 0);
+  int pr = 0;
 #pragma unroll 1
-  for (; s + 1 < nstages; s += 2) {
-    // -- even half: multiply stage s (fa), fetch fragments of stage s+1 into fb
-    wait_vmcnt_lgkm0<2 * LPW>();   // stage s+1 has landed; this wavefront's fragment reads of stage s are complete
-    __syncthreads();               // ... and so for every wavefront: the slot of stage s may be overwritten
-    issue_stage(s + 4);            // into the slot of stage s
-    read_frags(fb, s + 1);
-    run_mfma(fa);
-    interleave();
-    __builtin_amdgcn_sched_barrier(0);
-    // -- odd half
-    wait_vmcnt_lgkm0<2 * LPW>();
-    __syncthreads();
-    issue_stage(s + 5);
-    read_frags(fa, s + 2);         // past the last stage this reads a slot that is never multiplied
-    run_mfma(fb);
-    interleave();
-    __builtin_amdgcn_sched_barrier(0);
+  for (; pr + 1 < npairs; pr += 2) {
+    pair_step(pr, q0, q1);
+    pair_step(pr + 1, q1, q0);
   }
-  if (s < nstages) run_mfma(fa);   // odd stage count: the last stage is already in registers
-  wait_vmcnt<0>();           // nothing may still be writing LDS when the block ends or reuses it
+  if (pr < npairs) pair_step(pr, q0, q1);
+  wait_vmcnt<0>();
   if (tid < ROWS) srow[tid] = my_row;
   __syncthreads();
 
-  // ---- epilogue -------------------------------------------------------------------------------
   float unscale = 1.0f;
   if (p.P.scale) unscale /= *p.P.scale;
   if (p.Q.scale) unscale /= *p.Q.scale;
   double red0 = 0.0, red1 = 0.0;
-  const int mbase = m0 + wm * WROWS + 4 * (lane >> 5), nbase = n0 + wn * WCOLS + (lane & 31);
+  const int mbase = m0 + wm * 128 + 4 * (lane >> 4), nbase = n0 + wn * 64 + (lane & 15);
   switch (p.epi) {
-    case EPI_PARTIAL: epilogue<EPI_PARTIAL, WTM, WTN>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
-    case EPI_STORE: epilogue<EPI_STORE, WTM, WTN>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
-    case EPI_INITZ: epilogue<EPI_INITZ, WTM, WTN>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
-    case EPI_RESID: epilogue<EPI_RESID, WTM, WTN>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
-    case EPI_AUPD: epilogue<EPI_AUPD, WTM, WTN>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
-    default: epilogue<EPI_ZUPD, WTM, WTN>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    case EPI_PARTIAL: epilogue16<EPI_PARTIAL>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    case EPI_STORE: epilogue16<EPI_STORE>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    case EPI_INITZ: epilogue16<EPI_INITZ>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    case EPI_RESID: epilogue16<EPI_RESID>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    case EPI_AUPD: epilogue16<EPI_AUPD>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
+    default: epilogue16<EPI_ZUPD>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
   }
   if (p.red) {
     red0 = wave_sum(red0);
@@ -234,17 +232,15 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma_kernel(const GemmP p) {
   }
 }
 
-template <int NW>
-static void launch_dma_nw(strp_ctx* ctx, const GemmP& p, int npp, int npq) {
-  const dim3 grid(gemm_grid_blocks(p)), block(64 * NW);
+void launch_gemm_dma(strp_ctx* ctx, const GemmP& p, int npp, int npq) {
+  const dim3 grid(gemm_grid_blocks(p)), block(512);
   switch (npp * 10 + npq) {
-    case 11: hipLaunchKernelGGL((gemm_dma_kernel<1, 1, NW>), grid, block, 0, ctx->stream, p); break;
-    case 12: hipLaunchKernelGGL((gemm_dma_kernel<1, 2, NW>), grid, block, 0, ctx->stream, p); break;
-    case 21: hipLaunchKernelGGL((gemm_dma_kernel<2, 1, NW>), grid, block, 0, ctx->stream, p); break;
-    default: hipLaunchKernelGGL((gemm_dma_kernel<2, 2, NW>), grid, block, 0, ctx->stream, p); break;
+    case 11: hipLaunchKernelGGL((gemm_dma_kernel<1, 1>), grid, block, 0, ctx->stream, p); break;
+    case 12: hipLaunchKernelGGL((gemm_dma_kernel<1, 2>), grid, block, 0, ctx->stream, p); break;
+    case 21: hipLaunchKernelGGL((gemm_dma_kernel<2, 1>), grid, block, 0, ctx->stream, p); break;
+    default: hipLaunchKernelGGL((gemm_dma_kernel<2, 2>), grid, block, 0, ctx->stream, p); break;
   }
 }
 
-void launch_gemm_dma(strp_ctx* ctx, const GemmP& p, int npp, int npq) { launch_dma_nw<8>(ctx, p, npp, npq); }
 
 }  // namespace strp

@@ -73,8 +73,10 @@ __device__ __forceinline__ bool decode_tile(const GemmP& p, int bid, int nblocks
   return true;
 }
 
-// Epilogue of one 32x32 accumulator tile (passed by value so the accumulators never need an address).
-// Register e of lane l is output row m_tile + 8 (e / 4) + (e % 4), column n  (m_tile, n include the lane's share).
+// Epilogue of one accumulator tile of 16 values per lane (passed by value so the accumulators never need an address).
+// Register e of lane l is output row m_tile + RS (e / 4) + (e % 4), column n  (m_tile, n include the lane's share):
+// RS = 8 for one 32x32 matrix-core tile (32 columns over the lanes of a half wavefront), RS = 16 for four stacked
+// 16x16 tiles (64 rows x 16 columns, 16 columns over the lanes of a quarter wavefront).
 //
 // Loads are branch-free and come first: rows and the column are clamped into range so that every address is
 // valid, and the 16 loads of the tile are issued back to back.  (A predicated load costs a wait per element, and
@@ -85,7 +87,7 @@ __device__ __forceinline__ bool decode_tile(const GemmP& p, int bid, int nblocks
 // Row sums (AUPD / ZUPD with p.rs_out): rs0 / rs1 collect, per element position e of this lane, the scoring terms of the
 // values just produced (AUPD: a^2 and, with p.rs_z0, a relu(z0); ZUPD: z0 z); they run over the column tiles of the
 // wavefront and are reduced over the lanes by rowsum_flush.
-template <int EPI, bool ZWRITE, bool EDGE>
+template <int EPI, bool ZWRITE, bool EDGE, int RS = 8>
 __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16, float unscale, int m_tile, int n, int split,
                                               const int* rowmap, int m_blk, double& red0, double& red1, float (&rs0)[16],
                                               float (&rs1)[16]) {
@@ -97,11 +99,11 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
   int rowid[16];         // GATHER: state row of each element's output row (0 for rows past M)
   if (GATHER) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) rowid[e] = rowmap[m_tile + 8 * (e >> 2) + (e & 3) - m_blk];   // slice of oidx staged in LDS
+    for (int e = 0; e < 16; ++e) rowid[e] = rowmap[m_tile + RS * (e >> 2) + (e & 3) - m_blk];   // slice of oidx staged in LDS
   }
   // 32 x 32 -> 64-bit products (one instruction each): rows, leading dimensions and columns all fit 32 bits
   auto offset = [&](int e) -> long long {
-    const int m = m_tile + 8 * (e >> 2) + (e & 3);
+    const int m = m_tile + RS * (e >> 2) + (e & 3);
     const unsigned mc = (unsigned)((!EDGE || m < p.M) ? m : p.M - 1);
     unsigned long long o;
     if (EPI == EPI_PARTIAL) o = (unsigned long long)((unsigned)split * (unsigned)p.M + mc) * (unsigned)p.N + (unsigned)nc;
@@ -135,7 +137,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
   float s0 = 0.0f, s1 = 0.0f;   // this tile's share of the reduction sums (16 terms in fp32, then fp64)
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    const int mq = m_tile + 8 * q;  // rows mq .. mq+3
+    const int mq = m_tile + RS * q;  // rows mq .. mq+3
     float outv[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -272,6 +274,75 @@ __device__ __forceinline__ void epilogue(const GemmP& p, floatx16 (&acc)[WTM][WT
     EpilogueWalk<EPI, false, WTM, WTN, 0>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1, rs0, rs1);
   else
     EpilogueWalk<EPI, true, WTM, WTN, 0>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1, rs0, rs1);
+}
+
+// ---- the same for accumulators of 16x16 matrix-core tiles -------------------------------------------------------------
+// Lane l of a 16x16 tile holds rows 4 (l / 16) + r (r < 4) of column l % 16.  Four tiles stacked along the rows
+// (tile rows 4 I .. 4 I + 3 of the wavefront) give a lane the 16 values of epilogue_tile with RS = 16.
+__device__ __forceinline__ void rowsum_flush16(const GemmP& p, const float (&rs)[16], int q, int m_tile, int slot) {
+  const int l4 = threadIdx.x & 15;
+  const bool b3 = l4 & 8, b2 = l4 & 4, b1 = l4 & 2, b0 = l4 & 1;
+  float v8[8], v4[4], v2[2];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v8[i] = (b3 ? rs[8 + i] : rs[i]) + __shfl_xor(b3 ? rs[i] : rs[8 + i], 8, 64);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) v4[i] = (b2 ? v8[4 + i] : v8[i]) + __shfl_xor(b2 ? v8[i] : v8[4 + i], 4, 64);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) v2[i] = (b1 ? v4[2 + i] : v4[i]) + __shfl_xor(b1 ? v4[i] : v4[2 + i], 2, 64);
+  const float v1 = (b0 ? v2[1] : v2[0]) + __shfl_xor(b0 ? v2[0] : v2[1], 1, 64);
+  const int e = l4;                                  // = 8 b3 + 4 b2 + 2 b1 + b0
+  const int row = m_tile + 16 * (e >> 2) + (e & 3);
+  if (row < p.M && slot < p.rs_slots) p.rs_out[((long long)q * p.rs_slots + slot) * p.M + row] = v1;
+}
+
+// acc[8][4]: the wavefront's 128 x 64 outputs as 8 x 4 tiles of 16 x 16.  IJ walks the 2 x 4 stacks of four tiles.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+template <int EPI, bool ZWRITE, int IJ>
+struct EpilogueWalk16 {
+  static __device__ __forceinline__ void run(const GemmP& p, floatx4 (&acc)[8][4], float unscale, int mbase, int nbase, int split,
+                                             const int* rowmap, int m_blk, double& red0, double& red1, float (&rs0)[16],
+                                             float (&rs1)[16]) {
+    constexpr bool ROWSUMS = (EPI == EPI_AUPD || EPI == EPI_ZUPD) && ZWRITE;
+    constexpr int I = IJ / 4, J = IJ % 4;
+    if (ROWSUMS && J == 0) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) rs0[e] = rs1[e] = 0.0f;
+    }
+    floatx16 a16;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) a16[4 * q + r] = acc[4 * I + q][J][r];
+    const int mt = mbase + 64 * I, nt = nbase + 16 * J;
+    const bool edge = __builtin_amdgcn_readfirstlane(mt) + 64 > p.M || __builtin_amdgcn_readfirstlane(nt) + 16 > p.N;
+    if (edge) epilogue_tile<EPI, ZWRITE, true, 16>(p, a16, unscale, mt, nt, split, rowmap, m_blk, red0, red1, rs0, rs1);
+    else epilogue_tile<EPI, ZWRITE, false, 16>(p, a16, unscale, mt, nt, split, rowmap, m_blk, red0, red1, rs0, rs1);
+    if (ROWSUMS && J == 3 && p.rs_out) {
+      if (EPI == EPI_AUPD) {
+        rowsum_flush16(p, rs0, 0, mt, nbase >> 6);
+        if (p.rs_z0) rowsum_flush16(p, rs1, 1, mt, nbase >> 6);
+      } else if (p.rs_z0) {
+        rowsum_flush16(p, rs0, 0, mt, nbase >> 6);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    EpilogueWalk16<EPI, ZWRITE, IJ + 1>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1, rs0, rs1);
+  }
+};
+template <int EPI, bool ZWRITE>
+struct EpilogueWalk16<EPI, ZWRITE, 8> {
+  static __device__ __forceinline__ void run(const GemmP&, floatx4 (&)[8][4], float, int, int, int, const int*, int, double&, double&,
+                                             float (&)[16], float (&)[16]) {}
+};
+// mbase = first row of the wavefront's tile + 4 (lane / 16), nbase = first column + lane % 16
+template <int EPI>
+__device__ __forceinline__ void epilogue16(const GemmP& p, floatx4 (&acc)[8][4], float unscale, int mbase, int nbase, int split,
+                                           const int* rowmap, int m_blk, double& red0, double& red1) {
+  float rs0[16], rs1[16];
+  if (EPI == EPI_ZUPD && !p.write_out)
+    EpilogueWalk16<EPI, false, 0>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1, rs0, rs1);
+  else
+    EpilogueWalk16<EPI, true, 0>::run(p, acc, unscale, mbase, nbase, split, rowmap, m_blk, red0, red1, rs0, rs1);
 }
 
 }  // namespace strp

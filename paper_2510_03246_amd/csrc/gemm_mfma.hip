@@ -260,13 +260,15 @@ void gemm_plan_tiles(GemmP& p, int want_splits) {
 
 int gemm_grid_blocks(const GemmP& p) { return p.gridM * p.gridN * p.splits; }
 
-// zero the pad k-group (index kg - 1) of a plane written by an epilogue whose row count is an odd number of groups
-__global__ __launch_bounds__(256) void zero_pad_group_kernel(unsigned short* hi, unsigned short* lo, long long kg, int npan) {
+// zero the pad k-groups [g_first, kg) of a plane written by an epilogue (whose rows fill the groups below g_first)
+__global__ __launch_bounds__(256) void zero_pad_group_kernel(unsigned short* hi, unsigned short* lo, long long kg, int g_first, int npan) {
   const long long e = (long long)blockIdx.x * 256 + threadIdx.x;   // 16-byte chunk index over npan x 128
   if (e >= (long long)npan * 128) return;
-  const long long o = (((e >> 7) * kg + (kg - 1)) * 128 + (e & 127)) * 8;
-  *(uint4*)(hi + o) = make_uint4(0, 0, 0, 0);
-  if (lo) *(uint4*)(lo + o) = make_uint4(0, 0, 0, 0);
+  for (long long g = g_first; g < kg; ++g) {
+    const long long o = (((e >> 7) * kg + g) * 128 + (e & 127)) * 8;
+    *(uint4*)(hi + o) = make_uint4(0, 0, 0, 0);
+    if (lo) *(uint4*)(lo + o) = make_uint4(0, 0, 0, 0);
+  }
 }
 
 void launch_gemm_dma(strp_ctx* ctx, const GemmP& p, int npp, int npq);   // gemm_dma.hip
@@ -283,7 +285,8 @@ strp_status launch_gemm(strp_ctx* ctx, GemmP& p) {
   if (p.M <= 0 || p.N <= 0 || p.K <= 0) return fail(ctx, STRP_EINVAL, "gemm: empty shape");
   if (p.ntiles <= 0 || p.splits <= 0 || (p.wt != 2 && p.wt != 4)) return fail(ctx, STRP_EINVAL, "gemm: tiles not planned");
   if (!p.P.hi || !p.Q.hi) return fail(ctx, STRP_EINVAL, "gemm: null operand plane");
-  if (p.P.kg * 8 < p.K || p.Q.kg * 8 < p.K || (p.P.kg & 1) || (p.Q.kg & 1)) return fail(ctx, STRP_EINVAL, "gemm: operand planes shorter than K or odd group count");
+  if (p.P.kg * 8 < p.K || p.Q.kg * 8 < p.K || (p.P.kg & 3) || (p.Q.kg & 3))
+    return fail(ctx, STRP_EINVAL, "gemm: operand planes shorter than K or a group count that is not a multiple of four");
   if ((long long)p.P.npan * 128 < p.M || (long long)p.Q.npan * 128 < p.N) return fail(ctx, STRP_EINVAL, "gemm: operand planes narrower than the output");
   if (p.epi != EPI_PARTIAL && p.splits != 1) return fail(ctx, STRP_EINVAL, "gemm: fused epilogues do not split K");
   const int npp = p.P.lo ? 2 : 1, npq = p.Q.lo ? 2 : 1;
@@ -299,9 +302,10 @@ strp_status launch_gemm(strp_ctx* ctx, GemmP& p) {
   const double ibytes = p.triangle ? 2.0 * npp * (double)p.M * (double)p.K
                                    : 2.0 * npp * (double)p.M * (double)p.K + 2.0 * npq * (double)p.N * (double)p.K;
   ProfScope ps(ctx, name, 2.0 * mn * (double)p.K, ibytes + obytes);
-  if (p.k8_hi && ((p.M + 7) / 8) % 2) {
+  if (p.k8_hi && (p.M + 7) / 8 < p.k8_kg) {
     const int npan = (p.N + 127) / 128;
-    hipLaunchKernelGGL(zero_pad_group_kernel, dim3((npan * 128 + 255) / 256), dim3(256), 0, ctx->stream, p.k8_hi, p.k8_lo, p.k8_kg, npan);
+    hipLaunchKernelGGL(zero_pad_group_kernel, dim3((npan * 128 + 255) / 256), dim3(256), 0, ctx->stream, p.k8_hi, p.k8_lo, p.k8_kg,
+                       (p.M + 7) / 8, npan);
   }
   switch (npp * 10 + npq) {
     case 11: launch_one<1, 1>(ctx, p); break;

@@ -216,7 +216,7 @@ __device__ __forceinline__ double small_src(const unsigned short* s, long long i
 template <typename TS>
 __global__ __launch_bounds__(256) void split_small_kernel(const TS* src, long long lds, int rows, int cols, int transpose,
                                                           const float* scale_dev, unsigned short* hi, unsigned short* lo) {
-  const int KG = (int)((((cols + 7) >> 3) + 1) & ~1);
+  const int KG = (int)((((cols + 7) >> 3) + 3) & ~3);   // = plane_kg(cols)
   const long long total = (long long)((rows + 127) >> 7) * KG * 1024;
   const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;

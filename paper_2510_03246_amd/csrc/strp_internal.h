@@ -74,7 +74,7 @@ struct Arena {
 // An operand as the matrix cores see it: one (hi) or two (hi, lo) fp16 planes in the panel-major chunk layout
 //   offset(k, r) = (((r / 128) * kg + k / 8) * 128 + r % 128) * 8 + k % 8
 // k = contraction index, r = output row (P) or output column (Q); npan panels of 128 rows, kg k-groups of 8
-// (kg = plane_kg(K): even, padding zero).
+// (kg = plane_kg(K): a multiple of four, padding zero).
 // scale (device, optional): the planes hold x * scale; the GEMM epilogue divides it out.
 struct PlaneOp {
   const unsigned short* hi;
@@ -83,9 +83,9 @@ struct PlaneOp {
   int npan;
   const float* scale;
 };
-// k-groups allocated for a contraction of length K: an even number, the pad group zero-filled
-// (the pipelined kernel moves two k-groups per stage without tail logic)
-static inline long long plane_kg(long long K) { return (((K + 7) / 8) + 1) & ~1LL; }
+// k-groups allocated for a contraction of length K: a multiple of four, the pad groups zero-filled (the pipelined
+// kernel moves two k-groups per stage and multiplies four per matrix-core instruction, both without tail logic)
+static inline long long plane_kg(long long K) { return (((K + 7) / 8) + 3) & ~3LL; }
 static inline size_t plane_elems(long long rows, long long K) {
   return (size_t)((rows + 127) / 128) * (size_t)plane_kg(K) * 1024;
 }
