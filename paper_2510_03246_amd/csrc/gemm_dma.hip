@@ -202,7 +202,7 @@ __global__ __launch_bounds__(512, 1) void gemm_dma_kernel(const GemmP p) {
   if (p.P.scale) unscale /= *p.P.scale;
   if (p.Q.scale) unscale /= *p.Q.scale;
   double red0 = 0.0, red1 = 0.0;
-  const int mbase = m0 + wm * 128 + 4 * (lane >> 4), nbase = n0 + wn * 64 + (lane & 15);
+  const int mbase = m0 + wm * 128 + 8 * (lane >> 5), nbase = n0 + wn * 64 + (lane & 31);
   switch (p.epi) {
     case EPI_PARTIAL: epilogue16<EPI_PARTIAL>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;
     case EPI_STORE: epilogue16<EPI_STORE>(p, acc, unscale, mbase, nbase, split, srow, m0, red0, red1); break;

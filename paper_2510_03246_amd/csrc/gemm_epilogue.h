@@ -73,10 +73,12 @@ __device__ __forceinline__ bool decode_tile(const GemmP& p, int bid, int nblocks
   return true;
 }
 
-// Epilogue of one accumulator tile of 16 values per lane (passed by value so the accumulators never need an address).
-// Register e of lane l is output row m_tile + RS (e / 4) + (e % 4), column n  (m_tile, n include the lane's share):
-// RS = 8 for one 32x32 matrix-core tile (32 columns over the lanes of a half wavefront), RS = 16 for four stacked
-// 16x16 tiles (64 rows x 16 columns, 16 columns over the lanes of a quarter wavefront).
+// Epilogue of one 32 x 32 tile of outputs, 16 values per lane (passed by value so the accumulators never need an address).
+// Register e of lane l is output row m_tile + tile_rowoff<LAYOUT>(e / 4) + (e % 4), column n (m_tile and n include the
+// lane's share: lane % 32 selects the column, lane / 32 the row half).  LAYOUT 0 is the accumulator of one 32x32
+// matrix-core instruction (row offsets 0, 8, 16, 24; the upper half wavefront 4 rows further down); LAYOUT 1 is what
+// four 16x16 accumulators become after exchanging quarter wavefronts between horizontal neighbours (row offsets 0, 4,
+// 16, 20; the upper half wavefront 8 rows further down), see EpilogueWalk16.
 //
 // Loads are branch-free and come first: rows and the column are clamped into range so that every address is
 // valid, and the 16 loads of the tile are issued back to back.  (A predicated load costs a wait per element, and
@@ -87,7 +89,12 @@ __device__ __forceinline__ bool decode_tile(const GemmP& p, int bid, int nblocks
 // Row sums (AUPD / ZUPD with p.rs_out): rs0 / rs1 collect, per element position e of this lane, the scoring terms of the
 // values just produced (AUPD: a^2 and, with p.rs_z0, a relu(z0); ZUPD: z0 z); they run over the column tiles of the
 // wavefront and are reduced over the lanes by rowsum_flush.
-template <int EPI, bool ZWRITE, bool EDGE, int RS = 8>
+template <int LAYOUT>
+__device__ __forceinline__ constexpr int tile_rowoff(int q) {
+  return LAYOUT == 0 ? 8 * q : 16 * (q >> 1) + 4 * (q & 1);
+}
+
+template <int EPI, bool ZWRITE, bool EDGE, int LAYOUT = 0>
 __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16, float unscale, int m_tile, int n, int split,
                                               const int* rowmap, int m_blk, double& red0, double& red1, float (&rs0)[16],
                                               float (&rs1)[16]) {
@@ -99,11 +106,11 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
   int rowid[16];         // GATHER: state row of each element's output row (0 for rows past M)
   if (GATHER) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) rowid[e] = rowmap[m_tile + RS * (e >> 2) + (e & 3) - m_blk];   // slice of oidx staged in LDS
+    for (int e = 0; e < 16; ++e) rowid[e] = rowmap[m_tile + tile_rowoff<LAYOUT>(e >> 2) + (e & 3) - m_blk];   // slice of oidx staged in LDS
   }
   // 32 x 32 -> 64-bit products (one instruction each): rows, leading dimensions and columns all fit 32 bits
   auto offset = [&](int e) -> long long {
-    const int m = m_tile + RS * (e >> 2) + (e & 3);
+    const int m = m_tile + tile_rowoff<LAYOUT>(e >> 2) + (e & 3);
     const unsigned mc = (unsigned)((!EDGE || m < p.M) ? m : p.M - 1);
     unsigned long long o;
     if (EPI == EPI_PARTIAL) o = (unsigned long long)((unsigned)split * (unsigned)p.M + mc) * (unsigned)p.N + (unsigned)nc;
@@ -123,21 +130,16 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
       in0[e] = src[o];
       if (EPI == EPI_ZUPD && !ZWRITE) in1[e] = p.Zs[o];
     }
-    if (GATHER && ZWRITE) {
-      if (rs_z0) {   // uniform over the grid: a scalar branch around 16 more loads
+    if (GATHER && ZWRITE && rs_z0) {   // uniform over the grid: a scalar branch around 16 more loads
 #pragma unroll
-        for (int e = 0; e < 16; ++e) in1[e] = p.rs_z0[offset(e)];
-      } else {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) in1[e] = 0.0f;
-      }
+      for (int e = 0; e < 16; ++e) in1[e] = p.rs_z0[offset(e)];
     }
   }
   const float inv_ab = 1.0f / (p.alpha + p.beta);
   float s0 = 0.0f, s1 = 0.0f;   // this tile's share of the reduction sums (16 terms in fp32, then fp64)
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    const int mq = m_tile + RS * q;  // rows mq .. mq+3
+    const int mq = m_tile + tile_rowoff<LAYOUT>(q);  // rows mq .. mq+3
     float outv[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -168,10 +170,8 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
         const float a = __builtin_fmaxf(in0[e], 0.0f) + v;
         if (ok) p.As[offset(e)] = a;
         outv[r] = ok ? a : 0.0f;
-        if (rsum) {
-          rs0[e] += ok ? a * a : 0.0f;
-          rs1[e] += ok ? a * __builtin_fmaxf(in1[e], 0.0f) : 0.0f;
-        }
+        if (rsum) rs0[e] += ok ? a * a : 0.0f;
+        if (rs_z0) rs1[e] += ok ? a * __builtin_fmaxf(in1[e], 0.0f) : 0.0f;
       } else {  // EPI_ZUPD
         const float a = in0[e];
         const float z1 = v;
@@ -215,6 +215,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmP& p, const floatx16 a16
 // wavefront's strip of columns (64 in both kernels).  A halving butterfly: each exchange keeps half of the values a lane still holds, so
 // 8 + 4 + 2 + 1 + 1 shuffles do what 16 five-step reductions would; a lane ends with position e = (lane / 2) % 16.
 // A strip that lies wholly past column N (last block of a ragged N) has no slot and is dropped.
+template <int LAYOUT>
 __device__ __forceinline__ void rowsum_flush(const GemmP& p, const float (&rs)[16], int q, int m_tile, int slot) {
   const int l5 = threadIdx.x & 31;
   const bool b4 = l5 & 16, b3 = l5 & 8, b2 = l5 & 4, b1 = l5 & 2;
@@ -228,7 +229,7 @@ __device__ __forceinline__ void rowsum_flush(const GemmP& p, const float (&rs)[1
   float v1 = (b1 ? v2[1] : v2[0]) + __shfl_xor(b1 ? v2[0] : v2[1], 2, 64);
   v1 += __shfl_xor(v1, 1, 64);
   const int e = (l5 >> 1) & 15;
-  const int row = m_tile + 8 * (e >> 2) + (e & 3);
+  const int row = m_tile + tile_rowoff<LAYOUT>(e >> 2) + (e & 3);
   if (!(l5 & 1) && row < p.M && slot < p.rs_slots) p.rs_out[((long long)q * p.rs_slots + slot) * p.M + row] = v1;
 }
 
@@ -251,10 +252,10 @@ struct EpilogueWalk {
     else epilogue_tile<EPI, ZWRITE, false>(p, acc[IJ / WTN][IJ % WTN], unscale, mt, nt, split, rowmap, m_blk, red0, red1, rs0, rs1);
     if (ROWSUMS && IJ % WTN == WTN - 1 && p.rs_out) {
       if (EPI == EPI_AUPD) {
-        rowsum_flush(p, rs0, 0, mt, nbase / (32 * WTN));
-        if (p.rs_z0) rowsum_flush(p, rs1, 1, mt, nbase / (32 * WTN));
+        rowsum_flush<0>(p, rs0, 0, mt, nbase / (32 * WTN));
+        if (p.rs_z0) rowsum_flush<0>(p, rs1, 1, mt, nbase / (32 * WTN));
       } else if (p.rs_z0) {
-        rowsum_flush(p, rs0, 0, mt, nbase / (32 * WTN));
+        rowsum_flush<0>(p, rs0, 0, mt, nbase / (32 * WTN));
       }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -277,52 +278,51 @@ __device__ __forceinline__ void epilogue(const GemmP& p, floatx16 (&acc)[WTM][WT
 }
 
 // ---- the same for accumulators of 16x16 matrix-core tiles -------------------------------------------------------------
-// Lane l of a 16x16 tile holds rows 4 (l / 16) + r (r < 4) of column l % 16.  Four tiles stacked along the rows
-// (tile rows 4 I .. 4 I + 3 of the wavefront) give a lane the 16 values of epilogue_tile with RS = 16.
-__device__ __forceinline__ void rowsum_flush16(const GemmP& p, const float (&rs)[16], int q, int m_tile, int slot) {
-  const int l4 = threadIdx.x & 15;
-  const bool b3 = l4 & 8, b2 = l4 & 4, b1 = l4 & 2, b0 = l4 & 1;
-  float v8[8], v4[4], v2[2];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) v8[i] = (b3 ? rs[8 + i] : rs[i]) + __shfl_xor(b3 ? rs[i] : rs[8 + i], 8, 64);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) v4[i] = (b2 ? v8[4 + i] : v8[i]) + __shfl_xor(b2 ? v8[i] : v8[4 + i], 4, 64);
-#pragma unroll
-  for (int i = 0; i < 2; ++i) v2[i] = (b1 ? v4[2 + i] : v4[i]) + __shfl_xor(b1 ? v4[i] : v4[2 + i], 2, 64);
-  const float v1 = (b0 ? v2[1] : v2[0]) + __shfl_xor(b0 ? v2[0] : v2[1], 1, 64);
-  const int e = l4;                                  // = 8 b3 + 4 b2 + 2 b1 + b0
-  const int row = m_tile + 16 * (e >> 2) + (e & 3);
-  if (row < p.M && slot < p.rs_slots) p.rs_out[((long long)q * p.rs_slots + slot) * p.M + row] = v1;
+// Lane l of a 16x16 tile holds rows 4 (l / 16) + r (r < 4) of column l % 16, so a store instruction would write 64-byte
+// pieces of four rows.  v_permlane16_swap exchanges the odd quarter wavefronts of one register with the even ones of
+// another: applied to the same register of two horizontally adjacent tiles it yields two registers in which lanes
+// 0-31 hold 32 consecutive columns of one row and lanes 32-63 those of the row 8 further down -- 128-byte pieces, the
+// column-per-lane arrangement of epilogue_tile.  Two such tile pairs stacked vertically are one 32 x 32 tile in LAYOUT 1.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void quarter_swap(float a, float b, float& x, float& y) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned int, a), __builtin_bit_cast(unsigned int, b), false, false);
+  x = __builtin_bit_cast(float, (unsigned int)r[0]);
+  y = __builtin_bit_cast(float, (unsigned int)r[1]);
 }
 
-// acc[8][4]: the wavefront's 128 x 64 outputs as 8 x 4 tiles of 16 x 16.  IJ walks the 2 x 4 stacks of four tiles.
-typedef float floatx4 __attribute__((ext_vector_type(4)));
+// acc[8][4]: the wavefront's 128 x 64 outputs as 8 x 4 tiles of 16 x 16.  IJ walks its 4 x 2 tiles of 32 x 32.
 template <int EPI, bool ZWRITE, int IJ>
 struct EpilogueWalk16 {
   static __device__ __forceinline__ void run(const GemmP& p, floatx4 (&acc)[8][4], float unscale, int mbase, int nbase, int split,
                                              const int* rowmap, int m_blk, double& red0, double& red1, float (&rs0)[16],
                                              float (&rs1)[16]) {
     constexpr bool ROWSUMS = (EPI == EPI_AUPD || EPI == EPI_ZUPD) && ZWRITE;
-    constexpr int I = IJ / 4, J = IJ % 4;
+    constexpr int I = IJ / 2, J = IJ % 2;
     if (ROWSUMS && J == 0) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) rs0[e] = rs1[e] = 0.0f;
     }
     floatx16 a16;
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) a16[4 * q + r] = acc[4 * I + q][J][r];
-    const int mt = mbase + 64 * I, nt = nbase + 16 * J;
-    const bool edge = __builtin_amdgcn_readfirstlane(mt) + 64 > p.M || __builtin_amdgcn_readfirstlane(nt) + 16 > p.N;
-    if (edge) epilogue_tile<EPI, ZWRITE, true, 16>(p, a16, unscale, mt, nt, split, rowmap, m_blk, red0, red1, rs0, rs1);
-    else epilogue_tile<EPI, ZWRITE, false, 16>(p, a16, unscale, mt, nt, split, rowmap, m_blk, red0, red1, rs0, rs1);
-    if (ROWSUMS && J == 3 && p.rs_out) {
+    for (int r = 0; r < 4; ++r) {
+      float x, y;
+      quarter_swap(acc[2 * I][2 * J][r], acc[2 * I][2 * J + 1][r], x, y);
+      a16[r] = x;
+      a16[4 + r] = y;
+      quarter_swap(acc[2 * I + 1][2 * J][r], acc[2 * I + 1][2 * J + 1][r], x, y);
+      a16[8 + r] = x;
+      a16[12 + r] = y;
+    }
+    const int mt = mbase + 32 * I, nt = nbase + 32 * J;
+    const bool edge = __builtin_amdgcn_readfirstlane(mt) + 32 > p.M || __builtin_amdgcn_readfirstlane(nt) + 32 > p.N;
+    if (edge) epilogue_tile<EPI, ZWRITE, true, 1>(p, a16, unscale, mt, nt, split, rowmap, m_blk, red0, red1, rs0, rs1);
+    else epilogue_tile<EPI, ZWRITE, false, 1>(p, a16, unscale, mt, nt, split, rowmap, m_blk, red0, red1, rs0, rs1);
+    if (ROWSUMS && J == 1 && p.rs_out) {
       if (EPI == EPI_AUPD) {
-        rowsum_flush16(p, rs0, 0, mt, nbase >> 6);
-        if (p.rs_z0) rowsum_flush16(p, rs1, 1, mt, nbase >> 6);
+        rowsum_flush<1>(p, rs0, 0, mt, nbase >> 6);
+        if (p.rs_z0) rowsum_flush<1>(p, rs1, 1, mt, nbase >> 6);
       } else if (p.rs_z0) {
-        rowsum_flush16(p, rs0, 0, mt, nbase >> 6);
+        rowsum_flush<1>(p, rs0, 0, mt, nbase >> 6);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -334,7 +334,7 @@ struct EpilogueWalk16<EPI, ZWRITE, 8> {
   static __device__ __forceinline__ void run(const GemmP&, floatx4 (&)[8][4], float, int, int, int, const int*, int, double&, double&,
                                              float (&)[16], float (&)[16]) {}
 };
-// mbase = first row of the wavefront's tile + 4 (lane / 16), nbase = first column + lane % 16
+// mbase = first row of the wavefront's tile + 8 (lane / 32), nbase = first column + lane % 32
 template <int EPI>
 __device__ __forceinline__ void epilogue16(const GemmP& p, floatx4 (&acc)[8][4], float unscale, int mbase, int nbase, int split,
                                            const int* rowmap, int m_blk, double& red0, double& red1) {
