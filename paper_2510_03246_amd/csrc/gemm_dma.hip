@@ -139,17 +139,26 @@ __global__ __launch_bounds__(512, 1) void gemm_dma_kernel(const GemmP p) {
   auto mma = [&](uint4 a, uint4 b, floatx4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
   };
-  auto run_row = [&](floatx4 (&c)[4], const PF& a, const QF& b) {
+  auto pass_hl = [&](floatx4 (&c)[4], const PF& a, const QF& b) {
     if (NPQ == 2) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) c[j] = mma(a.h, b.l[j], c[j]);
     }
+  };
+  auto pass_lh = [&](floatx4 (&c)[4], const PF& a, const QF& b) {
     if (NPP == 2) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) c[j] = mma(a.l, b.h[j], c[j]);
     }
+  };
+  auto pass_hh = [&](floatx4 (&c)[4], const PF& a, const QF& b) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) c[j] = mma(a.h, b.h[j], c[j]);
+  };
+  auto run_row = [&](floatx4 (&c)[4], const PF& a, const QF& b) {
+    pass_hl(c, a, b);
+    pass_lh(c, a, b);
+    pass_hh(c, a, b);
   };
   // One pair: bc holds the pair's Q fragments, pa its first P fragment; on return bn / pa hold those of the next pair.
   PF pa, pb;
@@ -171,12 +180,19 @@ __global__ __launch_bounds__(512, 1) void gemm_dma_kernel(const GemmP p) {
 #undef STRP_ROW
     wait_vmcnt_lgkm0<(NP - 2) * 2 * LPW>();   // the next pair has landed; this wavefront's fragment reads of this pair are complete
     __syncthreads();               // ... and so for every wavefront: the pair's slots may be overwritten
+    // the last row needs nothing from LDS: its matrix-core instructions go out first and run while the refill is
+    // requested and the next pair's first fragments are read
+    pass_hh(acc[7], pb, bc);
+    __builtin_amdgcn_sched_barrier(0);
     issue_stage(2 * (pr + NP));
     issue_stage(2 * (pr + NP) + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    pass_hl(acc[7], pb, bc);
+    __builtin_amdgcn_sched_barrier(0);
     read_q(bn, pr + 1);            // past the last pair this reads slots that are never multiplied
     read_p(pa, pr + 1, 0);
     __builtin_amdgcn_sched_barrier(0);
-    run_row(acc[7], pb, bc);
+    pass_lh(acc[7], pb, bc);
     __builtin_amdgcn_sched_barrier(0);
   };
 
