@@ -197,7 +197,7 @@ def main():
                          "largest configuration (one global threshold); reported under \"select_stress\" in the same line")
     ap.add_argument("--no-mfma-ceiling", action="store_true",
                     help="skip the sustained-rate measurement of the fp16 matrix-core instruction (register-only, and fed from "
-                         "LDS with random data in the GEMM's wavefront shape; about one second, outside the timed region) "
+                         "LDS with random data in the GEMM's wavefront shape; under two seconds, outside the timed region) "
                          "that is reported under \"mfma_ceiling\"")
     ap.add_argument("--dump-launches", default="",
                     help="write the library's per-launch records of the timed region (kernel class names in enqueue order) "
@@ -312,7 +312,10 @@ def main():
         from paper_2510_03246_amd import bench_probe
         out["mfma_ceiling"] = {"unit": "TFLOP/s", "register_operands": bench_probe.mfma_rate(0),
                                "register_operands_random_data": bench_probe.mfma_rate(2),
-                               "lds_fed_random_data": bench_probe.mfma_rate(1)}
+                               "lds_fed_random_data": bench_probe.mfma_rate(1),
+                               "lds_fed_random_data_32x32x16": bench_probe.mfma_rate(3),
+                               "instruction": "v_mfma_f32_16x16x32_f16 (the pipelined GEMM's); the last entry is the same "
+                                              "loop on v_mfma_f32_32x32x16_f16"}
         if roof.get("executed"):
             roof["executed_frac_of_lds_fed_ceiling"] = roof["executed"] / out["mfma_ceiling"]["lds_fed_random_data"]
     if not args.no_cpu_baseline:

@@ -14,8 +14,9 @@ _lib = None
 
 
 def mfma_rate(kind: int, milliseconds: float = 200.0) -> float:
-    """TFLOP/s of v_mfma_f32_32x32x16_f16 on the current stream.  kind 0: constant register operands; 2: random
-    fp16 values in the registers; 1: the GEMM's inner loop without its memory side (fragments re-read from LDS)."""
+    """TFLOP/s of the fp16 matrix-core instruction on the current stream.  kind 0: v_mfma_f32_16x16x32_f16 on constant
+    register operands; 2: random fp16 values in the registers; 1: the pipelined GEMM's inner loop without its memory
+    side (fragments re-read from LDS); 3: kind 1 on v_mfma_f32_32x32x16_f16 (same flops, same LDS traffic)."""
     global _lib
     if _lib is None:
         if not os.path.exists(LIB_PATH):
