@@ -2,6 +2,7 @@
 // recursive doubling, right-side solves as two triangular-aware GEMMs, and small cast / scatter helpers.
 // The Gram systems reach condition numbers ~1e4, so factor and solve stay in fp64.  The GEMM runs on the
 // fp64 matrix cores (v_mfma_f64_16x16x4_f64): same peak as the vector unit, far less LDS traffic per flop.
+#include "cojob.h"
 #include "strp_internal.h"
 
 namespace strp {
@@ -30,16 +31,21 @@ struct DgemmP {
   long long sa, sb, sc;
   int lim_base, lim_step;   // lim_step == 0: no clamping
   int clamp_k;              // clamp K like M (square ragged block)
+  int own_x;                // blocks with blockIdx.x >= own_x are spare workgroups for the ride-along job (0: there are none)
 };
 
 template <int WT>
-__global__ __launch_bounds__(256) void dgemm_kernel(const DgemmP p) {
+__global__ __launch_bounds__(256) void dgemm_kernel(const DgemmP p, const CoJob job) {
   constexpr int TS = 32 * WT;      // block tile (rows and columns)
   constexpr int DK = 16;
   constexpr int LD = TS + 4;
   // double-buffered operand tiles: one barrier per K tile
   __shared__ double As[2][DK][LD];
   __shared__ double Bs[2][DK][LD];
+  if (p.own_x && (int)blockIdx.x >= p.own_x) {
+    cojob_help(job);
+    return;
+  }
   const int z = blockIdx.z;
   int M = p.M, K = p.K;
   if (p.lim_step) {
@@ -139,14 +145,35 @@ __global__ __launch_bounds__(256) void dgemm_kernel(const DgemmP p) {
     }
 }
 
-static strp_status dgemm_launch(strp_ctx* ctx, const DgemmP& p, int batch) {
+// spare workgroups a short launch of the factorisation chain carries for the ride-along job: about as many units as
+// HBM moves in the ~30 us such a launch takes (1024, 1536 and 2048 units per launch with 2, 3 and 4 per workgroup were
+// timed on the benchmark's module: 1536 at 3 is the best by a little; the launches grow by about half of what they hide)
+static int cojob_spare_blocks(const CoJob* cj, int own, int cap) {
+  if (!cj || !cj->ticket || cj->take <= 0) return 0;
+  int h = 1536 / cj->take;
+  if (h > cap - own) h = cap - own;
+  return h > 0 ? h : 0;
+}
+
+static strp_status dgemm_launch(strp_ctx* ctx, const DgemmP& pin, int batch, const CoJob* cj = nullptr) {
+  DgemmP p = pin;
   if (p.M <= 0 || p.N <= 0 || batch <= 0) return STRP_OK;
   // 64 x 64 tiles throughout: a block is a serial chain of fp64 matrix-core instructions, the grids here are a few
   // thousand tiles at most, and with triangular K ranges small tiles balance far better (measured 20 % faster than
   // 128 x 128 tiles on the 4096 x 4915 solves)
   constexpr int ts = 64;
   dim3 grid((p.M + ts - 1) / ts, (p.N + ts - 1) / ts, batch);
-  hipLaunchKernelGGL((dgemm_kernel<2>), grid, dim3(256), 0, ctx->stream, p);
+  p.own_x = 0;
+  CoJob job;
+  memset(&job, 0, sizeof(job));
+  const int own = (int)(grid.x * grid.y * grid.z);
+  const int spare = cojob_spare_blocks(cj, own, 1024);   // four workgroups of this kernel fit a CU
+  if (spare > 0) {
+    job = *cj;
+    p.own_x = (int)grid.x;
+    grid.x += (unsigned)((spare + grid.y * grid.z - 1) / (grid.y * grid.z));
+  }
+  hipLaunchKernelGGL((dgemm_kernel<2>), grid, dim3(256), 0, ctx->stream, p, job);
   STRP_HIP(ctx, hipGetLastError());
   return STRP_OK;
 }
@@ -308,10 +335,16 @@ __device__ __forceinline__ void potrf_block(const double* A, long long ld, int j
 // the critical path.  Block 0 stores the inverse of the block's factor; block b >= 1 multiplies rows [64 (b-1), +64)
 // of the panel below the diagonal block by L^-T in place.  The diagonal block itself is only read (all blocks load
 // it; nobody writes it), so blocks that start at different times cannot see each other's output.
-__global__ __launch_bounds__(256) void potrf_panel_kernel(double* Ajj, long long ld, int jb, int rest, double* invd, int32_t* status) {
+// Blocks past `own` are spare workgroups for the ride-along job (cojob.h).
+__global__ __launch_bounds__(256) void potrf_panel_kernel(double* Ajj, long long ld, int jb, int rest, double* invd, int32_t* status, int own,
+                                                          const CoJob job) {
   __shared__ PotrfShared sh;
   __shared__ double Ms[NB][NB + 1];   // Ms[k][c] = Linv[c][k]
   __shared__ double Xs[NB][NB + 1];
+  if ((int)blockIdx.x >= own) {
+    cojob_help(job);
+    return;
+  }
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   const int b = blockIdx.x;
   double* X = Ajj + (long long)jb * ld;          // panel below the diagonal block
@@ -385,6 +418,9 @@ __global__ __launch_bounds__(256) void potrf_panel_kernel(double* Ajj, long long
 strp_status chol_factor(strp_ctx* ctx, double* A, int n, long long ld, double* invd, int32_t* status) {
   ProfScope ps(ctx, "chol_factor_f64", (double)n * n * n / 3.0, 8.0 * (double)n * n);
   constexpr int NB2 = 4 * NB;
+  const CoJob* cj = ctx->cojob;
+  CoJob nojob;
+  memset(&nojob, 0, sizeof(nojob));
   for (int J0 = 0; J0 < n; J0 += NB2) {
     const int Jend = (n - J0 < NB2) ? n : J0 + NB2;
     for (int j0 = J0; j0 < Jend; j0 += NB) {
@@ -392,14 +428,20 @@ strp_status chol_factor(strp_ctx* ctx, double* A, int n, long long ld, double* i
       double* Ajj = A + (long long)j0 * ld + j0;
       double* inv = invd + (long long)(j0 / NB) * NB * NB;
       const int rest = n - j0 - jb;
-      hipLaunchKernelGGL(potrf_panel_kernel, dim3(1 + (rest + NB - 1) / NB), dim3(256), 0, ctx->stream, Ajj, ld, jb, rest, inv, status);
+      const int own = 1 + (rest + NB - 1) / NB;
+      const int spare = cojob_spare_blocks(cj, own, 512);   // two workgroups of this kernel fit a CU
+      hipLaunchKernelGGL(potrf_panel_kernel, dim3(own + spare), dim3(256), 0, ctx->stream, Ajj, ld, jb, rest, inv, status, own, spare ? *cj : nojob);
       STRP_HIP(ctx, hipGetLastError());
       if (rest <= 0) continue;
       double* A21 = A + (long long)(j0 + jb) * ld + j0;
       const int pc = Jend - (j0 + jb);   // columns of the outer panel still to be factored
       if (pc > 0) {
         double* A22 = A + (long long)(j0 + jb) * ld + (j0 + jb);
-        STRP_TRY(dgemm(ctx, rest, pc, jb, -1.0, A21, ld, 1, A21, 1, ld, 1.0, A22, ld, 1));
+        DgemmP u;
+        memset(&u, 0, sizeof(u));
+        u.M = rest; u.N = pc; u.K = jb; u.alpha = -1.0; u.beta = 1.0;
+        u.A = A21; u.rsa = ld; u.csa = 1; u.B = A21; u.rsb = 1; u.csb = ld; u.C = A22; u.ldc = ld; u.lower = 1;
+        STRP_TRY(dgemm_launch(ctx, u, 1, cj));
       }
     }
     const int rest2 = n - Jend;

@@ -6,6 +6,7 @@
 #include <string>
 #include <vector>
 
+#include "cojob.h"
 #include "strp_internal.h"
 
 struct Profiler {
@@ -114,26 +115,7 @@ __global__ __launch_bounds__(256) void transpose_f32_f64_kernel(const float* src
   dst[(long long)c * ldd + r] = (double)src[(long long)r * lds + c];
 }
 
-// Rows of pruned units (mask == 0): W2[:, j] = 0 and W1[j, :] = 0 decouple them.
-//   phase 0 (a-update): A_j = relu(Z_j)
-//   phase 1 (z-update): exact z rule with z1 = 0; accumulates (A - relu Z)^2 and (Z - 0)^2
-//   phase 2: both in one pass over the row (A_j = relu(Z_j), then the z rule on the new A_j)
-__device__ __forceinline__ void pruned_elem(float& zv, float& av, int phase, float alpha, float beta, int write, double& r0, double& r1) {
-  if (phase != 1) av = __builtin_fmaxf(zv, 0.0f);
-  if (phase != 0) {
-    if (write) {
-      const float z2 = beta * av / (alpha + beta);
-      const float costm = beta * av * av;
-      const float cp = __builtin_fmaxf(z2, 0.0f);
-      const float costp = beta * (av - cp) * (av - cp) + alpha * cp * cp;
-      zv = costm < costp ? 0.0f : cp;
-    }
-    const float ra = av - __builtin_fmaxf(zv, 0.0f);
-    r0 += (double)ra * (double)ra;
-    r1 += (double)zv * (double)zv;
-  }
-}
-
+// The per-element rules of the pruned rows (pruned_elem) are in cojob.h.
 // rowsums (phase 2 only, may be null): the scoring sums of the row's NEW state, [0][j] = sum A^2 and, when Z0 is
 // given, [1][j] = sum A relu(Z0), [2][j] = sum Z0 Z, [3][j] = sum Z0^2, so that the next selection does not have
 // to stream the pruned rows again.
@@ -224,6 +206,69 @@ __global__ __launch_bounds__(256) void pruned_rows_kernel(const uint8_t* mask, f
       } else if (rowsums && pruned && (q == 2 || Z0)) {
         rowsums[(long long)(q - 2) * rows + j] = t;
       }
+    }
+  }
+}
+
+// ---- the fused a/z pass of the pruned rows as a ride-along job (cojob.h) ---------------------------------------------
+// rows[0 .. f - s) = the rows with mask == 0, ascending (one block; f is a few ten thousand at most)
+__global__ __launch_bounds__(1024) void pruned_list_kernel(const uint8_t* mask, int f, int32_t* rows) {
+  __shared__ int scan[1024];
+  const int tid = threadIdx.x;
+  const int per = (f + 1023) / 1024;
+  const int j0 = tid * per, j1 = (j0 + per < f) ? j0 + per : f;
+  int cnt = 0;
+  for (int j = j0; j < j1; ++j) cnt += mask[j] ? 0 : 1;
+  scan[tid] = cnt;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    const int v = tid >= o ? scan[tid - o] : 0;
+    __syncthreads();
+    scan[tid] += v;
+    __syncthreads();
+  }
+  int pos = scan[tid] - cnt;
+  for (int j = j0; j < j1; ++j)
+    if (!mask[j]) rows[pos++] = j;
+  // entries past the last pruned row name no row (a unit of such an entry does nothing): the job's row count comes
+  // from the host's record of the kept count, which a caller-supplied mask need not match
+  const int total = scan[1023];
+  for (int j = total + tid; j < f; j += 1024) rows[j] = -1;
+}
+
+// takes units until none are left
+__global__ __launch_bounds__(256) void cojob_drain_kernel(const CoJob job) {
+  __shared__ unsigned int u0s;
+  for (;;) {
+    if (threadIdx.x == 0) u0s = atomicAdd(job.ticket, (unsigned int)job.take);
+    __syncthreads();
+    const unsigned int u0 = u0s;
+    if (u0 >= job.units) return;
+    for (int i = 0; i < job.take; ++i) {
+      if (u0 + i >= job.units) break;
+      cojob_unit(job, u0 + i);   // ends with a barrier: u0s may be rewritten afterwards
+    }
+  }
+}
+
+// per pruned row: the units' sums added in segment order -> red[2 j], red[2 j + 1] and the row's scoring sums
+__global__ __launch_bounds__(256) void cojob_finish_kernel(const CoJob job, double* red, double* rowsums, int f) {
+  const int p = blockIdx.x * 256 + threadIdx.x;
+  if (p >= job.nrows) return;
+  const int j = job.rows[p];
+  double t[6] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+  const double* src = job.partial + (unsigned long long)p * job.segs * 6;
+  for (int g = 0; g < job.segs; ++g)
+#pragma unroll
+    for (int q = 0; q < 6; ++q) t[q] += src[g * 6 + q];
+  red[2 * (long long)j] = t[0];
+  red[2 * (long long)j + 1] = t[1];
+  if (rowsums) {
+    rowsums[j] = t[2];
+    if (job.Z0) {
+      rowsums[(long long)f + j] = t[3];
+      rowsums[2 * (long long)f + j] = t[4];
+      rowsums[3 * (long long)f + j] = t[5];
     }
   }
 }
@@ -712,7 +757,10 @@ size_t strp_workspace_bytes(const strp_module_desc* desc) {
   upd(nt_partial_elems((int)km, (int)d, T, 0));
   upd(nt_partial_elems((int)d, (int)d, (long long)kp, 1));
   upd(nt_partial_elems((int)d, (int)d, T, 1));   // E E^T of the objective
+  const size_t segs = (size_t)((T + 8191) / 8192);
   size_t step = 256 + al(4 * f * 8) + al(d * kp * 4) + al(km * d * 4) +
+                /* the pruned rows' pass: its sums, the row list, the unit counter, the units' partial sums */
+                al(2 * f * 8) + al(f * 4) + 256 + al(f * segs * 6 * 8) +
                 (al(256) + 2 * al(plane_elems(d, km) * 2)) + 2 * (al(256) + 2 * al(plane_elems(km, d) * 2)) +
                 al(part * 4) + 3 * al(nmax * nmax * 8) + 2 * al(invd_max) + al(d * km * 8) * 4 + 2 * al(d * d * 8) +
                 2 * al(plane_elems(km, T) * 2) /* kept rows, token contraction */ +
@@ -926,6 +974,39 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
   const int s = st->s;
   const long long sp = round_up(s, 8);
 
+  // ---- the pruned rows' fused a/z pass as a ride-along job ------------------------------------------------------
+  // It touches only rows outside S, which nothing else in the step reads or writes, so it may run any time from
+  // here to the end of the step: the factorisation chains of the fc2 refit and of the a-update carry spare
+  // workgroups for it (chol_factor reads ctx->cojob), and what they leave is drained where the pass used to run.
+  const bool fuse_pruned = (stages & STRP_STAGE_AUPD) && (stages & STRP_STAGE_ZUPD);
+  struct CoJobGuard {
+    strp_ctx* c;
+    ~CoJobGuard() { c->cojob = nullptr; }
+  } cojob_guard{ctx};
+  CoJob pjob;
+  memset(&pjob, 0, sizeof(pjob));
+  double* red_pruned = nullptr;
+  if (fuse_pruned) {
+    STRP_TAKE(ctx, arena, rp, double, 2 * (size_t)f);
+    red_pruned = rp;
+    STRP_TRY(fill_zero(ctx, red_pruned, 2 * (size_t)f * sizeof(double)));
+    if (s < f) {
+      constexpr long long SEG = 8192;
+      const int segs = (int)((T + SEG - 1) / SEG);
+      STRP_TAKE(ctx, arena, prow, int32_t, (size_t)f);
+      STRP_TAKE(ctx, arena, ticket, unsigned int, 64);
+      STRP_TAKE(ctx, arena, partial, double, (size_t)(f - s) * segs * 6);
+      STRP_TRY(fill_zero(ctx, ticket, 256));
+      hipLaunchKernelGGL(pruned_list_kernel, dim3(1), dim3(1024), 0, ctx->stream, st->mask, f, prow);
+      pjob.ticket = ticket;
+      pjob.units = (unsigned int)(f - s) * (unsigned int)segs;
+      pjob.take = 3;
+      pjob.rows = prow; pjob.nrows = f - s; pjob.segs = segs; pjob.seg_tokens = SEG;
+      pjob.Z = st->Z; pjob.A = st->A; pjob.Z0 = wanda ? nullptr : st->Z0;
+      pjob.lda = lda; pjob.T = T; pjob.alpha = alpha; pjob.beta = beta; pjob.partial = partial;
+      ctx->cojob = &pjob;
+    }
+  }
   // ---- S1/S5: Gram of the kept A rows, fc2 refit -------------------------------------------
   if (stages & STRP_STAGE_REFIT2) {
     Arena a2 = arena;
@@ -1060,7 +1141,6 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     STRP_TRY(make_weight_planes(ctx, arena, W1S, SRC_F32, d, s, d, 0, npa, &W1Sp));
   }
 
-  const bool fuse_pruned = (stages & STRP_STAGE_AUPD) && (stages & STRP_STAGE_ZUPD);
   // scoring sums of the kept rows, collected by the two epilogues that write those rows (64-column strips, fp32)
   const int rs_slots = (int)((T + 63) / 64);
   float* rsA = nullptr;
@@ -1150,17 +1230,27 @@ strp_status strp_admm_step(strp_ctx* ctx, const strp_module_desc* desc, strp_mod
     STRP_TRY(launch_gemm(ctx, p));
     STRP_TRY(launch_block_sum(ctx, red, nb, sc + SC_TMP0, sc + SC_TMP1, 1.0, 1.0));
     if (p.rs_out) STRP_TRY(launch_rowsum_reduce(ctx, rsZ, 1, rs_slots, s, st->idx, cv.rowsums, f, 2, 2, rs_chunks));
-    {
-      ProfScope ps(ctx, fuse_pruned ? "pruned_rows_az" : "pruned_rows_z", 0.0, (fuse_pruned ? 12.0 : 8.0) * (double)(f - s) * (double)T);
-      const bool keep_sums = fuse_pruned && zupd;   // the rows are in registers in their final state: sum them for the next selection
-      const float* z0_for_sums = wanda ? nullptr : st->Z0;
-      hipLaunchKernelGGL(pruned_rows_kernel, dim3(f), dim3(256), 0, ctx->stream, st->mask, st->Z, st->A, lda, T, fuse_pruned ? 2 : 1, alpha, beta,
-                         zupd ? 1 : 0, red, keep_sums ? z0_for_sums : nullptr, keep_sums ? cv.rowsums : nullptr, f);
+    if (fuse_pruned) {
+      // what the factorisation chains' spare workgroups left of the pruned rows' pass, then the rows' sums
+      ctx->cojob = nullptr;
+      if (pjob.ticket) {
+        {
+          ProfScope ps(ctx, "pruned_rows_drain", 0.0, 0.0);
+          CoJob dj = pjob;
+          dj.take = 4;
+          hipLaunchKernelGGL(cojob_drain_kernel, dim3(2048), dim3(256), 0, ctx->stream, dj);
+        }
+        hipLaunchKernelGGL(cojob_finish_kernel, dim3((pjob.nrows + 255) / 256), dim3(256), 0, ctx->stream, pjob, red_pruned, cv.rowsums, f);
+      }
       // every row's sums are now in place: the kept rows' from the two epilogues, the pruned rows' from this pass
       // (which also rewrites their sum Z0^2; the kept rows' is only there if it was streamed before)
-      if (keep_sums) st->sums_cached = (st->sums_cached & SUMS_V) | SUMS_G | (z0_for_sums ? SUMS_EU : 0);
+      st->sums_cached = (st->sums_cached & SUMS_V) | SUMS_G | (wanda ? 0 : SUMS_EU);
+    } else {
+      ProfScope ps(ctx, "pruned_rows_z", 0.0, 8.0 * (double)(f - s) * (double)T);
+      hipLaunchKernelGGL(pruned_rows_kernel, dim3(f), dim3(256), 0, ctx->stream, st->mask, st->Z, st->A, lda, T, 1, alpha, beta,
+                         zupd ? 1 : 0, red, (const float*)nullptr, (double*)nullptr, f);
     }
-    STRP_TRY(launch_block_sum(ctx, red, f, sc + SC_TMP2, sc + SC_TMP3, 1.0, 1.0));
+    STRP_TRY(launch_block_sum(ctx, fuse_pruned ? red_pruned : red, f, sc + SC_TMP2, sc + SC_TMP3, 1.0, 1.0));
     hipLaunchKernelGGL(axpby_scalar_kernel, dim3(1), dim3(1), 0, ctx->stream, sc, (int)SC_T2, params->beta / (double)T, (int)SC_TMP0, params->beta / (double)T, (int)SC_TMP2);
     hipLaunchKernelGGL(axpby_scalar_kernel, dim3(1), dim3(1), 0, ctx->stream, sc, (int)SC_T3, params->alpha / (double)T, (int)SC_TMP1, params->alpha / (double)T, (int)SC_TMP3);
   }

@@ -8,6 +8,10 @@
 
 #include "strp.h"
 
+namespace strp {
+struct CoJob;
+}
+
 struct strp_ctx {
   int device;
   hipStream_t stream;
@@ -19,6 +23,9 @@ struct strp_ctx {
   char err[512];
   struct Profiler* prof;  // optional per-kernel event timing (host object)
   unsigned char prod_planes[8][2];  // fp16 planes (1 or 2) of the P and Q operand per strp_product of strp_admm_step
+  // Set by strp_admm_step while a streaming job may ride along with the factorisation chains (see cojob.h); null
+  // everywhere else.  chol_factor gives its short launches spare workgroups for it.
+  const strp::CoJob* cojob;
 };
 
 struct Profiler;

@@ -568,10 +568,12 @@ def test_cached_sums_match_streamed_sums(ctx, mode, flags):
 
 @pytest.mark.parametrize("name,d,f,T,k,dt", [("all kept", 72, 264, 520, 264, "bf16"), ("k=8", 136, 520, 1003, 8, "bf16"),
                                               ("tiny T", 64, 256, 96, 100, "f32"), ("f32 X", 264, 1048, 3000, 400, "f32"),
-                                              ("k=f-1", 72, 264, 777, 263, "bf16"), ("wide d", 776, 1032, 2600, 300, "bf16")])
+                                              ("k=f-1", 72, 264, 777, 263, "bf16"), ("wide d", 776, 1032, 2600, 300, "bf16"),
+                                              ("three token segments", 72, 264, 2 * 8192 + 1003, 100, "bf16")])
 def test_free_running_edge_shapes(ctx, name, d, f, T, k, dt):
     """Two free-running iterations (GAIN score, re-select) at the corners: nothing pruned, almost everything pruned,
-    fewer tokens than one tile, fp32 inputs, d larger than a tile and not a multiple of it."""
+    fewer tokens than one tile, fp32 inputs, d larger than a tile and not a multiple of it, and a token count that
+    cuts the pruned rows' pass into two full segments and a ragged third with a scalar tail."""
     base = inputs.CONFIGS["opt125m"]
     cfg = type(base)(**{**base.__dict__, "d": d, "f": f, "T": T, "n_outlier": 2, "dtype": dt})
     m = inputs.make_ffn_module(cfg, 0, 5, "cuda", ld=(T + 7) // 8 * 8)
