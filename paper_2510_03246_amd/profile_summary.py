@@ -33,7 +33,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 
 # kernels whose every launch belongs to one class of the library's records
-KERNEL_CLASS = {"pruned_rows_kernel": "pruned_rows", "split_t_kernel": "split_act", "split_c_kernel": "split_act",
+KERNEL_CLASS = {"pruned_rows_kernel": "pruned_rows", "cojob_drain_kernel": "pruned_rows_drain", "split_t_kernel": "split_act", "split_c_kernel": "split_act",
                 "row_sums_kernel": "row_sums", "plane_c_to_t_kernel": "plane_c_to_t", "splitk_reduce_kernel": "splitk_reduce"}
 
 
@@ -116,6 +116,7 @@ def traffic_tables(fetch_dir, write_dir, launches):
     start = classify(F, launches)
     rows = []
     per_class = collections.defaultdict(lambda: dict(launches=0, fetch_gb=0.0, write_gb=0.0, ms=0.0))
+    short = collections.defaultdict(lambda: dict(launches=0, fetch_gb=0.0, write_gb=0.0, ms=0.0))
     for i in range(len(F)):
         d = F[i]
         if "strp::" not in d["name"]:
@@ -124,6 +125,12 @@ def traffic_tables(fetch_dir, write_dir, launches):
         wg = W[i]["counters"]["WRITE_SIZE"] * ws * 1024 / 1e9
         if d["ms"] >= 0.3:
             rows.append((d["name"], d.get("cls", "" if i >= start else "(before the timed region)"), d["wg"], d["ms"], fg, wg))
+        elif i >= start:
+            sh = short[d["name"]]
+            sh["launches"] += 1
+            sh["fetch_gb"] += fg
+            sh["write_gb"] += wg
+            sh["ms"] += d["ms"]
         if i >= start and "cls" in d:
             pc = per_class[d["cls"]]
             pc["launches"] += 1
@@ -133,7 +140,7 @@ def traffic_tables(fetch_dir, write_dir, launches):
     cal_note = (f"Calibration: the elementwise copy kernel of `--copy-calibration` (2^30 bytes in, 2^30 bytes out) reads "
                 f"FETCH_SIZE = {fcal:.0f} KiB and WRITE_SIZE = {wcal:.0f} KiB, so FETCH_SIZE is scaled by {fs:.2f} and "
                 f"WRITE_SIZE by {ws:.2f}.")
-    return rows, per_class, cal_note, dict(fetch_scale=fs, write_scale=ws)
+    return rows, per_class, cal_note, dict(fetch_scale=fs, write_scale=ws), short
 
 
 def mfma_table(mfma_dir, clock_dir, launches):
@@ -196,7 +203,7 @@ def main():
                           f"{float(r['Percentage']):.2f} |")
         md.append("")
     if args.fetch and args.write:
-        rows, per_class, cal_note, scales = traffic_tables(args.fetch, args.write, launches)
+        rows, per_class, cal_note, scales, short = traffic_tables(args.fetch, args.write, launches)
         md += ["## HBM-side traffic per launch", "",
                "    rocprofv3 --pmc FETCH_SIZE --kernel-trace -d R/gpurun_out/pmc_fetch -o pmc --output-format csv -- python3 R/bench.py ARGS --copy-calibration",
                "    rocprofv3 --pmc WRITE_SIZE --kernel-trace -d R/gpurun_out/pmc_write -o pmc --output-format csv -- python3 R/bench.py ARGS --copy-calibration", "",
@@ -212,6 +219,12 @@ def main():
                       f"{(pc['fetch_gb'] + pc['write_gb']) / n:.2f} |")
             classes[cls] = dict(launches=n, fetch_gb=pc["fetch_gb"] / n, write_gb=pc["write_gb"] / n,
                                 traffic_gb=(pc["fetch_gb"] + pc["write_gb"]) / n, avg_ms_under_counters=pc["ms"] / n)
+        md += ["", "Launches shorter than 0.3 ms of the timed region, summed per kernel (the factorisation chains' panel and update "
+               "launches carry the units of the pruned rows' pass: its 12 GB in and 24 GB out per iteration show up here):", "",
+               "| kernel | launches | total ms | fetch GB | write GB |", "|---|---|---|---|---|"]
+        for name, sh in sorted(short.items(), key=lambda kv: -(kv[1]["fetch_gb"] + kv[1]["write_gb"])):
+            if sh["fetch_gb"] + sh["write_gb"] >= 0.05:
+                md.append(f"| {name} | {sh['launches']} | {sh['ms']:.2f} | {sh['fetch_gb']:.2f} | {sh['write_gb']:.2f} |")
         md.append("")
         js = dict(workload=args.workload, sources_sha256=sources_hash(), unit="GB per launch (FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
                   command="rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE --kernel-trace -- python3 bench.py " + args.bench_args + " --copy-calibration",
