@@ -1,8 +1,8 @@
 """Turn rocprofv3 output of bench.py runs into the short summaries kept under profiles/.
 
-    python -m paper_2510_03246_amd.profile_summary --workload opt6.7b --launches gpurun_out/launches.json \
-        --stats gpurun_out/prof_bench --fetch gpurun_out/pmc_fetch --write gpurun_out/pmc_write \
-        [--mfma gpurun_out/pmc_mfma] [--clock gpurun_out/pmc_clock] --out profiles
+    python -m paper_2510_03246_amd.profile_summary --workload opt6.7b --launches OUT/launches.json \
+        --stats OUT/prof_bench --fetch OUT/pmc_fetch --write OUT/pmc_write \
+        [--mfma OUT/pmc_mfma] [--clock OUT/pmc_clock] --out profiles
 
 Inputs: the output directories of
     rocprofv3 --kernel-trace --stats -d <stats> -o bench --output-format csv -- python3 bench.py <ARGS>
@@ -180,18 +180,18 @@ def main():
     launches = json.load(open(args.launches))["launches"]
     os.makedirs(args.out, exist_ok=True)
     md = [f"# bench.py, {args.workload}-shaped FFN module: kernel statistics, HBM traffic and matrix-core counters per launch", "",
-          "Every run below is started on the MI355X box from /tmp with TMPDIR=/tmp; `R` = the repository's root, "
-          "`ARGS` = `" + args.bench_args + "`; the first run also carries `--dump-launches R/gpurun_out/launches.json` "
+          "Every run below is started on the MI355X box from /tmp with TMPDIR=/tmp; `R` = the repository's root, `OUT` = a scratch directory, "
+          "`ARGS` = `" + args.bench_args + "`; the first run also carries `--dump-launches OUT/launches.json` "
           "(the library's own launch records, which name the class of every GEMM launch).",
           "This file and `traffic_" + args.workload + ".json` are then written from the runs' CSV output by", "",
-          "    python3 -m paper_2510_03246_amd.profile_summary --workload " + args.workload + " --launches gpurun_out/launches.json "
-          "--stats gpurun_out/prof_bench --fetch gpurun_out/pmc_fetch --write gpurun_out/pmc_write --mfma gpurun_out/pmc_mfma "
-          "--clock gpurun_out/pmc_clock --out profiles", "",
+          "    python3 -m paper_2510_03246_amd.profile_summary --workload " + args.workload + " --launches OUT/launches.json "
+          "--stats OUT/prof_bench --fetch OUT/pmc_fetch --write OUT/pmc_write --mfma OUT/pmc_mfma "
+          "--clock OUT/pmc_clock --out profiles", "",
           f"Kernel sources: sha256 {sources_hash()[:16]} (over csrc/*.hip, *.h of libstrp.so).", ""]
     if args.stats:
         files = glob.glob(os.path.join(args.stats, "**", "*kernel_stats.csv"), recursive=True)
         md += ["## Kernel statistics", "",
-               "    rocprofv3 --kernel-trace --stats -d R/gpurun_out/prof_bench -o bench --output-format csv -- python3 R/bench.py ARGS", "",
+               "    rocprofv3 --kernel-trace --stats -d OUT/prof_bench -o bench --output-format csv -- python3 R/bench.py ARGS", "",
                "Library kernels only (torch's input-generation kernels omitted); module initialisation, warm-up and the timed iterations.", "",
                "| kernel | calls | total ms | avg ms | min ms | max ms | % |", "|---|---|---|---|---|---|---|"]
         with open(files[0], newline="") as f:
@@ -205,8 +205,8 @@ def main():
     if args.fetch and args.write:
         rows, per_class, cal_note, scales, short = traffic_tables(args.fetch, args.write, launches)
         md += ["## HBM-side traffic per launch", "",
-               "    rocprofv3 --pmc FETCH_SIZE --kernel-trace -d R/gpurun_out/pmc_fetch -o pmc --output-format csv -- python3 R/bench.py ARGS --copy-calibration",
-               "    rocprofv3 --pmc WRITE_SIZE --kernel-trace -d R/gpurun_out/pmc_write -o pmc --output-format csv -- python3 R/bench.py ARGS --copy-calibration", "",
+               "    rocprofv3 --pmc FETCH_SIZE --kernel-trace -d OUT/pmc_fetch -o pmc --output-format csv -- python3 R/bench.py ARGS --copy-calibration",
+               "    rocprofv3 --pmc WRITE_SIZE --kernel-trace -d OUT/pmc_write -o pmc --output-format csv -- python3 R/bench.py ARGS --copy-calibration", "",
                cal_note, "Launches of 0.3 ms and more in dispatch order; `class` is the library's record of that launch.", "",
                "| kernel | class | workgroups | ms | fetch GB | write GB |", "|---|---|---|---|---|---|"]
         md += [f"| {n} | {c} | {wg} | {ms:.2f} | {fg:.2f} | {wgb:.2f} |" for n, c, wg, ms, fg, wgb in rows]
@@ -235,9 +235,9 @@ def main():
     if args.mfma:
         rows = mfma_table(args.mfma, args.clock, launches)
         md += ["## Matrix-core counters per GEMM launch of the timed region", "",
-               "    rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_WAIT_INST_ANY --kernel-trace -d R/gpurun_out/pmc_mfma -o pmc --output-format csv -- python3 R/bench.py ARGS"]
+               "    rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_WAIT_INST_ANY --kernel-trace -d OUT/pmc_mfma -o pmc --output-format csv -- python3 R/bench.py ARGS"]
         if args.clock:
-            md.append("    rocprofv3 --pmc GRBM_GUI_ACTIVE --kernel-trace -d R/gpurun_out/pmc_clock -o pmc --output-format csv -- python3 R/bench.py ARGS")
+            md.append("    rocprofv3 --pmc GRBM_GUI_ACTIVE --kernel-trace -d OUT/pmc_clock -o pmc --output-format csv -- python3 R/bench.py ARGS")
         md += ["", "`MFMA busy` = (SQ_VALU_MFMA_BUSY_CYCLES / 1024 SIMDs) / (SQ_BUSY_CYCLES / 32 shader engines): the share of the kernel's cycles "
                "in which a SIMD's matrix core executes, averaged over the SIMDs; "
                "`waiting` = SQ_WAIT_INST_ANY / SQ_WAVE_CYCLES (share of the wavefront cycles spent waiting on any instruction); "
