@@ -20,8 +20,7 @@ namespace strp {
 
 namespace dma {
 constexpr int ROWS = 256;          // rows of P / columns of Q per block
-constexpr int SK = 16;             // contraction steps per stage (two k-groups)
-constexpr int PLANE_STAGE_BYTES = 2 * ROWS * 16;   // one plane of one operand in one stage: 8 KB
+constexpr int PLANE_STAGE_BYTES = 2 * ROWS * 16;   // one plane of one operand in one stage (16 contraction steps = two k-groups): 8 KB
 }  // namespace dma
 
 // m0 is written here, so it is named as clobbered; the compiler treats m0 as a reserved register (it never keeps a
