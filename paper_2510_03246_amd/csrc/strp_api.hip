@@ -631,12 +631,38 @@ static int plan_splits(int ntiles, long long K) {
   return (int)s;
 }
 
+// Tiles and K splits of a token-contraction product.  A grid of no more than two rounds of workgroups is a matter of
+// how well its last round fills the chip: from the split count of plan_splits upwards (at most a quarter more: shorter
+// chains, never longer ones) the one with the least rounds x chain length is taken (17 % on the Gram of a d = 768
+// module).  Larger grids are left alone: measured, their run time does not follow the round count (workgroups do not run
+// in lockstep, and more splits cost more prologues and partial sums).
+static void plan_nt_product(GemmP& p) {
+  gemm_plan_tiles(p, 1);
+  const int s0 = plan_splits(p.ntiles, p.K);
+  gemm_plan_tiles(p, s0);
+  const long long slots0 = p.wt == 4 ? 256 : 512;   // workgroups the chip runs at a time (one or two per CU)
+  if (s0 <= 1 || (long long)p.ntiles * p.splits > 2 * slots0) return;
+  double best_cost = 0.0;
+  int best = s0;
+  for (int s = s0; s <= s0 + s0 / 4; ++s) {
+    GemmP q = p;
+    gemm_plan_tiles(q, s);
+    const long long slots = q.wt == 4 ? 256 : 512;
+    const long long blocks = (long long)q.ntiles * q.splits;
+    const double cost = (double)((blocks + slots - 1) / slots) * (double)q.kchunk;
+    if (s == s0 || cost < best_cost * 0.995) {
+      best_cost = cost;
+      best = s;
+    }
+  }
+  gemm_plan_tiles(p, best);
+}
+
 static size_t nt_partial_elems(int M, int N, long long K, int triangle) {
   GemmP p;
   memset(&p, 0, sizeof(p));
   p.M = M; p.N = N; p.K = K; p.triangle = triangle;
-  gemm_plan_tiles(p, 1);
-  gemm_plan_tiles(p, plan_splits(p.ntiles, K));
+  plan_nt_product(p);
   return (size_t)p.splits * (size_t)M * (size_t)N;
 }
 
@@ -647,8 +673,7 @@ static strp_status nt_product(strp_ctx* ctx, Arena arena, const PlaneOp& P, cons
   memset(&p, 0, sizeof(p));
   p.P = P; p.Q = Q; p.M = M; p.N = N; p.K = K; p.triangle = triangle;
   p.epi = EPI_PARTIAL;
-  gemm_plan_tiles(p, 1);
-  gemm_plan_tiles(p, plan_splits(p.ntiles, K));
+  plan_nt_product(p);
   STRP_TAKE(ctx, arena, part, float, (size_t)p.splits * M * N);
   p.out = part;
   STRP_TRY(launch_gemm(ctx, p));
