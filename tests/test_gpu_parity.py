@@ -8,7 +8,7 @@ import pytest
 import torch
 
 from oracle import strp_oracle as orc
-from paper_2510_03246_amd import inputs, strp
+from paper_2510_03246_amd import driver, inputs, strp
 
 pytestmark = pytest.mark.gpu
 
@@ -378,36 +378,22 @@ def test_model_driver_temperature_sweep(ctx):
         mods_in.append(m)
     ref, best_ref = orc.prune_model([tuple(m[n].double().cpu().numpy() for n in ("W1hat", "W2hat", "X")) for m in mods_in],
                                     rbar, temps, K)
-    totals = {}
-    n_units = torch.full((L,), cfg.f, dtype=torch.int32, device="cuda")
+    res, best = driver.prune_model(ctx, mods_in, cfg.T, rbar, temps, K, alpha=1.0, beta=1.0, delta=0.01, mode=strp.WANDA,
+                                   reselect=0, keep_weights=True)
     for temp in temps:
-        mods = []
-        energies = torch.zeros(L, dtype=torch.float64, device="cuda")
-        r_out = torch.empty(L, dtype=torch.float64, device="cuda")
-        npr = torch.empty(L, dtype=torch.int32, device="cuda")
-        for layer, m in enumerate(mods_in):
-            mod = strp.FFNModule(ctx, m["W1hat"], m["W2hat"], m["X"], cfg.T)
-            mod.init(_params(1))
-            last = layer == L - 1
-            ctx.strp_score_alloc(mod.A, cfg.T, strp.WANDA, mod.score, energies, layer, L, n2=mod.n2,
-                                 **(dict(n_units=n_units, rbar=rbar, temperature=temp, rmax=0.95, r_out=r_out, nprune_out=npr)
-                                    if last else {}))
-            mods.append(mod)
-        assert ctx.poll() == strp.OK
-        assert np.allclose(energies.cpu().numpy(), ref[temp]["energies"], rtol=1e-6)
-        assert np.allclose(r_out.cpu().numpy(), ref[temp]["r"], rtol=1e-6)
-        assert np.array_equal(npr.cpu().numpy().astype(np.int64), ref[temp]["nprune"])
-        losses = []
-        for layer, mod in enumerate(mods):
-            k = cfg.f - int(npr[layer].item())
-            p = _params(k)
-            for it in range(K):
-                rep = mod.step(p)
-            assert rep.status == strp.OK
-            losses.append(rep.J_ridge)
-        assert np.allclose(losses, ref[temp]["losses"], rtol=TOL_J)
-        totals[temp] = float(np.sum(losses))
-    assert min(totals, key=totals.get) == best_ref
+        assert np.allclose(res[temp].energies, ref[temp]["energies"], rtol=1e-6)
+        assert np.allclose(res[temp].r, ref[temp]["r"], rtol=1e-6)
+        assert np.array_equal(np.array(res[temp].nprune, dtype=np.int64), ref[temp]["nprune"])
+        assert np.allclose(res[temp].losses, ref[temp]["losses"], rtol=TOL_J)
+        assert np.isclose(res[temp].total, ref[temp]["total"], rtol=TOL_J)
+    assert best == best_ref
+    # the pruned modules of the best temperature are handed back: masks of the allocated widths, weights zero outside
+    assert all(not res[t].pruned for t in temps if t != best) and len(res[best].pruned) == L
+    for layer, (mask, W1, W2) in enumerate(res[best].pruned):
+        st = ref[best]["states"][layer]
+        assert np.array_equal(mask.cpu().numpy(), st.mask)
+        assert int(mask.sum().item()) == cfg.f - res[best].nprune[layer]
+        assert rel_fro(W1.cpu().numpy(), st.W1) < TOL_F and rel_fro(W2.cpu().numpy(), st.W2) < TOL_F
 
 
 @pytest.mark.parametrize("mode", [strp.WANDA, strp.GAIN])
