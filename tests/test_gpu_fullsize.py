@@ -313,6 +313,32 @@ def test_head_variant_at_full_width(run):
     assert not bool(W[:, off].any())
 
 
+def test_gain_iteration_keeps_every_rows_sums(run):
+    """One full GAIN iteration with re-selection at full size (the pruned rows' pass reads Z0 as well and rides with the
+    factorisation chains, the kept rows' sums come from the a/z epilogues): afterwards a selection from the cached sums
+    gives the scores and the mask of a selection that streams every row of A, Z and Z0 again.  Moves the state."""
+    mod, k = run["mod"], run["k"]
+    rep = mod.step(strp.Params(ALPHA, BETA, DELTA, strp.GAIN, 1, k, 0))
+    assert rep.status == strp.OK
+    assert mod.state.sums_cached == 7
+    sel = strp.Params(ALPHA, BETA, DELTA, strp.GAIN, 1, k, strp.STAGE_SELECT)
+    mod.ctx.profile_enable(True)
+    mod.step(sel)
+    assert not any(n.startswith("row_sums") for n in mod.ctx.profile_read())
+    mod.ctx.profile_enable(False)
+    score_cached, mask_cached = mod.score.clone(), mod.mask.clone()
+    mod.state.sums_cached = 0
+    mod.step(sel)
+    assert mod.ctx.poll() == strp.OK
+    # 2P - Q is a difference of sums: agreement is relative to the largest score
+    scale = float(mod.score.abs().max().item())
+    assert float((score_cached - mod.score).abs().max().item()) <= 2e-6 * scale
+    # the two masks may differ only in units whose score lies within that agreement of the threshold
+    tau = float(torch.sort(mod.score, descending=True).values[k - 1].item())
+    differ = (mask_cached != mod.mask).nonzero().flatten().cpu().numpy()
+    assert all(abs(float(mod.score[j].item()) - tau) <= 4e-6 * scale for j in differ), differ
+
+
 def test_objective_does_not_rise_on_a_fixed_mask(run):
     """Block-coordinate descent on the augmented objective (Appendix A.1: every update is the exact minimiser of its
     block): with the mask held, three more iterations at full size never raise J + ridge terms, and the pruned rows'
@@ -320,7 +346,7 @@ def test_objective_does_not_rise_on_a_fixed_mask(run):
     Runs last in this module: it moves the state."""
     mod, k = run["mod"], run["k"]
     p = strp.Params(ALPHA, BETA, DELTA, strp.WANDA, 0, k, 0)
-    prev = run["rep"].J_ridge
+    prev = mod.step(p).J_ridge            # the mask is whatever the tests before left; it stays from here on
     mod.ctx.profile_enable(True)
     for it in range(3):
         rep = mod.step(p)
