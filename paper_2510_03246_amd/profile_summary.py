@@ -247,6 +247,20 @@ def main():
             ghz = f"{r['ghz']:.2f}" if "ghz" in r else "-"
             md.append(f"| {r['cls']} | {r['wg']} | {r['ms']:.2f} | {r['mfma_busy']:.3f} | {r['wait_any']:.3f} | {ghz} |")
         md.append("")
+        if args.clock:
+            # the same clock figure for every library kernel: the chip holds 2.2-2.4 GHz on everything but the fp16 GEMMs
+            agg = collections.defaultdict(lambda: [0.0, 0.0, 0])
+            for d in load_counters(args.clock):
+                if "strp::" in d["name"] and d["ms"] >= 0.2 and "GRBM_GUI_ACTIVE" in d["counters"]:
+                    a = agg[d["name"]]
+                    a[0] += d["counters"]["GRBM_GUI_ACTIVE"] / N_XCD
+                    a[1] += d["ms"] * 1e6
+                    a[2] += 1
+            md += ["Sustained clock per kernel over its launches of 0.2 ms and more (whole run):", "",
+                   "| kernel | launches | clock GHz |", "|---|---|---|"]
+            for name, (cyc, ns, n) in sorted(agg.items(), key=lambda kv: -kv[1][1]):
+                md.append(f"| {name} | {n} | {cyc / ns:.2f} |")
+            md.append("")
     os.makedirs(args.out, exist_ok=True)
     path = os.path.join(args.out, f"bench_{args.workload}_admm_step_kernel_stats.md")
     with open(path, "w") as f:
