@@ -4,6 +4,8 @@ it needs an MI355X and, for part "oracle", minutes of host time.
 
     python tests/precision_table.py oracle  ITERS [short]    # OPT-125m-shaped module, whole, against the oracle
     python tests/precision_table.py self WORKLOAD ITERS [short]   # any workload, against the library's own 3-pass run
+    python tests/precision_table.py device WORKLOAD ITERS [short] # opt1.3b / opt6.7b against the oracle's chunked torch
+                                                                  # form in fp64 on the GPU (its own trajectory)
 
 Both parts select once and then hold the mask (reselect = 0), so that every variant follows the same kept set and the
 figures are errors of the arithmetic, not of a diverged selection.  "short" runs the combined variants only.
@@ -19,6 +21,7 @@ import torch
 
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 from oracle import strp_oracle as orc                      # noqa: E402
+from oracle import strp_oracle_torch as ort                # noqa: E402
 from paper_2510_03246_amd import inputs, strp              # noqa: E402
 
 NAMES = ["GRAM", "RHS2", "RHS1", "RESID", "AUPD", "ZUPD"]
@@ -93,6 +96,37 @@ def against_oracle(iters, variants):
     ctx.close()
 
 
+def against_device_fp64(workload, iters, variants):
+    cfg = inputs.CONFIGS[workload]
+    k = cfg.f - int(round(cfg.rbar * cfg.f))
+    m = inputs.make_ffn_module(cfg, 0, 0, "cuda")
+    t0 = time.time()
+    st = ort.module_init(m["W1hat"], m["W2hat"], m["X"], cfg.T)
+    terms = None
+    for it in range(iters):
+        terms = ort.admm_step(st, k, 1.0, 1.0, select=(it == 0))
+    torch.cuda.synchronize()
+    print(f"fp64 reference on the device: {time.time() - t0:.0f} s", flush=True)
+    ref = {n: getattr(st, n) for n in ("W1", "W2", "Z", "A")}
+    j_ref = float(np.sum(terms))
+    ctx = strp.Context(0)
+    mod = strp.FFNModule(ctx, m["W1hat"], m["W2hat"], m["X"], cfg.T, k_max=k)
+    p = strp.Params(1.0, 1.0, 0.01, strp.WANDA, 0, k, 0)
+    print(f"{workload} against fp64 on the device, {iters} iterations")
+    print(f"{'variant':12s} {'W1':>9s} {'W2':>9s} {'Z':>9s} {'A':>9s} {'J':>9s} maskdiff")
+    for name, setting in variants:
+        if name == "null":
+            continue
+        rep = run(ctx, mod, p, iters, setting)
+        e = {n: rel(getattr(mod, n)[:, :ref[n].shape[1]], ref[n]) for n in ref}
+        md = int((mod.mask.cpu().numpy() != st.mask).sum())
+        print(f"{name:12s} {e['W1']:9.2e} {e['W2']:9.2e} {e['Z']:9.2e} {e['A']:9.2e} {abs(rep.J_ridge - j_ref) / j_ref:9.2e} {md}",
+              flush=True)
+    for prod in range(6):
+        ctx.set_product_planes(prod, 2, 2)
+    ctx.close()
+
+
 def against_itself(workload, iters, variants):
     cfg = inputs.CONFIGS[workload]
     k = cfg.f - int(round(cfg.rbar * cfg.f))
@@ -131,5 +165,7 @@ if __name__ == "__main__":
         against_oracle(int(args[1]), variants)
     elif args[0] == "self":
         against_itself(args[1], int(args[2]), variants)
+    elif args[0] == "device":
+        against_device_fp64(args[1], int(args[2]), variants)
     else:
         sys.exit(__doc__)
