@@ -1,9 +1,10 @@
-"""Free-running iterations at the full size of configs 3 and 4 against fp64 on the device.
+"""Free-running iterations at the full size of configs 3, 4 and 5 against fp64 on the device.
 
 The numpy oracle cannot hold an OPT-6.7B-shaped module; its token-chunked torch form (oracle/strp_oracle_torch.py,
 held to the numpy oracle by tests/test_oracle_torch_pin.py) can, in fp64 on the GPU through the vendor's BLAS.  The
 library and that reference start from the same inputs, select once, and run three iterations without ever seeing each
-other's state: the whole of W1, W2, Z, A and the objective are compared at the end.
+other's state: the whole of W1, W2, Z, A and the objective are compared at the end.  At config 5 the two do not fit the
+device together: the reference runs first and keeps its weights, its objective and 96 sampled rows of Z and A.
 """
 import gc
 
@@ -35,7 +36,7 @@ def rel_rows(a, b, T, step=512):
     return (num / max(den, 1e-300)) ** 0.5
 
 
-@pytest.mark.parametrize("name,need", [("opt1.3b", 120e9), ("opt6.7b", 215e9)])
+@pytest.mark.parametrize("name,need", [("opt1.3b", 120e9), ("opt6.7b", 215e9), ("opt30b", 250e9)])
 def test_three_free_running_iterations_against_fp64_on_the_device(name, need):
     gc.collect()
     torch.cuda.empty_cache()
@@ -51,6 +52,15 @@ def test_three_free_running_iterations_against_fp64_on_the_device(name, need):
     terms = None
     for it in range(ITERS):
         terms = ort.admm_step(st, k, ALPHA, BETA, select=(it == 0))
+    rows = None
+    if name == "opt30b":      # keep a sample of the auxiliaries and release the rest before the library allocates its state
+        rng = np.random.default_rng(11)
+        kept, pruned = np.nonzero(st.mask)[0], np.nonzero(st.mask == 0)[0]
+        rows = torch.from_numpy(np.sort(np.concatenate([rng.choice(kept, 48, replace=False), rng.choice(pruned, 48, replace=False)]))).cuda()
+        st.Z, st.A = st.Z[rows].clone(), st.A[rows].clone()
+        st.Y = None
+        gc.collect()
+        torch.cuda.empty_cache()
     # ---- the library, on its own
     ctx = strp.Context(0)
     try:
@@ -67,8 +77,9 @@ def test_three_free_running_iterations_against_fp64_on_the_device(name, need):
         assert all(abs(st.score[j] - st.tau) <= TIE * abs(st.tau) for j in differ), differ
         assert differ.size == 0, "a tie at the threshold: the two trajectories follow different masks"
         # ---- weights, auxiliaries, objective
+        Zg, Ag = (mod.Z, mod.A) if rows is None else (mod.Z[rows], mod.A[rows])
         err = {"W1": rel_rows(mod.W1, st.W1, cfg.d), "W2": rel_rows(mod.W2, st.W2, cfg.f),
-               "Z": rel_rows(mod.Z, st.Z, T), "A": rel_rows(mod.A, st.A, T)}
+               "Z": rel_rows(Zg, st.Z, T), "A": rel_rows(Ag, st.A, T)}
         print(name, {n: f"{v:.2e}" for n, v in err.items()}, "J", rep.J_ridge, float(terms.sum()))
         assert max(err.values()) < TOL_F, err
         got = np.array(rep.terms[:])
