@@ -196,6 +196,18 @@ strp_status strp_alloc_inverse(strp_ctx* ctx, const double* energies, int32_t L,
                                double* r_out, int32_t* nprune_out);
 
 /*
+ * strp_alloc_softmax -- the softmax sparsity allocation of Lemma 2 / Alg. 1 step 2 on its own, over energies[L]
+ * (device) that earlier strp_score_alloc calls have filled: exactly what strp_score_alloc runs when it is given
+ * n_units (r_l = clip(rbar * L_g * softmax(-I / T)_l, 0, rmax) per softmax group with the energies divided by the
+ * group's mean |I|, the rescale branch when nothing was clipped, largest-remainder integer counts, every layer
+ * keeping at least one unit).  For a driver that scores the modules once and then walks a temperature grid.
+ * All arrays are device arrays of length L.  Errors: STRP_EINVAL.
+ */
+strp_status strp_alloc_softmax(strp_ctx* ctx, const double* energies, int32_t L, const int32_t* n_units,
+                               const int32_t* group_id, double rbar, double temperature, double rmax,
+                               double* r_out, int32_t* nprune_out);
+
+/*
  * strp_mask_topk -- structured mask by score threshold (rule below Lemma 1; Alg. 4 threshold step).
  * Keeps exactly the k highest of the n unit scores; equal scores keep the lower index.
  *   mask[n] uint8 in {0,1};  idx[k*group] int32 ascending kept CHANNEL indices (unit*group + c);

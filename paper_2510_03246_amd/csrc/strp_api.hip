@@ -539,6 +539,16 @@ strp_status strp_alloc_inverse(strp_ctx* ctx, const double* energies, int32_t L,
   return launch_alloc(ctx, energies, L, n_units, group_id, rbar, temperature, rmax, 1, r_out, nprune_out);
 }
 
+strp_status strp_alloc_softmax(strp_ctx* ctx, const double* energies, int32_t L, const int32_t* n_units, const int32_t* group_id,
+                               double rbar, double temperature, double rmax, double* r_out, int32_t* nprune_out) {
+  if (!ctx) return STRP_EINVAL;
+  if (!energies || !n_units || !r_out || !nprune_out) return fail(ctx, STRP_EINVAL, "alloc_softmax: null argument");
+  if (L <= 0) return fail(ctx, STRP_EINVAL, "alloc_softmax: L must be positive");
+  if (!(temperature > 0.0) || !(rbar >= 0.0 && rbar <= 1.0) || !(rmax > 0.0 && rmax <= 1.0))
+    return fail(ctx, STRP_EINVAL, "alloc_softmax: need temperature > 0, 0 <= rbar <= 1, 0 < rmax <= 1");
+  return launch_alloc(ctx, energies, L, n_units, group_id, rbar, temperature, rmax, 0, r_out, nprune_out);
+}
+
 size_t strp_topk_workspace_bytes(int32_t n) { return n > 0 ? topk_scratch_bytes(n) + 512 : 0; }
 
 strp_status strp_mask_topk_static(strp_ctx* ctx, const float* score, int32_t n, int32_t k, uint8_t* mask, int32_t* idx, float* tau) {

@@ -1,10 +1,11 @@
-"""Alg. 1 end to end on one GPU, composed from the library's entry points: per temperature of the grid, the layers'
-energies -> softmax sparsity allocation (Lemma 2, Alg. 1 steps 1-2) -> per-module ADMM with the allocated widths
-(Alg. 3, FFN function) -> summed loss; the best temperature is the argmin of the totals (Alg. 1 step 5).
+"""Alg. 1 end to end on one GPU, composed from the library's entry points: the layers' energies once, then per
+temperature of the grid the softmax sparsity allocation (Lemma 2, Alg. 1 steps 1-2) -> per-module ADMM with the
+allocated widths (Alg. 3, FFN function) -> summed loss; the best temperature is the argmin of the totals (Alg. 1 step 5).
 
 Orchestration only: every number is produced by libstrp.so.  One module state is resident; the modules' inputs are
-re-bound to it one after another (device tensors, or host modules handed over through stream.ModuleStreamer), so the
-device memory is that of one module whatever the depth of the model.
+re-bound to it one after another, so the device memory is that of one module whatever the depth of the model.  The
+modules are either dicts of device tensors, or dicts of PINNED HOST tensors (stream.pin), which travel to the device
+through stream.ModuleStreamer (two staging sets, copies on a side stream beside the previous module's iterations).
 """
 from __future__ import annotations
 
@@ -12,7 +13,7 @@ from dataclasses import dataclass, field
 
 import torch
 
-from . import strp
+from . import stream, strp
 
 
 @dataclass
@@ -26,53 +27,56 @@ class TemperatureResult:
     pruned: list = field(default_factory=list)   # per module (mask, W1, W2) clones, kept for the best temperature only
 
 
+def _walk(modules, device):
+    """Yield (layer, dict of device tensors) in layer order."""
+    if modules[0]["X"].is_cuda:
+        yield from enumerate(modules)
+    else:
+        yield from stream.ModuleStreamer(modules, device=device)
+
+
 def prune_model(ctx: strp.Context, modules, T: int, rbar: float, temperatures, iters: int, alpha: float = 1.0,
                 beta: float = 1.0, delta: float = 0.01, mode: int = strp.WANDA, reselect: int = 0, rmax: float = 0.95,
-                keep_weights: bool = False):
-    """modules: sequence of dicts with device tensors "W1hat" [f x d], "W2hat" [d x f], "X" [d x ld] of equal shapes
-    (or any iterable that yields such dicts each time it is iterated, e.g. a list of stream.ModuleStreamer items
-    materialised by the caller).  Returns ({temperature: TemperatureResult}, best_temperature)."""
+                keep_weights: bool = False, on_module=None):
+    """modules: list of dicts with "W1hat" [f x d], "W2hat" [d x f], "X" [d x ld] of equal shapes, all on the device or
+    all in pinned host memory.  on_module(temperature, layer, module, report), if given, is called after a module's last
+    iteration while its state is still resident (to copy out what the caller wants to keep).
+    Returns ({temperature: TemperatureResult}, best_temperature)."""
     modules = list(modules)
     L = len(modules)
     assert L > 0
-    m0 = modules[0]
-    f = m0["W1hat"].shape[0]
-    dev = m0["X"].device
-    mod = strp.FFNModule(ctx, m0["W1hat"], m0["W2hat"], m0["X"], T)
+    f = modules[0]["W1hat"].shape[0]
+    dev = ctx.device
+    mod = None
     n_units = torch.full((L,), f, dtype=torch.int32, device=dev)
     energies = torch.zeros(L, dtype=torch.float64, device=dev)
-    r_out = torch.empty(L, dtype=torch.float64, device=dev)
-    npr = torch.empty(L, dtype=torch.int32, device=dev)
     p_init = strp.Params(alpha, beta, delta, mode, reselect, 1, 0)
     full = mode != strp.WANDA
 
-    def score(layer, **alloc):
-        m = modules[layer]
-        mod.rebind_inputs(m["W1hat"], m["W2hat"], m["X"])
+    # ---- the energies do not depend on the temperature: every module is initialised and scored once
+    for layer, m in _walk(modules, dev):
+        if mod is None:
+            mod = strp.FFNModule(ctx, m["W1hat"], m["W2hat"], m["X"], T)
+        else:
+            mod.rebind_inputs(m["W1hat"], m["W2hat"], m["X"])
         mod.init(p_init)
         ctx.strp_score_alloc(mod.A, T, mode, mod.score, energies, layer, L, n2=mod.n2, Z=mod.Z if full else None,
-                             Z0=mod.Z0 if full else None, **alloc)
-
-    # the energies do not depend on the temperature: every layer is scored once, the last one again per temperature
-    # because the allocation runs inside a scoring call
-    for layer in range(L - 1):
-        score(layer)
+                             Z0=mod.Z0 if full else None)
+    status = ctx.poll()
+    if status != strp.OK:
+        raise strp.StrpError(status, "scoring failed")
+    e_h = energies.cpu().tolist()
     results = {}
     best = None
     for temp in temperatures:
-        score(L - 1, n_units=n_units, rbar=rbar, temperature=float(temp), rmax=rmax, r_out=r_out, nprune_out=npr)
-        status = ctx.poll()
-        if status != strp.OK:
-            raise strp.StrpError(status, "allocation failed")
-        e_h, r_h, npr_h = energies.cpu().tolist(), r_out.cpu().tolist(), [int(v) for v in npr.cpu().tolist()]
+        r_out, npr = ctx.strp_alloc_softmax(energies, n_units, rbar, float(temp), rmax)
+        r_h, npr_h = r_out.cpu().tolist(), [int(v) for v in npr.cpu().tolist()]
         losses, kept = [None] * L, [None] * L
-        for layer in [L - 1] + list(range(L - 1)):   # the last module is resident and initialised: it goes first
+        for layer, m in _walk(modules, dev):
             k = f - npr_h[layer]
             p = strp.Params(alpha, beta, delta, mode, reselect, k, 0)
-            if layer != L - 1:
-                m = modules[layer]
-                mod.rebind_inputs(m["W1hat"], m["W2hat"], m["X"])
-                mod.init(p)
+            mod.rebind_inputs(m["W1hat"], m["W2hat"], m["X"])
+            mod.init(p)
             rep = None
             for it in range(iters):
                 rep = mod.step(p)
@@ -81,6 +85,8 @@ def prune_model(ctx: strp.Context, modules, T: int, rbar: float, temperatures, i
             losses[layer] = rep.J_ridge
             if keep_weights:
                 kept[layer] = (mod.mask.clone(), mod.W1.clone(), mod.W2.clone())
+            if on_module is not None:
+                on_module(temp, layer, mod, rep)
         res = TemperatureResult(float(temp), e_h, r_h, npr_h, losses, float(sum(losses)))
         results[temp] = res
         if best is None or res.total < results[best].total:

@@ -25,7 +25,7 @@ STAGE_ALL = 63
 
 EXPORTS = [
     "strp_create", "strp_destroy", "strp_last_error", "strp_set_precision", "strp_set_product_planes", "strp_set_workspace",
-    "strp_poll", "strp_workspace_bytes", "strp_module_cache_bytes", "strp_profile_enable", "strp_profile_read", "strp_profile_launches", "strp_gram", "strp_score_alloc", "strp_mask_topk", "strp_mask_topk_static", "strp_topk_workspace_bytes", "strp_weight_energy", "strp_alloc_inverse",
+    "strp_poll", "strp_workspace_bytes", "strp_module_cache_bytes", "strp_profile_enable", "strp_profile_read", "strp_profile_launches", "strp_gram", "strp_score_alloc", "strp_mask_topk", "strp_mask_topk_static", "strp_topk_workspace_bytes", "strp_weight_energy", "strp_alloc_inverse", "strp_alloc_softmax",
     "strp_refit", "strp_module_init", "strp_admm_step",
 ]
 
@@ -107,6 +107,7 @@ def load_library():
     lib.strp_topk_workspace_bytes.argtypes = [C.c_int32]
     lib.strp_weight_energy.argtypes = [vp, C.POINTER(WeightRef), i32, C.c_double, C.c_double, C.c_double, vp]
     lib.strp_alloc_inverse.argtypes = [vp, vp, i32, vp, vp, C.c_double, C.c_double, C.c_double, vp, vp]
+    lib.strp_alloc_softmax.argtypes = [vp, vp, i32, vp, vp, C.c_double, C.c_double, C.c_double, vp, vp]
     lib.strp_gram.argtypes = [vp, vp, C.c_int, i32, i64, i64, vp, i32, vp, i32, vp, C.c_int]
     lib.strp_score_alloc.argtypes = [vp, C.POINTER(ScoreIn), vp, vp, i32, i32, vp, vp, dbl, dbl, dbl, vp, vp]
     lib.strp_mask_topk.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
@@ -260,6 +261,14 @@ class Context:
         r = torch.empty(L, dtype=torch.float64, device=energies.device)
         npr = torch.empty(L, dtype=torch.int32, device=energies.device)
         self.check(self.lib.strp_alloc_inverse(self.h, _ptr(energies), L, _ptr(n_units), _ptr(group_id), float(rbar),
+                                               float(temperature), float(rmax), _ptr(r), _ptr(npr)))
+        return r, npr
+
+    def strp_alloc_softmax(self, energies, n_units, rbar, temperature, rmax=0.95, group_id=None):
+        L = energies.numel()
+        r = torch.empty(L, dtype=torch.float64, device=energies.device)
+        npr = torch.empty(L, dtype=torch.int32, device=energies.device)
+        self.check(self.lib.strp_alloc_softmax(self.h, _ptr(energies), L, _ptr(n_units), _ptr(group_id), float(rbar),
                                                float(temperature), float(rmax), _ptr(r), _ptr(npr)))
         return r, npr
 

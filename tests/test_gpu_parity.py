@@ -8,7 +8,7 @@ import pytest
 import torch
 
 from oracle import strp_oracle as orc
-from paper_2510_03246_amd import driver, inputs, strp
+from paper_2510_03246_amd import driver, inputs, stream, strp
 
 pytestmark = pytest.mark.gpu
 
@@ -208,6 +208,13 @@ def test_allocation_parity(ctx, temperature, rbar):
     r_ref, n_ref = orc.softmax_allocation(I, n_units, rbar, temperature, 0.95, gid)
     assert np.allclose(r_out.cpu().numpy(), r_ref, rtol=1e-12, atol=1e-15)
     assert np.array_equal(npr.cpu().numpy(), n_ref)
+    # the allocation on its own, over the energies the scoring calls left
+    r2, npr2 = ctx.strp_alloc_softmax(energies, torch.from_numpy(n_units).cuda(), rbar, temperature, 0.95,
+                                      group_id=torch.from_numpy(gid).cuda())
+    assert torch.equal(r2, r_out) and torch.equal(npr2, npr)
+    with pytest.raises(strp.StrpError) as e:
+        ctx.strp_alloc_softmax(energies, torch.from_numpy(n_units).cuda(), rbar, 0.0)
+    assert e.value.status == strp.EINVAL
 
 
 def test_weight_only_importance_and_inverse_allocation(ctx):
@@ -365,7 +372,8 @@ def test_free_running_config1(ctx):
         assert max(err.values()) < TOL_F, err
 
 
-def test_model_driver_temperature_sweep(ctx):
+@pytest.mark.parametrize("streamed", [False, True])
+def test_model_driver_temperature_sweep(ctx, streamed):
     """Alg. 1 end to end on three small modules: energies -> softmax allocation -> per-module ADMM -> summed loss,
     for each temperature of the grid; the best temperature is the argmin of the totals."""
     cfg = inputs.CONFIGS["tiny"]
@@ -378,6 +386,8 @@ def test_model_driver_temperature_sweep(ctx):
         mods_in.append(m)
     ref, best_ref = orc.prune_model([tuple(m[n].double().cpu().numpy() for n in ("W1hat", "W2hat", "X")) for m in mods_in],
                                     rbar, temps, K)
+    if streamed:     # the same modules from pinned host memory, through the double-buffered streamer
+        mods_in = [stream.pin(m) for m in mods_in]
     res, best = driver.prune_model(ctx, mods_in, cfg.T, rbar, temps, K, alpha=1.0, beta=1.0, delta=0.01, mode=strp.WANDA,
                                    reselect=0, keep_weights=True)
     for temp in temps:
